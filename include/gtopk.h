@@ -1,0 +1,136 @@
+/*
+ * gtopk.h - C ABI of the gTop-k S-SGD data-parallel hot path for MI355X (gfx950).
+ *
+ * The library computes, for P simulated workers whose gradient buffers all
+ * live on one GPU, the three parts of one gTop-k S-SGD iteration
+ * (paper: Algorithm 4, "gTopKAllReduce based S-SGD"):
+ *
+ *   1. local selection        Algorithm 4 lines 4-8
+ *   2. gTopKAllReduce         Algorithm 3 lines 1-18, built from the Top-k
+ *                             operation of Definition 1, then the average of Eq. 3
+ *   3. extra residual         Algorithm 3 lines 19-23 (broadcast and gMask, which
+ *                             on one GPU reduce to "all workers read one global
+ *                             index set") and Algorithm 4 line 10
+ *
+ * Conventions, for every entry point:
+ *   - Every pointer argument is a DEVICE pointer owned by the caller.  The
+ *     library never allocates, frees or keeps device memory; temporary storage
+ *     comes from the caller's workspace `ws` (size from the *_workspace_bytes
+ *     query; contents need no initialisation and are clobbered).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     A call only enqueues kernels on `stream` and returns; it never
+ *     synchronises with the host.  Two calls that share a workspace must be
+ *     ordered (same stream, or an event between them).
+ *   - Values are IEEE-754 binary32 ("All models are trained with 32-bit floating
+ *     points", note under Table III).  Every add is one round-to-nearest fp32
+ *     add; denormals are not flushed.  Magnitude |v| is compared on the integer
+ *     `bits(v) & 0x7fffffff`.  "Top k" means: the first k entries under the
+ *     total order (|v| descending, index ascending) - exactly k entries, the
+ *     lower index winning among equal magnitudes.
+ *   - A sparse k-set is two arrays, indices (uint32, ascending, distinct) and
+ *     values (float), k entries each.
+ *   - Return value: GTOPK_OK (0) when the work was enqueued, a negative
+ *     gtopk_status otherwise; on an argument error nothing is enqueued.
+ *     Argument errors are found on the host, without touching the GPU.
+ *   - Not checked (results unspecified, but no out-of-bounds access inside the
+ *     given sizes): NaN/Inf inputs; unsorted, duplicate or >= 2^32-1 indices in
+ *     caller-provided k-sets; buffers that overlap each other.
+ */
+#ifndef GTOPK_H_
+#define GTOPK_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    GTOPK_OK = 0,
+    GTOPK_EINVAL = -1,     /* null pointer; m < 1 or m > 2^31; k < 1 or k > m; P < 1 or not a
+                              power of two (the paper assumes a power of two, Section III);
+                              stride < m; batch < 1; k-set stride < k                        */
+    GTOPK_EWORKSPACE = -2, /* ws_bytes smaller than the matching *_workspace_bytes query   */
+    GTOPK_EALIGN = -3,     /* a pointer is not 16-byte aligned                              */
+    GTOPK_EHIP = -4        /* a kernel launch failed (hipGetLastError)                      */
+} gtopk_status;
+
+/* Human-readable name of a status code (static string, never NULL). */
+const char* gtopk_status_string(int status);
+
+/* Bytes of workspace that gtopk_local_select, gtopk_tree, gtopk_residual_restore
+ * and gtopk_step need for these sizes.  Returns 0 if the sizes are invalid. */
+size_t gtopk_workspace_bytes(int64_t m, int32_t k, int32_t P);
+
+/* Bytes of workspace gtopk_merge needs for `batch` pairs of k-sets (0 if invalid). */
+size_t gtopk_merge_workspace_bytes(int32_t k, int32_t batch);
+
+/*
+ * Local selection, Algorithm 4 lines 4-8, for P workers at once.
+ *
+ *   grad      [P rows] in : fresh gradients; row w starts at grad + w*stride, m floats
+ *   residual  [P rows] i/o: G_{i-1} on entry.  On return row w holds
+ *                           acc = residual + grad (line 4) with the k selected
+ *                           entries replaced by +0.0 (line 8)
+ *   m, stride             : elements per worker and distance between rows (>= m)
+ *   out_idx   [P][k] out  : indices of the k selected entries of each worker, ascending
+ *   out_val   [P][k] out  : acc at those indices, bit for bit (line 7)
+ */
+int gtopk_local_select(const float* grad, float* residual, int64_t m, int64_t stride,
+                       int32_t P, int32_t k, uint32_t* out_idx, float* out_val,
+                       void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * The Top-k operation of Definition 1 on `batch` independent pairs of k-sets:
+ * out[b] = a[b] TOP b[b].  The candidates are the union of the two index sets;
+ * at an index held by both operands the two values are added (one fp32 add), at
+ * an index held by one its value is kept unchanged; the top k of the union are
+ * written index-ascending.  Always exactly k entries.
+ *
+ *   a_idx/a_val, b_idx/b_val : set b of each operand starts at + b*in_stride (elements)
+ *   out_idx/out_val          : result b starts at + b*out_stride
+ *   in_stride, out_stride    : >= k
+ */
+int gtopk_merge(const uint32_t* a_idx, const float* a_val,
+                const uint32_t* b_idx, const float* b_val,
+                int32_t k, int32_t batch, int64_t in_stride,
+                uint32_t* out_idx, float* out_val, int64_t out_stride,
+                void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * gTopKAllReduce, Algorithm 3 lines 1-18, over the P workers' k-sets, followed
+ * by the division by P of Eq. 3.  Round j (j = 0 .. log2 P - 1) merges worker i
+ * with worker i + 2^j for every i that is a multiple of 2^(j+1); the result of
+ * the last round is what rank 0 would broadcast (line 19).
+ *
+ *   loc_idx, loc_val [P][k] in : the workers' local k-sets (not modified)
+ *   g_idx, g_val     [k]   out : the global k-set; values are the tree's sums / P
+ */
+int gtopk_tree(const uint32_t* loc_idx, const float* loc_val, int32_t P, int32_t k,
+               uint32_t* g_idx, float* g_val, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Extra residual, Algorithm 4 line 10, for P workers at once: every locally
+ * selected entry whose INDEX is not in the global set (gMask, Algorithm 3 lines
+ * 21-22) is added back: residual[w][loc_idx[w][t]] += loc_val[w][t].
+ * Needs no workspace.
+ */
+int gtopk_residual_restore(float* residual, int64_t m, int64_t stride, int32_t P, int32_t k,
+                           const uint32_t* loc_idx, const float* loc_val,
+                           const uint32_t* g_idx, void* stream);
+
+/*
+ * One whole iteration of the hot path: gtopk_local_select, gtopk_tree and
+ * gtopk_residual_restore in sequence, with bit-identical results.
+ * loc_idx / loc_val may be NULL (then the local k-sets stay in the workspace).
+ */
+int gtopk_step(const float* grad, float* residual, int64_t m, int64_t stride,
+               int32_t P, int32_t k, uint32_t* g_idx, float* g_val,
+               uint32_t* loc_idx, float* loc_val,
+               void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GTOPK_H_ */

@@ -1,0 +1,196 @@
+"""Thin ctypes binding over libgtopk.so (argument marshalling only).
+
+Every function has the name and argument order of its C entry point in
+include/gtopk.h, takes torch CUDA(ROCm) tensors where the C side takes device
+pointers, checks dtypes/devices/contiguity, passes raw pointers and the current
+stream, and raises `GtopkError` on a non-zero status.  No step of the method
+runs in Python and there is no fallback: if the library is missing, loading
+raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libgtopk.so")
+_lib: Optional[ctypes.CDLL] = None
+
+EXPORTS = (
+    "gtopk_status_string", "gtopk_workspace_bytes", "gtopk_merge_workspace_bytes",
+    "gtopk_local_select", "gtopk_merge", "gtopk_tree", "gtopk_residual_restore", "gtopk_step",
+)
+
+GTOPK_OK, GTOPK_EINVAL, GTOPK_EWORKSPACE, GTOPK_EALIGN, GTOPK_EHIP = 0, -1, -2, -3, -4
+
+
+class GtopkError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load() -> ctypes.CDLL:
+    """Load libgtopk.so (built by `python -m paper_1901_04359_amd.build`)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_1901_04359_amd.build` "
+            "(there is no CPU fallback)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    c = ctypes
+    vp, i32, i64, sz = c.c_void_p, c.c_int32, c.c_int64, c.c_size_t
+    lib.gtopk_status_string.restype = c.c_char_p
+    lib.gtopk_status_string.argtypes = [c.c_int]
+    lib.gtopk_workspace_bytes.restype = sz
+    lib.gtopk_workspace_bytes.argtypes = [i64, i32, i32]
+    lib.gtopk_merge_workspace_bytes.restype = sz
+    lib.gtopk_merge_workspace_bytes.argtypes = [i32, i32]
+    lib.gtopk_local_select.restype = c.c_int
+    lib.gtopk_local_select.argtypes = [vp, vp, i64, i64, i32, i32, vp, vp, vp, sz, vp]
+    lib.gtopk_merge.restype = c.c_int
+    lib.gtopk_merge.argtypes = [vp, vp, vp, vp, i32, i32, i64, vp, vp, i64, vp, sz, vp]
+    lib.gtopk_tree.restype = c.c_int
+    lib.gtopk_tree.argtypes = [vp, vp, i32, i32, vp, vp, vp, sz, vp]
+    lib.gtopk_residual_restore.restype = c.c_int
+    lib.gtopk_residual_restore.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp]
+    lib.gtopk_step.restype = c.c_int
+    lib.gtopk_step.argtypes = [vp, vp, i64, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load().gtopk_status_string(int(status)).decode()
+
+
+def gtopk_workspace_bytes(m: int, k: int, P: int) -> int:
+    return int(load().gtopk_workspace_bytes(m, k, P))
+
+
+def gtopk_merge_workspace_bytes(k: int, batch: int) -> int:
+    return int(load().gtopk_merge_workspace_bytes(k, batch))
+
+
+# -- marshalling helpers ------------------------------------------------------
+
+def _torch():
+    import torch
+    return torch
+
+
+def _ptr(t, dtype, name: str, allow_none: bool = False):
+    if t is None:
+        if allow_none:
+            return None
+        raise TypeError(f"{name} is None")
+    torch = _torch()
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a GPU tensor")
+    if t.dtype != dtype:
+        raise TypeError(f"{name} must have dtype {dtype}, got {t.dtype}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream():
+    torch = _torch()
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _rows(t, name: str):
+    """(m, stride) of a [P][m] tensor whose rows are contiguous."""
+    if t.dim() != 2 or t.stride(1) != 1:
+        raise ValueError(f"{name} must be 2-D with contiguous rows")
+    return t.shape[1], (t.stride(0) if t.shape[0] > 1 else max(t.stride(0), t.shape[1]))
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise GtopkError(status, where)
+
+
+def alloc_workspace(m: int, k: int, P: int, device="cuda"):
+    torch = _torch()
+    n = gtopk_workspace_bytes(m, k, P)
+    if n == 0:
+        raise GtopkError(GTOPK_EINVAL, "gtopk_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def alloc_merge_workspace(k: int, batch: int, device="cuda"):
+    torch = _torch()
+    n = gtopk_merge_workspace_bytes(k, batch)
+    if n == 0:
+        raise GtopkError(GTOPK_EINVAL, "gtopk_merge_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+# -- entry points -------------------------------------------------------------
+# index tensors are torch.int32 holding the uint32 bit patterns
+
+def gtopk_local_select(grad, residual, k: int, out_idx, out_val, ws) -> None:
+    torch = _torch()
+    m, stride = _rows(residual, "residual")
+    mg, sg = _rows(grad, "grad")
+    P = residual.shape[0]
+    if (mg, grad.shape[0]) != (m, P) or (P > 1 and sg != stride):
+        raise ValueError("grad and residual must have the same shape and row stride")
+    rc = load().gtopk_local_select(
+        _ptr(grad, torch.float32, "grad"), _ptr(residual, torch.float32, "residual"),
+        m, stride, P, k, _ptr(out_idx, torch.int32, "out_idx"),
+        _ptr(out_val, torch.float32, "out_val"), _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream())
+    _check(rc, "gtopk_local_select")
+
+
+def gtopk_merge(a_idx, a_val, b_idx, b_val, k: int, batch: int, in_stride: int,
+                out_idx, out_val, out_stride: int, ws) -> None:
+    torch = _torch()
+    rc = load().gtopk_merge(
+        _ptr(a_idx, torch.int32, "a_idx"), _ptr(a_val, torch.float32, "a_val"),
+        _ptr(b_idx, torch.int32, "b_idx"), _ptr(b_val, torch.float32, "b_val"),
+        k, batch, in_stride, _ptr(out_idx, torch.int32, "out_idx"),
+        _ptr(out_val, torch.float32, "out_val"), out_stride,
+        _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream())
+    _check(rc, "gtopk_merge")
+
+
+def gtopk_tree(loc_idx, loc_val, P: int, k: int, g_idx, g_val, ws) -> None:
+    torch = _torch()
+    rc = load().gtopk_tree(
+        _ptr(loc_idx, torch.int32, "loc_idx"), _ptr(loc_val, torch.float32, "loc_val"), P, k,
+        _ptr(g_idx, torch.int32, "g_idx"), _ptr(g_val, torch.float32, "g_val"),
+        _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream())
+    _check(rc, "gtopk_tree")
+
+
+def gtopk_residual_restore(residual, k: int, loc_idx, loc_val, g_idx) -> None:
+    torch = _torch()
+    m, stride = _rows(residual, "residual")
+    P = residual.shape[0]
+    rc = load().gtopk_residual_restore(
+        _ptr(residual, torch.float32, "residual"), m, stride, P, k,
+        _ptr(loc_idx, torch.int32, "loc_idx"), _ptr(loc_val, torch.float32, "loc_val"),
+        _ptr(g_idx, torch.int32, "g_idx"), _stream())
+    _check(rc, "gtopk_residual_restore")
+
+
+def gtopk_step(grad, residual, k: int, g_idx, g_val, loc_idx, loc_val, ws) -> None:
+    torch = _torch()
+    m, stride = _rows(residual, "residual")
+    mg, sg = _rows(grad, "grad")
+    P = residual.shape[0]
+    if (mg, grad.shape[0]) != (m, P) or (P > 1 and sg != stride):
+        raise ValueError("grad and residual must have the same shape and row stride")
+    rc = load().gtopk_step(
+        _ptr(grad, torch.float32, "grad"), _ptr(residual, torch.float32, "residual"),
+        m, stride, P, k, _ptr(g_idx, torch.int32, "g_idx"), _ptr(g_val, torch.float32, "g_val"),
+        _ptr(loc_idx, torch.int32, "loc_idx", allow_none=True),
+        _ptr(loc_val, torch.float32, "loc_val", allow_none=True),
+        _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream())
+    _check(rc, "gtopk_step")

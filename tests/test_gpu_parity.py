@@ -1,0 +1,231 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle,
+element by element and bit for bit (indices and fp32 values), on the same seeded
+inputs.  Sizes here are ones the oracle finishes in seconds; they span several
+8192-element blocks, ragged tails, unaligned rows and the degenerate cases."""
+import numpy as np
+import pytest
+
+from oracle import gtopk_oracle as orc
+from paper_1901_04359_amd import workloads as W
+from tests.gpu_harness import Device, bits_equal, first_diff, say, to_dev, idx_np, val_np
+
+pytestmark = pytest.mark.gpu
+
+
+def check_select(dev, res_in, grad, label):
+    """Run gtopk_local_select on the device and the oracle on the same rows."""
+    P, k = dev.P, dev.k
+    dev.set_res(res_in)
+    dev.set_grad(grad)
+    say(f"local_select {label} P={P} m={dev.m} k={k} stride={dev.stride}")
+    gi, gv = dev.local_select()
+    gres = dev.residual()
+    for w in range(P):
+        oi, ov, ores = orc.local_select(res_in[w], grad[w], k)
+        assert np.array_equal(gi[w], oi), f"{label} w={w} idx: {first_diff(gi[w], oi)}"
+        assert bits_equal(gv[w], ov), f"{label} w={w} val: {first_diff(gv[w], ov)}"
+        assert bits_equal(gres[w], ores), f"{label} w={w} residual: {first_diff(gres[w], ores)}"
+    return gres
+
+
+@pytest.mark.parametrize("name", ["C1", "C2"])
+def test_local_select_configs_with_feedback(name):
+    cfg = W.CONFIGS[name]
+    dev = Device(cfg.P, cfg.m, cfg.k)
+    res = np.zeros((cfg.P, cfg.m), dtype=np.float32)
+    for it in range(cfg.iters):
+        g = W.gradients(cfg, it)
+        res = check_select(dev, res, g, f"{name} it={it}")
+
+
+@pytest.mark.parametrize("base,m,P", [("C3", 1_000_003, 2), ("C4a", 2_000_000, 2),
+                                      ("C4b", 1_500_001, 2), ("C5", 1_234_567, 2)])
+def test_local_select_scaled_recipes(base, m, P):
+    cfg = W.scaled(W.CONFIGS[base], m, P=P)
+    dev = Device(P, cfg.m, cfg.k)
+    res = np.zeros((P, cfg.m), dtype=np.float32)
+    for it in range(2):
+        g = W.gradients(cfg, it)
+        res = check_select(dev, res, g, f"{cfg.name} it={it}")
+
+
+@pytest.mark.parametrize("m,k,stride", [
+    (1, 1, None), (5, 2, None), (5, 5, None), (255, 7, None), (8191, 100, None), (8192, 8192, None),
+    (8193, 1, None), (20_001, 333, 20_003),      # odd stride: rows are not 16-byte aligned
+    (40_000, 40_000, None), (100_000, 1, None), (65_537, 66, 65_540),
+])
+def test_local_select_shapes(m, k, stride):
+    P = 2
+    rng = np.random.default_rng(m * 31 + k)
+    dev = Device(P, m, k, stride=stride)
+    res = (rng.standard_normal((P, m)) * 1e-3).astype(np.float32)
+    grad = (rng.standard_normal((P, m)) * 1e-3).astype(np.float32)
+    check_select(dev, res, grad, "shape")
+
+
+@pytest.mark.parametrize("kind", ["all_equal", "all_zero", "special", "few_levels", "one_spike"])
+def test_local_select_degenerate_values(kind):
+    P, m, k = 2, 50_000, 777
+    rng = np.random.default_rng(1)
+    if kind == "all_equal":        # every magnitude ties: the lowest k indices win
+        grad = np.where(rng.random((P, m)) < 0.5, -1, 1).astype(np.float32) * np.float32(0.125)
+    elif kind == "all_zero":
+        grad = np.zeros((P, m), dtype=np.float32)
+        grad[:, ::3] = -0.0
+    elif kind == "special":
+        grad = np.stack([W.special_values(m, seed=s) for s in range(P)])
+    elif kind == "few_levels":
+        grad = rng.integers(-3, 4, (P, m)).astype(np.float32) * np.float32(0.5)
+    else:
+        grad = np.zeros((P, m), dtype=np.float32)
+        grad[:, 12345] = 7.0
+    res = np.zeros((P, m), dtype=np.float32)
+    if kind == "special":
+        res = np.stack([W.special_values(m, seed=10 + s) for s in range(P)])
+    dev = Device(P, m, k)
+    check_select(dev, res, grad, kind)
+
+
+def run_merge(a_idx, a_val, b_idx, b_val, k):
+    import torch
+    from paper_1901_04359_amd import binding as B
+    batch = a_idx.shape[0]
+    ws = B.alloc_merge_workspace(k, batch)
+    ws.fill_(0x5A)
+    out_idx = torch.zeros((batch, k), dtype=torch.int32, device="cuda")
+    out_val = torch.zeros((batch, k), dtype=torch.float32, device="cuda")
+    B.gtopk_merge(to_dev(a_idx), to_dev(a_val), to_dev(b_idx), to_dev(b_val), k, batch, k,
+                  out_idx, out_val, k, ws)
+    torch.cuda.synchronize()
+    return idx_np(out_idx), val_np(out_val)
+
+
+@pytest.mark.parametrize("kind", ["gauss", "ties", "cancel"])
+@pytest.mark.parametrize("k,m", [(1, 10), (2, 3), (64, 64), (255, 5000), (256, 5000), (257, 5000),
+                                 (5000, 200_000), (14_728, 1_000_000)])
+def test_merge_parity(kind, k, m):
+    batch = 3
+    idx, val = W.ksets(2 * batch, k, m, seed=k, overlap=0.4, value_kind=kind)
+    a_idx, a_val = idx[0::2].copy(), val[0::2].copy()
+    b_idx, b_val = idx[1::2].copy(), val[1::2].copy()
+    say(f"merge kind={kind} k={k} m={m} batch={batch}")
+    gi, gv = run_merge(a_idx, a_val, b_idx, b_val, k)
+    for b in range(batch):
+        oi, ov = orc.merge(a_idx[b], a_val[b], b_idx[b], b_val[b], k)
+        assert np.array_equal(gi[b], oi), f"b={b} idx: {first_diff(gi[b], oi)}"
+        assert bits_equal(gv[b], ov), f"b={b} val: {first_diff(gv[b], ov)}"
+
+
+@pytest.mark.parametrize("P", [1, 2, 4, 8, 16, 32])
+@pytest.mark.parametrize("k,m,kind", [(66, 65_536, "gauss"), (1000, 30_000, "cancel"),
+                                      (300, 2000, "ties")])
+def test_tree_parity(P, k, m, kind):
+    idx, val = W.ksets(P, k, m, seed=P + k, overlap=0.5, value_kind=kind)
+    dev = Device(P, k, k)          # only the k-set buffers and the workspace are used
+    dev.loc_idx.copy_(to_dev(idx))
+    dev.loc_val.copy_(to_dev(val))
+    say(f"tree P={P} k={k} m={m} kind={kind}")
+    gi, gv = dev.tree()
+    oi, ov = orc.tree(list(idx), list(val), k)
+    assert np.array_equal(gi, oi), first_diff(gi, oi)
+    assert bits_equal(gv, ov), first_diff(gv, ov)
+
+
+def test_tree_every_round_matches_oracle():
+    """Intermediate sets of every round, through gtopk_merge, in the tree's pairing."""
+    P, k, m = 8, 500, 20_000
+    idx, val = W.ksets(P, k, m, seed=77, overlap=0.6, value_kind="cancel")
+    hist = orc.tree_rounds(list(idx), list(val), k)
+    cur_i, cur_v = idx.copy(), val.copy()
+    for j, rnd in enumerate(hist):
+        say(f"tree round {j}")
+        gi, gv = run_merge(cur_i[0::2].copy(), cur_v[0::2].copy(),
+                           cur_i[1::2].copy(), cur_v[1::2].copy(), k)
+        survivors = [c for c in rnd if c is not None]
+        assert len(survivors) == gi.shape[0]
+        for p, (oi, ov) in enumerate(survivors):
+            assert np.array_equal(gi[p], oi) and bits_equal(gv[p], ov), f"round {j} pair {p}"
+        cur_i, cur_v = gi, gv
+
+
+@pytest.mark.parametrize("P,m,k", [(4, 65_536, 66), (2, 1000, 1000), (8, 100_000, 5000)])
+def test_restore_parity(P, m, k):
+    rng = np.random.default_rng(P * m + k)
+    res = (rng.standard_normal((P, m))).astype(np.float32)
+    loc_idx, loc_val = W.ksets(P, k, m, seed=5, overlap=0.5)
+    loc_val[:, ::7] = -0.0
+    for w in range(P):
+        res[w, loc_idx[w]] = 0.0
+    g_idx = np.sort(rng.choice(m, k, replace=False)).astype(np.uint32)
+    g_idx[: k // 2] = np.sort(loc_idx[0][: k // 2])       # make some local entries survive
+    g_idx = np.unique(g_idx)
+    while g_idx.size < k:
+        extra = rng.choice(m, k - g_idx.size, replace=False).astype(np.uint32)
+        g_idx = np.unique(np.concatenate([g_idx, extra]))
+    g_idx = g_idx[:k]
+    dev = Device(P, m, k)
+    dev.set_res(res)
+    dev.loc_idx.copy_(to_dev(loc_idx))
+    dev.loc_val.copy_(to_dev(loc_val))
+    dev.g_idx.copy_(to_dev(g_idx))
+    say(f"restore P={P} m={m} k={k}")
+    dev.restore()
+    out = dev.residual()
+    for w in range(P):
+        exp = orc.residual_restore(res[w], loc_idx[w], loc_val[w], g_idx)
+        assert bits_equal(out[w], exp), f"w={w}: {first_diff(out[w], exp)}"
+
+
+def check_steps(cfg, grads_of_iter, iters, label, want_loc=True):
+    P, m, k = cfg.P, cfg.m, cfg.k
+    dev = Device(P, m, k)
+    res = np.zeros((P, m), dtype=np.float32)
+    dev.set_res(res)
+    for it in range(iters):
+        g = grads_of_iter(it)
+        dev.set_grad(g)
+        say(f"step {label} it={it} P={P} m={m} k={k}")
+        gi, gv = dev.step(want_loc=want_loc)
+        exp = orc.step(res, g, k)
+        if want_loc:
+            li, lv = idx_np(dev.loc_idx), val_np(dev.loc_val)
+            assert np.array_equal(li, exp["loc_idx"]), f"it={it} loc_idx {first_diff(li, exp['loc_idx'])}"
+            assert bits_equal(lv, exp["loc_val"]), f"it={it} loc_val {first_diff(lv, exp['loc_val'])}"
+        assert np.array_equal(gi, exp["g_idx"]), f"it={it} g_idx {first_diff(gi, exp['g_idx'])}"
+        assert bits_equal(gv, exp["g_val"]), f"it={it} g_val {first_diff(gv, exp['g_val'])}"
+        out = dev.residual()
+        assert bits_equal(out, exp["residual"]), f"it={it} residual {first_diff(out, exp['residual'])}"
+        res = exp["residual"]
+
+
+@pytest.mark.parametrize("name", ["C1", "C2"])
+def test_step_configs_all_iterations(name):
+    cfg = W.CONFIGS[name]
+    check_steps(cfg, lambda it: W.gradients(cfg, it), cfg.iters, name)
+
+
+@pytest.mark.parametrize("base,m,P", [("C3", 500_009, 16), ("C4a", 1_000_000, 32),
+                                      ("C4b", 300_000, 32), ("C5", 400_001, 32)])
+def test_step_scaled_recipes(base, m, P):
+    cfg = W.scaled(W.CONFIGS[base], m, P=P)
+    check_steps(cfg, lambda it: W.gradients(cfg, it), 3, cfg.name, want_loc=(base != "C4b"))
+
+
+def test_step_correlated_workers():
+    """Workers share a component, so merges meet matching indices in every round."""
+    cfg = W.scaled(W.CONFIGS["C2"], 200_003, k=2000, P=8, name="correlated")
+    check_steps(cfg, lambda it: W.correlated_gradients(cfg.m, cfg.P, it), 3, "correlated")
+
+
+def test_step_is_deterministic():
+    cfg = W.scaled(W.CONFIGS["C4a"], 700_001, P=8)
+    g = W.gradients(cfg, 0)
+    outs = []
+    for rep in range(2):
+        dev = Device(cfg.P, cfg.m, cfg.k)
+        dev.set_grad(g)
+        say(f"determinism rep={rep}")
+        gi, gv = dev.step()
+        outs.append((gi.copy(), gv.copy(), dev.residual().copy(), idx_np(dev.loc_idx).copy()))
+    assert np.array_equal(outs[0][0], outs[1][0]) and bits_equal(outs[0][1], outs[1][1])
+    assert bits_equal(outs[0][2], outs[1][2]) and np.array_equal(outs[0][3], outs[1][3])
