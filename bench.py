@@ -1,0 +1,161 @@
+#!/usr/bin/env python3
+"""Benchmark of the gTop-k hot path on one MI355X.
+
+A "step" is one pass of the whole hot path (gtopk_step: local select for all P
+workers, log2 P merge rounds, division by P, residual restore) over one batch
+of synthetic gradients that is already resident in HBM.  The workload is the
+ResNet-50-sized configuration (m = 25,557,032 per worker, P = 32, k = 25,557).
+Successive steps feed on different gradient batches and on the residual the
+previous step left, as in training.
+
+Prints ONE JSON line.  `value` = P*m / t_step (gradient elements per second).
+`roofline` prices the dominant kernel (the streaming accumulate/filter pass)
+against HBM: algorithmic bytes = 12 per gradient element (read gradient, read
+residual, write residual), duration from HIP events recorded by the library
+around that kernel inside the timed steps.  `cpu_baseline` times the CPU oracle
+on a bounded sample of the same workload (a few whole workers).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+N_STAGES = 6
+STAGE_NAMES = ["sample", "accumulate_filter", "exact_select", "tree", "restore"]
+
+
+def read_traffic_note(workload: str):
+    """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc
+    summary (a line `traffic_bytes_per_launch <workload> <bytes>`), or None."""
+    path = os.path.join(ROOT, "profiles", "k_accum_filter_traffic.txt")
+    try:
+        for line in open(path):
+            f = line.split()
+            if len(f) == 3 and f[0] == "traffic_bytes_per_launch" and f[1] == workload:
+                return float(f[2])
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(cfg, n_workers: int):
+    from oracle import gtopk_oracle as orc
+    from paper_1901_04359_amd import workloads as W
+    g = W.gradients(cfg, 0, workers=range(n_workers))
+    r = np.zeros_like(g)
+    t0 = time.perf_counter()
+    orc.step(r, g, cfg.k)
+    dt = time.perf_counter() - t0
+    return {
+        "value": n_workers * cfg.m / dt, "unit": "gradient elements/s", "cores": 1,
+        "kind": "oracle",
+        "sample": (f"oracle.step on {n_workers} of the {cfg.P} workers at full m={cfg.m}, "
+                   f"k={cfg.k} (select, {n_workers.bit_length() - 1}-round tree, restore), "
+                   f"one iteration, {dt:.1f} s, numpy single-threaded"),
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="C4a")
+    ap.add_argument("--batches", type=int, default=2, help="distinct gradient batches staged in HBM")
+    ap.add_argument("--cpu-workers", type=int, default=4, help="workers in the oracle sample (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (all P workers are buffers on one device); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_1901_04359_amd import binding as B
+    from paper_1901_04359_amd import workloads as W
+
+    B.load()      # fails loudly if the HIP library is missing
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    cfg = W.CONFIGS[args.workload]
+    P, m, k = cfg.P, cfg.m, cfg.k
+    K, Wm = args.steps, args.warmup
+
+    t_gen = time.perf_counter()
+    grads = []
+    for b in range(args.batches):
+        host = W.gradients(cfg, b, threads=min(16, os.cpu_count() or 8))
+        grads.append(torch.from_numpy(host).cuda())
+        del host
+    t_gen = time.perf_counter() - t_gen
+    res = torch.zeros((P, m), dtype=torch.float32, device="cuda")
+    g_idx = torch.zeros(k, dtype=torch.int32, device="cuda")
+    g_val = torch.zeros(k, dtype=torch.float32, device="cuda")
+    ws = B.alloc_workspace(m, k, P)
+
+    def step(i: int) -> None:
+        B.gtopk_step(grads[i % len(grads)], res, k, g_idx, g_val, None, None, ws)
+
+    # stage events: created up front (a first record forces creation), recorded by the library
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(N_STAGES)] for _ in range(K)]
+    for row in events:
+        for e in row:
+            e.record()
+    for i in range(Wm):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(K):
+        B.gtopk_arm_stage_events([e.cuda_event for e in events[i]])
+        step(Wm + i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    ms_per_step = (t1 - t0) * 1e3 / K
+    stage_ms = np.zeros(N_STAGES - 1)
+    for row in events:
+        for s in range(N_STAGES - 1):
+            stage_ms[s] += row[s].elapsed_time(row[s + 1])
+    stage_ms /= K
+    value = P * m / (ms_per_step * 1e-3)
+
+    kern_ms = float(stage_ms[1])
+    alg_bytes = 12.0 * P * m
+    achieved = alg_bytes / (kern_ms * 1e-3) / 1e9
+    traffic = read_traffic_note(cfg.name)
+    out = {
+        "metric": "gTop-k step throughput (P*m gradient elem/s) + achieved HBM GB/s vs peak",
+        "value": value, "unit": "gradient elements/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: ResNet-50-sized, m={m} fp32 per worker, P={P} workers "
+                               f"on one GPU, k={k} (rho={cfg.rho:.4g}), {len(grads)} gradient "
+                               f"batches cycled, residual carried across steps",
+                   "m": m, "P": P, "k": k},
+        "step_hbm": {"algorithmic_GBs": alg_bytes / (ms_per_step * 1e-3) / 1e9,
+                     "frac_of_peak": alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
+        "stages_ms": {n: round(float(v), 4) for n, v in zip(STAGE_NAMES, stage_ms)},
+        "roofline": {"kernel": "k_accum_filter", "bound": "hbm", "achieved": achieved,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": traffic, "launch_ms": kern_ms,
+                     "algorithmic_bytes_per_launch": alg_bytes},
+        "input_generation_s": round(t_gen, 1),
+    }
+    if args.cpu_workers > 0:
+        out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_workers)
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -130,6 +130,31 @@ int gtopk_step(const float* grad, float* residual, int64_t m, int64_t stride,
                uint32_t* loc_idx, float* loc_val,
                void* ws, size_t ws_bytes, void* stream);
 
+/*
+ * Instrumentation for benchmarks (not part of the method): arm the NEXT
+ * gtopk_step call on this process to record the given HOST handles of six
+ * hipEvent_t (created by the caller, passed as void*) on its stream at its
+ * stage boundaries:
+ *   [0] start  [1] after the sampling kernels  [2] after the streaming
+ *   accumulate/filter kernel  [3] after the exact local selection
+ *   [4] after the tree  [5] after the residual restore.
+ * The arming is consumed by that one call.  events == NULL disarms.  Not
+ * thread-safe.  Returns GTOPK_EINVAL if one of the six handles is NULL.
+ */
+#define GTOPK_STAGE_EVENTS 6
+int gtopk_arm_stage_events(void* const* events);
+
+/*
+ * Instrumentation for tests (not part of the method): after a gtopk_local_select or
+ * gtopk_step on workspace `ws` with these sizes has COMPLETED, copy to the host how
+ * many candidates the streaming pass kept for each worker (host_counts[P]) and the
+ * capacity of a worker's candidate list (*host_capacity).  A worker whose count is
+ * below k or above the capacity was selected from its dense row instead.
+ * Synchronous (blocking device-to-host copy).
+ */
+int gtopk_debug_candidate_counts(const void* ws, int64_t m, int32_t k, int32_t P,
+                                 uint32_t* host_counts, uint32_t* host_capacity);
+
 #ifdef __cplusplus
 }
 #endif

@@ -19,6 +19,7 @@ _lib: Optional[ctypes.CDLL] = None
 EXPORTS = (
     "gtopk_status_string", "gtopk_workspace_bytes", "gtopk_merge_workspace_bytes",
     "gtopk_local_select", "gtopk_merge", "gtopk_tree", "gtopk_residual_restore", "gtopk_step",
+    "gtopk_arm_stage_events", "gtopk_debug_candidate_counts",
 )
 
 GTOPK_OK, GTOPK_EINVAL, GTOPK_EWORKSPACE, GTOPK_EALIGN, GTOPK_EHIP = 0, -1, -2, -3, -4
@@ -62,6 +63,11 @@ def load() -> ctypes.CDLL:
     lib.gtopk_residual_restore.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp]
     lib.gtopk_step.restype = c.c_int
     lib.gtopk_step.argtypes = [vp, vp, i64, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.gtopk_arm_stage_events.restype = c.c_int
+    lib.gtopk_arm_stage_events.argtypes = [c.POINTER(c.c_void_p)]
+    lib.gtopk_debug_candidate_counts.restype = c.c_int
+    lib.gtopk_debug_candidate_counts.argtypes = [vp, i64, i32, i32, c.POINTER(c.c_uint32),
+                                                 c.POINTER(c.c_uint32)]
     _lib = lib
     return lib
 
@@ -194,3 +200,24 @@ def gtopk_step(grad, residual, k: int, g_idx, g_val, loc_idx, loc_val, ws) -> No
         _ptr(loc_val, torch.float32, "loc_val", allow_none=True),
         _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream())
     _check(rc, "gtopk_step")
+
+
+def gtopk_arm_stage_events(events) -> None:
+    """events: sequence of six raw hipEvent_t handles (ints), or None to disarm."""
+    if events is None:
+        _check(load().gtopk_arm_stage_events(None), "gtopk_arm_stage_events")
+        return
+    arr = (ctypes.c_void_p * len(events))(*events)
+    _check(load().gtopk_arm_stage_events(arr), "gtopk_arm_stage_events")
+
+
+def gtopk_debug_candidate_counts(ws, m: int, k: int, P: int):
+    """(per-worker candidate counts, list capacity) of the last completed select on `ws`."""
+    torch = _torch()
+    torch.cuda.synchronize()
+    counts = (ctypes.c_uint32 * P)()
+    cap = ctypes.c_uint32(0)
+    rc = load().gtopk_debug_candidate_counts(_ptr(ws, torch.uint8, "ws"), m, k, P, counts,
+                                             ctypes.byref(cap))
+    _check(rc, "gtopk_debug_candidate_counts")
+    return list(counts), int(cap.value)

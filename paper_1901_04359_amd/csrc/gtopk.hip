@@ -5,16 +5,26 @@
 //   local select   sample histogram -> speculative threshold -> ONE streaming pass
 //                  (acc = residual + grad, written back; entries at or above the
 //                  speculative threshold are compacted into a short candidate list)
-//                  -> exact radix select of the k-th key among the candidates
-//                  -> index-ordered emit of the k selected entries (+ zeroing).
+//                  -> exact select of the k-th key among the candidates
+//                  -> index-ordered emit of the k selected entries.
 //                  The speculative threshold only decides how much work the exact
-//                  part has; if it was too high or too low for a worker, that
-//                  worker's exact part reads its dense row instead (same kernels).
+//                  part has; if it left a worker fewer than k candidates or more than
+//                  the list holds, that worker's exact part reads its dense row
+//                  instead (same kernels, decided on the device).
 //   tree           per round: index-ordered union of the two k-sets of each pair
-//                  (values at shared indices added) -> the same exact radix select
+//                  (values at shared indices added) -> the same exact select
 //                  -> ordered emit; the last round divides by P.
-//   restore        membership test of each local entry in the global index set,
-//                  add back on a miss.
+//   restore        membership test of each local entry in the global index set.
+//
+// Exact select of the k-th largest 31-bit key of a set, in four kernels:
+//   hist    12-bit histogram of the top key bits
+//   bucket  every block first picks, from that histogram, the bucket d1 that holds the
+//           k-th key; then per group of items: count of keys above the bucket; keys
+//           inside the bucket are appended (low 19 bits + group id) to a short list
+//   finish  one block per set: two LDS radix passes over the list give the exact key
+//           T and the number of ties to take; per-group counts are completed from the
+//           list and scanned into output offsets
+//   emit    per group: ordered compaction of the selected entries
 //
 // Nothing here is a dense contraction, so there is no MFMA; the streaming pass is
 // bound by HBM bandwidth and everything after it by launch latency.
@@ -26,22 +36,25 @@
 namespace {
 
 constexpr int kWave = 64;
-constexpr int kBlock = 256;                 // threads per block in the streaming kernels
-constexpr int kIters = 8;                   // float4 loads per lane in the streaming pass
-constexpr int kWaveSpan = kIters * 4 * kWave;      // 2048 elements per wave
-constexpr int kChunk = kWaveSpan * (kBlock / kWave);  // 8192 elements per block = one run
-constexpr int kMergeRun = 256;              // merged-array slots per run
-constexpr int kHistBins = 4096;             // 12-bit digits (the last pass uses 128 of them)
+constexpr int kSBlock = 512;                // threads per block of the streaming pass
+constexpr int kIters = 16;                  // float4 loads per lane and array in the streaming pass
+constexpr int kWaveSpan = kIters * 4 * kWave;            // 4096 elements per wave
+constexpr int kChunk = kWaveSpan * (kSBlock / kWave);    // 32768 elements per block = one run
+constexpr int kBlock = 256;                 // threads per block of the select kernels
+constexpr int kMaxSeg = 32;                 // runs per group, at most
+constexpr int kMaxGroups = 2048;            // groups per set, at most (LDS arrays in k_finish)
+constexpr int kHistBins = 4096;             // first digit: key bits 30..19
+constexpr int kLowBits = 19;                // key bits below the first digit
+constexpr uint32_t kLowMask = (1u << kLowBits) - 1;
 constexpr int kSampleBits = 14;             // sample histogram: exponent + 6 mantissa bits
 constexpr int kSampleBins = 1 << kSampleBits;
 constexpr int kSampleShift = 31 - kSampleBits;
 constexpr int kSampleTile = 256;            // contiguous elements per sample tile
+constexpr int kSampleBlock = 1024;
 constexpr uint32_t kTomb = 0xFFFFFFFFu;     // index of a merged slot that holds nothing
 constexpr uint32_t kAbs = 0x7FFFFFFFu;
 
-// digit of a 31-bit key in select pass p: bits 30..19, 18..7, 6..0
-__device__ __forceinline__ int pass_shift(int p) { return p == 0 ? 19 : (p == 1 ? 7 : 0); }
-__device__ __forceinline__ int pass_bits(int p) { return p == 2 ? 7 : 12; }
+typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ uint32_t lane_id() { return threadIdx.x & (kWave - 1); }
 
@@ -52,97 +65,159 @@ __device__ __forceinline__ uint32_t rank_in(uint64_t mask) {
 }
 
 // ---------------------------------------------------------------------------------
-// small utilities
+// block-wide primitives (every thread of the block must call them)
 // ---------------------------------------------------------------------------------
 
-typedef float floatx4 __attribute__((ext_vector_type(4)));
-
-// clears up to three arrays in one launch (an array with n == 0 is skipped)
-__global__ void k_zero_u32(uint32_t* p0, size_t n0, uint32_t* p1, size_t n1, uint32_t* p2, size_t n2) {
-    const size_t step = (size_t)gridDim.x * blockDim.x;
-    const size_t first = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    for (size_t i = first; i < n0; i += step) p0[i] = 0u;
-    for (size_t i = first; i < n1; i += step) p1[i] = 0u;
-    for (size_t i = first; i < n2; i += step) p2[i] = 0u;
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v) {
+    const uint32_t lane = lane_id();
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const uint32_t t = __shfl_up(v, d);
+        if (lane >= (uint32_t)d) v += t;
+    }
+    return v;
 }
 
-// Largest digit d with sum_{b >= d} h[b] >= target, and above = sum_{b > d} h[b].
-// All threads of the block call it; blockDim.x divides nbins and nbins / blockDim.x <= 16.
-// Results land in s_out[0] (digit) and s_out[1] (above), valid after the call for all
-// threads.  If the whole histogram holds fewer than `target` entries, digit = 0 and
-// above = total - h[0] are NOT guaranteed; s_out[2] is 1 only when a digit was found.
-__device__ void suffix_pick(const uint32_t* h, int nbins, uint32_t target,
-                            uint32_t* s_tsum, uint32_t* s_out) {
-    const int t = threadIdx.x;
-    const int per = nbins / blockDim.x;
-    uint32_t loc[16];
+// inclusive prefix sum over the block in thread order; s_wave: LDS, >= blockDim.x/64 words
+__device__ uint32_t block_incl_scan(uint32_t v, uint32_t* s_wave, uint32_t& total) {
+    const uint32_t wave = threadIdx.x / kWave;
+    const uint32_t nw = blockDim.x / kWave;
+    const uint32_t incl = wave_incl_scan(v);
+    __syncthreads();                       // s_wave may still be read from an earlier call
+    if (lane_id() == kWave - 1) s_wave[wave] = incl;
+    __syncthreads();
+    uint32_t base = 0, tot = 0;
+    for (uint32_t i = 0; i < nw; ++i) {
+        const uint32_t x = s_wave[i];
+        if (i < wave) base += x;
+        tot += x;
+    }
+    total = tot;
+    return incl + base;
+}
+
+// Thread t owns the PER histogram bins [t*PER, (t+1)*PER), counts in loc[].  Finds the
+// largest bin d with sum_{b >= d} >= target.  s_out[0] = d, s_out[1] = sum_{b > d},
+// s_out[2] = 1 if such a bin exists (0 if the histogram holds fewer than target entries).
+template <int PER>
+__device__ void suffix_pick(const uint32_t (&loc)[PER], uint32_t target, uint32_t* s_wave,
+                            uint32_t* s_out) {
     uint32_t mine = 0;
 #pragma unroll
-    for (int j = 0; j < 16; ++j) {
-        loc[j] = (j < per) ? h[t * per + j] : 0u;
-        mine += loc[j];
-    }
-    s_tsum[t] = mine;
-    if (t == 0) { s_out[0] = 0; s_out[1] = 0; s_out[2] = 0; }
-    __syncthreads();
-    uint32_t above = 0;
-    for (int u = t + 1; u < (int)blockDim.x; ++u) above += s_tsum[u];
-    if (above < target && above + mine >= target) {      // exactly one thread owns the crossing
+    for (int j = 0; j < PER; ++j) mine += loc[j];
+    if (threadIdx.x == 0) { s_out[0] = 0; s_out[1] = 0; s_out[2] = 0; }
+    uint32_t total;
+    const uint32_t incl = block_incl_scan(mine, s_wave, total);
+    const uint32_t above = total - incl;
+    if (above < target && above + mine >= target) {       // exactly one thread owns the crossing
         uint32_t run = above;
 #pragma unroll
-        for (int j = 15; j >= 0; --j) {
-            if (j < per) {
-                uint32_t c = loc[j];
-                if (run < target && run + c >= target) {
-                    s_out[0] = (uint32_t)(t * per + j);
-                    s_out[1] = run;
-                    s_out[2] = 1;
-                }
-                run += c;
+        for (int j = PER - 1; j >= 0; --j) {
+            const uint32_t c = loc[j];
+            if (run < target && run + c >= target) {
+                s_out[0] = (uint32_t)(threadIdx.x * PER + j);
+                s_out[1] = run;
+                s_out[2] = 1;
             }
+            run += c;
         }
     }
     __syncthreads();
 }
+
+// ---------------------------------------------------------------------------------
+// clearing
+// ---------------------------------------------------------------------------------
+
+struct ZeroJob { uint32_t* p[4]; size_t n[4]; };
+
+// clears up to four arrays in one launch (an array with n == 0 is skipped)
+__global__ void k_zero_u32(ZeroJob job) {
+    const size_t step = (size_t)gridDim.x * blockDim.x;
+    const size_t first = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+        for (size_t i = first; i < job.n[a]; i += step) job.p[a][i] = 0u;
+}
+
+// ---------------------------------------------------------------------------------
+// per-set state of the exact select
+// ---------------------------------------------------------------------------------
+
+struct SelState {
+    uint32_t* hist;       // [sets][4096]   zero between uses
+    uint32_t* list_cnt;   // [sets]         zero between uses
+    uint32_t* d1;         // [sets] first digit of the k-th key
+    uint32_t* krem;       // [sets] rank of the k-th key inside bucket d1 (1-based, from the top)
+    uint32_t* T;          // [sets] the k-th largest key
+    uint32_t* need;       // [sets] entries with key == T to take (>= 1)
+    uint32_t* list;       // [sets][list_cap]  (low 19 key bits) | (group << 19)
+    uint32_t* grp_gt;     // [sets][maxgroups] entries of the group above bucket d1
+    uint32_t* off_gt;     // [sets][maxgroups] exclusive scans over groups
+    uint32_t* off_eq;
+    uint32_t list_cap, maxgroups;
+};
 
 // ---------------------------------------------------------------------------------
 // local select, part 1: sampled histogram of |residual + grad| -> speculative threshold
 // ---------------------------------------------------------------------------------
 
-// Sample tile t of a row covers [t*tile_stride, t*tile_stride + 256) (clipped to m).
-__global__ __launch_bounds__(kBlock) void k_sample_hist(
+// Sample tile t of a row covers [t*tile_stride, t*tile_stride + 256) (clipped to m).  A
+// block of 1024 threads takes four tiles per round.
+__global__ __launch_bounds__(kSampleBlock) void k_sample(
         const float* __restrict__ grad, const float* __restrict__ res, uint32_t m, int64_t stride,
         uint32_t tile_stride, uint32_t n_tiles, uint32_t* __restrict__ samp_hist) {
     __shared__ uint32_t h[kSampleBins];
     const int w = blockIdx.y;
-    for (int b = threadIdx.x; b < kSampleBins; b += kBlock) h[b] = 0u;
+    for (int b = threadIdx.x; b < kSampleBins; b += kSampleBlock) h[b] = 0u;
     __syncthreads();
     const float* g = grad + (int64_t)w * stride;
     const float* r = res + (int64_t)w * stride;
-    for (uint32_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
-        uint64_t q = (uint64_t)t * tile_stride + threadIdx.x;
-        if (q < m) {
-            float a = r[q] + g[q];
-            uint32_t key = __float_as_uint(a) & kAbs;
-            atomicAdd(&h[key >> kSampleShift], 1u);
+    const uint32_t sub = threadIdx.x / kSampleTile, el = threadIdx.x % kSampleTile;
+    constexpr int kUnroll = 8;
+    const uint64_t tiles_per_round = (uint64_t)(kSampleBlock / kSampleTile) * gridDim.x;
+    for (uint64_t t0 = (uint64_t)blockIdx.x * (kSampleBlock / kSampleTile) + sub; t0 < n_tiles;
+         t0 += tiles_per_round * kUnroll) {
+        float gv[kUnroll], rv[kUnroll];
+        bool ok[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const uint64_t t = t0 + (uint64_t)u * tiles_per_round;
+            const uint64_t q = t * tile_stride + el;
+            ok[u] = t < n_tiles && q < m;
+            gv[u] = ok[u] ? g[q] : 0.0f;
+            rv[u] = ok[u] ? r[q] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            if (ok[u]) {
+                const uint32_t key = __float_as_uint(rv[u] + gv[u]) & kAbs;
+                atomicAdd(&h[key >> kSampleShift], 1u);
+            }
         }
     }
     __syncthreads();
     uint32_t* out = samp_hist + (size_t)w * kSampleBins;
-    for (int b = threadIdx.x; b < kSampleBins; b += kBlock) {
-        uint32_t c = h[b];
+    for (int b = threadIdx.x; b < kSampleBins; b += kSampleBlock) {
+        const uint32_t c = h[b];
         if (c) atomicAdd(&out[b], c);
     }
 }
 
-// One block of 1024 threads per worker: the lower edge of the bucket at which the
-// sample's suffix count reaches `target` becomes the worker's speculative threshold.
-__global__ __launch_bounds__(1024) void k_sample_pick(const uint32_t* __restrict__ samp_hist,
-                                                      uint32_t target, uint32_t* __restrict__ tspec) {
-    __shared__ uint32_t s_tsum[1024];
+// One block per worker turns the worker's sample histogram into the speculative
+// threshold: the lower edge of the bucket at which the count from the top reaches
+// `target`.
+__global__ __launch_bounds__(kSampleBlock) void k_sample_pick(
+        const uint32_t* __restrict__ samp_hist, uint32_t target, uint32_t* __restrict__ tspec) {
+    __shared__ uint32_t s_wave[kSampleBlock / kWave];
     __shared__ uint32_t s_out[3];
     const int w = blockIdx.x;
-    suffix_pick(samp_hist + (size_t)w * kSampleBins, kSampleBins, target, s_tsum, s_out);
+    constexpr int kPer = kSampleBins / kSampleBlock;
+    const uint32_t* hist = samp_hist + (size_t)w * kSampleBins;
+    uint32_t loc[kPer];
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) loc[j] = hist[threadIdx.x * kPer + j];
+    suffix_pick<kPer>(loc, target, s_wave, s_out);
     if (threadIdx.x == 0) tspec[w] = s_out[2] ? (s_out[0] << kSampleShift) : 0u;
 }
 
@@ -150,20 +225,21 @@ __global__ __launch_bounds__(1024) void k_sample_pick(const uint32_t* __restrict
 // local select, part 2: the streaming pass
 // ---------------------------------------------------------------------------------
 
-// Block (chunk, w) handles elements [chunk*8192, +8192) of worker w; each wave a
-// contiguous 2048 of them, 8 float4 per lane, all held in registers.  Phase 1
+// Block (chunk, w) handles elements [chunk*32768, +32768) of worker w; each of its 8
+// waves a contiguous 4096 of them, 16 float4 per lane, all held in registers.  Phase 1
 // loads, adds, stores and counts the entries whose key reaches the speculative
 // threshold; one atomicAdd per block reserves a contiguous range of the worker's
 // candidate list; phase 2 writes the block's candidates there in index order.
 // run_table[w][chunk] = (first slot, count) lets later kernels walk the list in
 // index order although blocks reserve in any order.
 template <bool ALIGNED>
-__global__ __launch_bounds__(kBlock) void k_accum_filter(
+__global__ __launch_bounds__(kSBlock) void k_accum_filter(
         const float* __restrict__ grad, float* __restrict__ res, uint32_t m, int64_t stride,
         const uint32_t* __restrict__ tspec, uint32_t* __restrict__ cand_idx,
         float* __restrict__ cand_val, uint32_t cap, uint32_t* __restrict__ cand_count,
         uint2* __restrict__ run_table, uint32_t nchunks) {
-    __shared__ uint32_t s_cnt[kBlock / kWave];
+    constexpr int kWaves = kSBlock / kWave;
+    __shared__ uint32_t s_cnt[kWaves];
     __shared__ uint32_t s_base;
     const int w = blockIdx.y;
     const uint32_t chunk = blockIdx.x;
@@ -172,7 +248,8 @@ __global__ __launch_bounds__(kBlock) void k_accum_filter(
     const float* g = grad + (int64_t)w * stride;
     float* r = res + (int64_t)w * stride;
     const uint32_t ts = tspec[w];
-    const uint32_t wbase = chunk * (uint32_t)kChunk + wave * (uint32_t)kWaveSpan;  // <= m + 8191 < 2^32
+    // m <= 2^31 and chunk < ceil(m / 32768), so none of the offsets below wraps
+    const uint32_t wbase = chunk * (uint32_t)kChunk + wave * (uint32_t)kWaveSpan;
 
     float a[kIters][4];
     const bool whole = ALIGNED && (wbase + (uint32_t)kWaveSpan <= m);   // wave-uniform
@@ -188,7 +265,7 @@ __global__ __launch_bounds__(kBlock) void k_accum_filter(
         for (int i = 0; i < kIters; ++i) {
             const uint32_t q = wbase + i * 256 + lane * 4;
             const floatx4 s = rv[i] + gv[i];          // four independent fp32 adds
-            *reinterpret_cast<floatx4*>(r + q) = s;
+            __builtin_nontemporal_store(s, reinterpret_cast<floatx4*>(r + q));
             a[i][0] = s.x; a[i][1] = s.y; a[i][2] = s.z; a[i][3] = s.w;
         }
     } else {
@@ -220,7 +297,8 @@ __global__ __launch_bounds__(kBlock) void k_accum_filter(
     if (lane == 0) s_cnt[wave] = cnt;
     __syncthreads();
     if (threadIdx.x == 0) {
-        const uint32_t total = s_cnt[0] + s_cnt[1] + s_cnt[2] + s_cnt[3];
+        uint32_t total = 0;
+        for (int v = 0; v < kWaves; ++v) total += s_cnt[v];
         uint32_t base = 0;
         if (total) base = atomicAdd(&cand_count[w], total);
         run_table[(size_t)w * nchunks + chunk] = make_uint2(base, total);
@@ -256,17 +334,18 @@ __global__ __launch_bounds__(kBlock) void k_accum_filter(
 }
 
 // ---------------------------------------------------------------------------------
-// item sources for the exact select (histogram passes, count, ordered emit)
+// item sources for the exact select
 // ---------------------------------------------------------------------------------
-// A source presents, per set s, a flat array of nphys(s) slots (for histograms) and
-// the same slots grouped into runs listed in index order (for the ordered emit).
+// A source presents, per set s, a flat array of nphys(s) slots (for the histogram) and
+// the same slots as groups of segments; groups, and the segments inside a group, are
+// listed in index order (for the ordered emit).
 
 // Local select: the candidate list of worker s, or - when the speculative threshold
 // left fewer than k candidates or more than the list holds - the worker's dense row.
 struct CandSrc {
     const float* res;
     int64_t stride;
-    uint32_t m, k, cap, nchunks;
+    uint32_t m, k, cap, nchunks, G;       // G runs per group
     const uint32_t* cand_idx;
     const float* cand_val;
     const uint32_t* cand_count;
@@ -287,8 +366,13 @@ struct CandSrc {
         }
         return true;
     }
-    __device__ uint32_t nruns(int, bool) const { return nchunks; }
-    __device__ uint2 run(int s, bool dn, uint32_t r) const {
+    __device__ uint32_t ngroups(int, bool) const { return (nchunks + G - 1) / G; }
+    __device__ uint32_t nseg(int, bool, uint32_t g) const {
+        const uint32_t left = nchunks - g * G;
+        return left < G ? left : G;
+    }
+    __device__ uint2 segment(int s, bool dn, uint32_t g, uint32_t j) const {
+        const uint32_t r = g * G + j;
         if (dn) {
             const uint32_t base = r * (uint32_t)kChunk;
             const uint32_t left = m - base;
@@ -298,11 +382,11 @@ struct CandSrc {
     }
 };
 
-// Merge: 2k slots per pair, index-ascending, a slot with index kTomb holds nothing.
+// Merge: n = 2k slots per pair, index-ascending, a slot with index kTomb holds nothing.
 struct MergedSrc {
     const uint32_t* idx;
     const float* val;
-    uint32_t n;       // 2k
+    uint32_t n, L;       // L slots per group
     __device__ bool dense(int) const { return false; }
     __device__ uint32_t nphys(int, bool) const { return n; }
     __device__ bool fetch(int s, bool, uint32_t p, uint32_t& i, uint32_t& bits) const {
@@ -310,182 +394,354 @@ struct MergedSrc {
         bits = __float_as_uint(val[(size_t)s * n + p]);
         return i != kTomb;
     }
-    __device__ uint32_t nruns(int, bool) const { return (n + kMergeRun - 1) / kMergeRun; }
-    __device__ uint2 run(int, bool, uint32_t r) const {
-        const uint32_t base = r * (uint32_t)kMergeRun;
+    __device__ uint32_t ngroups(int, bool) const { return (n + L - 1) / L; }
+    __device__ uint32_t nseg(int, bool, uint32_t) const { return 1; }
+    __device__ uint2 segment(int, bool, uint32_t g, uint32_t) const {
+        const uint32_t base = g * L;
         const uint32_t left = n - base;
-        return make_uint2(base, left < (uint32_t)kMergeRun ? left : (uint32_t)kMergeRun);
+        return make_uint2(base, left < L ? left : L);
     }
 };
 
-// ---------------------------------------------------------------------------------
-// exact select: three digit passes (12 + 12 + 7 bits of the 31-bit key)
-// ---------------------------------------------------------------------------------
+// Segments of one group, in LDS; item i of the group is slot base[j] + i - start[j]
+// of the segment j with start[j] <= i < start[j+1].
+struct GroupSegs {
+    uint32_t base[kMaxSeg];
+    uint32_t start[kMaxSeg + 1];
+    uint32_t n;
+};
 
 template <class Src>
-__global__ __launch_bounds__(kBlock) void k_hist(Src src, int pass, uint32_t* __restrict__ hist,
-                                                 const uint32_t* __restrict__ st_prefix) {
-    __shared__ uint32_t h[kHistBins];
-    const int s = blockIdx.y;
-    const int shift = pass_shift(pass), bits = pass_bits(pass);
-    const int nbins = 1 << bits;
-    for (int b = threadIdx.x; b < nbins; b += kBlock) h[b] = 0u;
-    __syncthreads();
-    const bool dn = src.dense(s);
-    const uint32_t n = src.nphys(s, dn);
-    const uint32_t prefix = pass == 0 ? 0u : st_prefix[s];
-    const uint32_t step = gridDim.x * kBlock;
-    for (uint64_t p = (uint64_t)blockIdx.x * kBlock + threadIdx.x; p < n; p += step) {
-        uint32_t idx, vb;
-        if (src.fetch(s, dn, (uint32_t)p, idx, vb)) {
-            const uint32_t key = vb & kAbs;
-            // (key >> 31) is 0, so pass 0 matches the empty prefix
-            if ((key >> (shift + bits)) == prefix) atomicAdd(&h[(key >> shift) & (nbins - 1)], 1u);
-        }
+__device__ uint32_t load_group(const Src& src, int s, bool dn, uint32_t g, GroupSegs* gs) {
+    const uint32_t ns = src.nseg(s, dn, g);
+    __syncthreads();                              // the previous group may still be in use
+    if (threadIdx.x < ns) {
+        const uint2 sg = src.segment(s, dn, g, threadIdx.x);
+        gs->base[threadIdx.x] = sg.x;
+        gs->start[threadIdx.x + 1] = sg.y;        // counts for now
     }
     __syncthreads();
-    uint32_t* out = hist + (size_t)s * kHistBins;
-    for (int b = threadIdx.x; b < nbins; b += kBlock) {
+    if (threadIdx.x == 0) {
+        uint32_t run = 0;
+        gs->start[0] = 0;
+        for (uint32_t j = 0; j < ns; ++j) {
+            run += gs->start[j + 1];
+            gs->start[j + 1] = run;
+        }
+        gs->n = ns;
+    }
+    __syncthreads();
+    return gs->start[ns];
+}
+
+__device__ __forceinline__ uint32_t group_slot(const GroupSegs* gs, uint32_t i) {
+    uint32_t j = 0;
+    while (j + 1 < gs->n && i >= gs->start[j + 1]) ++j;
+    return gs->base[j] + (i - gs->start[j]);
+}
+
+// ---------------------------------------------------------------------------------
+// exact select, kernel 1: histogram of the first digit (key bits 30..19)
+// ---------------------------------------------------------------------------------
+
+constexpr int kHistBlock = 1024;
+
+// adds the block's LDS histogram into the set's global one
+__device__ void flush_hist(const uint32_t* h, uint32_t* out) {
+    for (int b = threadIdx.x; b < kHistBins; b += blockDim.x) {
         const uint32_t c = h[b];
         if (c) atomicAdd(&out[b], c);
     }
 }
 
-// One block per set: pick the digit of this pass, extend the prefix, clear the histogram.
-// After pass 2, st_prefix[s] is the k-th largest key T and st_krem[s] the number of
-// entries with key == T to take (>= 1); k - st_krem[s] entries have key > T.
-__global__ void k_pick(uint32_t* __restrict__ hist, int pass, uint32_t k,
-                       uint32_t* __restrict__ st_prefix, uint32_t* __restrict__ st_krem) {
-    __shared__ uint32_t s_tsum[kBlock];
-    __shared__ uint32_t s_out[3];
-    const int s = blockIdx.x;
-    const int bits = pass_bits(pass);
-    const int nbins = 1 << bits;
-    uint32_t* h = hist + (size_t)s * kHistBins;
-    const uint32_t target = pass == 0 ? k : st_krem[s];
-    const uint32_t prefix = pass == 0 ? 0u : st_prefix[s];
-    suffix_pick(h, nbins, target, s_tsum, s_out);
-    const int per = nbins / blockDim.x;
-    for (int j = 0; j < per; ++j) h[threadIdx.x * per + j] = 0u;
-    if (threadIdx.x == 0) {
-        st_prefix[s] = (prefix << bits) | s_out[0];
-        st_krem[s] = target - s_out[1];
+// Few, large blocks per set: a popular bin receives one global atomic per block.
+template <class Src>
+__global__ __launch_bounds__(kHistBlock) void k_hist(Src src, SelState st) {
+    __shared__ uint32_t h[kHistBins];
+    const int s = blockIdx.y;
+    for (int b = threadIdx.x; b < kHistBins; b += kHistBlock) h[b] = 0u;
+    __syncthreads();
+    const bool dn = src.dense(s);
+    const uint32_t n = src.nphys(s, dn);
+    const uint32_t step = gridDim.x * kHistBlock;
+    for (uint64_t p = (uint64_t)blockIdx.x * kHistBlock + threadIdx.x; p < n; p += step) {
+        uint32_t idx, vb;
+        if (src.fetch(s, dn, (uint32_t)p, idx, vb)) atomicAdd(&h[(vb & kAbs) >> kLowBits], 1u);
     }
+    __syncthreads();
+    flush_hist(h, st.hist + (size_t)s * kHistBins);
 }
 
 // ---------------------------------------------------------------------------------
-// ordered emit: per-run counts -> exclusive scan over runs -> write
+// exact select, kernel 2: per group, count keys above the bucket, list keys inside it
 // ---------------------------------------------------------------------------------
 
-// One wave per run.
 template <class Src>
-__global__ __launch_bounds__(kBlock) void k_count(Src src, const uint32_t* __restrict__ st_T,
-                                                  uint32_t* __restrict__ run_gt,
-                                                  uint32_t* __restrict__ run_eq, uint32_t maxruns) {
+__global__ __launch_bounds__(kBlock) void k_bucket(Src src, SelState st, uint32_t k) {
+    __shared__ GroupSegs gs;
+    __shared__ uint32_t s_wave[kBlock / kWave];
+    __shared__ uint32_t s_out[3];
+    __shared__ uint32_t s_gt[kBlock / kWave];
+    __shared__ uint32_t s_in[kBlock / kWave];
+    __shared__ uint32_t s_base;
     const int s = blockIdx.y;
-    const uint32_t r = blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
+    const uint32_t g = blockIdx.x;
     const bool dn = src.dense(s);
-    if (r >= src.nruns(s, dn)) return;
-    const uint2 rn = src.run(s, dn, r);
-    const uint32_t T = st_T[s];
-    const uint32_t lane = lane_id();
-    uint32_t gt = 0, eq = 0;
-    for (uint32_t j0 = 0; j0 < rn.y; j0 += kWave) {
-        const uint32_t j = j0 + lane;
-        bool is_gt = false, is_eq = false;
-        if (j < rn.y) {
+    if (g >= src.ngroups(s, dn)) return;
+    // every block picks the bucket of the k-th key from the set's histogram
+    {
+        constexpr int kPer = kHistBins / kBlock;      // thread t owns 16 consecutive bins
+        const uint32_t* hist = st.hist + (size_t)s * kHistBins;
+        uint32_t loc[kPer];
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) loc[j] = hist[threadIdx.x * kPer + j];
+        suffix_pick<kPer>(loc, k, s_wave, s_out);
+    }
+    const uint32_t d1 = s_out[0];
+    if (g == 0 && threadIdx.x == 0) {
+        st.d1[s] = d1;
+        st.krem[s] = k - s_out[1];
+    }
+    const uint32_t total = load_group(src, s, dn, g, &gs);
+    const uint32_t wave = threadIdx.x / kWave;
+    uint32_t gt = 0, in = 0;     // wave-uniform
+    for (uint32_t i0 = 0; i0 < total; i0 += kBlock) {
+        const uint32_t i = i0 + threadIdx.x;
+        bool above = false, inside = false;
+        if (i < total) {
             uint32_t idx, vb;
-            if (src.fetch(s, dn, rn.x + j, idx, vb)) {
-                const uint32_t key = vb & kAbs;
-                is_gt = key > T;
-                is_eq = key == T;
+            if (src.fetch(s, dn, group_slot(&gs, i), idx, vb)) {
+                const uint32_t d = (vb & kAbs) >> kLowBits;
+                above = d > d1;
+                inside = d == d1;
             }
         }
-        gt += (uint32_t)__popcll(__ballot(is_gt));
-        eq += (uint32_t)__popcll(__ballot(is_eq));
+        gt += (uint32_t)__popcll(__ballot(above));
+        in += (uint32_t)__popcll(__ballot(inside));
     }
-    if (lane == 0) {
-        run_gt[(size_t)s * maxruns + r] = gt;
-        run_eq[(size_t)s * maxruns + r] = eq;
-    }
-}
-
-// One block of 1024 threads per set: exclusive scans of run_gt and run_eq over the runs.
-template <class Src>
-__global__ __launch_bounds__(1024) void k_scan_runs(Src src, const uint32_t* __restrict__ run_gt,
-                                                    const uint32_t* __restrict__ run_eq,
-                                                    uint32_t* __restrict__ off_gt,
-                                                    uint32_t* __restrict__ off_eq, uint32_t maxruns) {
-    __shared__ uint32_t s_g[1024];
-    __shared__ uint32_t s_e[1024];
-    __shared__ uint32_t s_carry[2];
-    const int s = blockIdx.x;
-    const uint32_t n = src.nruns(s, src.dense(s));
-    const int t = threadIdx.x;
-    if (t == 0) { s_carry[0] = 0; s_carry[1] = 0; }
+    if (lane_id() == 0) { s_gt[wave] = gt; s_in[wave] = in; }
     __syncthreads();
-    for (uint32_t base = 0; base < n; base += 1024) {
-        const uint32_t r = base + t;
-        const uint32_t g = r < n ? run_gt[(size_t)s * maxruns + r] : 0u;
-        const uint32_t e = r < n ? run_eq[(size_t)s * maxruns + r] : 0u;
-        s_g[t] = g;
-        s_e[t] = e;
-        __syncthreads();
-        // Hillis-Steele inclusive scan over 1024 entries
-        for (int d = 1; d < 1024; d <<= 1) {
-            uint32_t ag = 0, ae = 0;
-            if (t >= d) { ag = s_g[t - d]; ae = s_e[t - d]; }
-            __syncthreads();
-            s_g[t] += ag;
-            s_e[t] += ae;
-            __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t tg = 0, ti = 0;
+        for (int v = 0; v < kBlock / kWave; ++v) { tg += s_gt[v]; ti += s_in[v]; }
+        st.grp_gt[(size_t)s * st.maxgroups + g] = tg;
+        s_base = ti ? atomicAdd(&st.list_cnt[s], ti) : 0u;     // one reservation per block
+    }
+    __syncthreads();
+    if (in == 0) return;
+    // second walk: this wave's bucket entries go to its slice of the block's reservation
+    uint32_t off = s_base;
+    for (uint32_t v = 0; v < wave; ++v) off += s_in[v];
+    uint32_t* list = st.list + (size_t)s * st.list_cap;
+    for (uint32_t i0 = 0; i0 < total; i0 += kBlock) {
+        const uint32_t i = i0 + threadIdx.x;
+        bool inside = false;
+        uint32_t key = 0;
+        if (i < total) {
+            uint32_t idx, vb;
+            if (src.fetch(s, dn, group_slot(&gs, i), idx, vb)) {
+                key = vb & kAbs;
+                inside = (key >> kLowBits) == d1;
+            }
         }
-        const uint32_t cg = s_carry[0], ce = s_carry[1];
-        if (r < n) {
-            off_gt[(size_t)s * maxruns + r] = cg + s_g[t] - g;
-            off_eq[(size_t)s * maxruns + r] = ce + s_e[t] - e;
+        const uint64_t inm = __ballot(inside);
+        if (inside) {
+            const uint32_t pos = off + rank_in(inm);
+            if (pos < st.list_cap) list[pos] = (key & kLowMask) | (g << kLowBits);
         }
-        __syncthreads();
-        if (t == 1023) { s_carry[0] = cg + s_g[t]; s_carry[1] = ce + s_e[t]; }
-        __syncthreads();
+        off += (uint32_t)__popcll(inm);
     }
 }
 
-// One wave per run.  An entry is selected if key > T, or key == T and fewer than
-// `need` equal-key entries precede it in index order.  Its output slot is the
-// number of selected entries before it.  ZERO: also store +0.0 at its index in
-// the set's dense row (Algorithm 4 line 8).  DIVIDE: value / divisor (Eq. 3).
+// ---------------------------------------------------------------------------------
+// exact select, kernel 3: one block per set finishes the key and scans the groups
+// ---------------------------------------------------------------------------------
+
+template <class Src>
+__global__ __launch_bounds__(1024) void k_finish(Src src, SelState st) {
+    constexpr int kT = 1024;
+    __shared__ uint32_t h[kT];
+    __shared__ uint32_t g_gt[kMaxGroups];
+    __shared__ uint32_t g_eq[kMaxGroups];
+    __shared__ uint32_t s_wave[kT / kWave];
+    __shared__ uint32_t s_out[3];
+    __shared__ GroupSegs gs;
+    const int s = blockIdx.x;
+    const uint32_t t = threadIdx.x;
+    const bool dn = src.dense(s);
+    const uint32_t ng = src.ngroups(s, dn);
+    const uint32_t d1 = st.d1[s];
+    uint32_t krem = st.krem[s];
+    const uint32_t nlist = st.list_cnt[s];
+    const bool overflow = nlist > st.list_cap;       // the list is incomplete: read the set itself
+    const uint32_t* list = st.list + (size_t)s * st.list_cap;
+    const uint32_t nphys = src.nphys(s, dn);
+
+    // a short list is read once and kept in registers
+    constexpr int kCache = 8;
+    constexpr uint32_t kNone = 0xFFFFFFFFu;            // bit 31 is never set in a list entry
+    const bool cached = !overflow && nlist <= (uint32_t)(kCache * kT);
+    uint32_t ent[kCache];
+#pragma unroll
+    for (int j = 0; j < kCache; ++j) {
+        const uint32_t i = t + (uint32_t)j * kT;
+        ent[j] = (cached && i < nlist) ? list[i] : kNone;
+    }
+    auto for_each_entry = [&](auto&& f) {
+        if (cached) {
+#pragma unroll
+            for (int j = 0; j < kCache; ++j)
+                if (ent[j] != kNone) f(ent[j]);
+        } else {
+            for (uint32_t i = t; i < nlist; i += kT) f(list[i]);
+        }
+    };
+
+    // two radix passes over the low 19 bits of the keys inside bucket d1: bits 18..9, 8..0
+    uint32_t hi = 0;
+    for (int pass = 0; pass < 2; ++pass) {
+        h[t] = 0u;
+        __syncthreads();
+        if (!overflow) {
+            for_each_entry([&](uint32_t e) {
+                const uint32_t low = e & kLowMask;
+                if (pass == 0) atomicAdd(&h[low >> 9], 1u);
+                else if ((low >> 9) == hi) atomicAdd(&h[low & 511u], 1u);
+            });
+        } else {
+            for (uint64_t p = t; p < nphys; p += kT) {
+                uint32_t idx, vb;
+                if (src.fetch(s, dn, (uint32_t)p, idx, vb)) {
+                    const uint32_t key = vb & kAbs;
+                    if ((key >> kLowBits) == d1) {
+                        const uint32_t low = key & kLowMask;
+                        if (pass == 0) atomicAdd(&h[low >> 9], 1u);
+                        else if ((low >> 9) == hi) atomicAdd(&h[low & 511u], 1u);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        const uint32_t loc[1] = {h[t]};
+        suffix_pick<1>(loc, krem, s_wave, s_out);
+        if (pass == 0) hi = s_out[0];
+        krem -= s_out[1];
+    }
+    const uint32_t tlow = (hi << 9) | s_out[0];
+    const uint32_t T = (d1 << kLowBits) | tlow;
+    const uint32_t need = krem;
+
+    // per-group counts of selected-for-sure (key > T) and tied (key == T) entries
+    for (uint32_t g = t; g < ng; g += kT) {
+        g_gt[g] = overflow ? 0u : st.grp_gt[(size_t)s * st.maxgroups + g];
+        g_eq[g] = 0u;
+    }
+    __syncthreads();
+    if (!overflow) {
+        for_each_entry([&](uint32_t e) {
+            const uint32_t low = e & kLowMask, g = e >> kLowBits;
+            if (low > tlow) atomicAdd(&g_gt[g], 1u);
+            else if (low == tlow) atomicAdd(&g_eq[g], 1u);
+        });
+    } else {
+        for (uint32_t g = 0; g < ng; ++g) {
+            const uint32_t total = load_group(src, s, dn, g, &gs);
+            uint32_t cg = 0, ce = 0;
+            for (uint32_t i = t; i < total; i += kT) {
+                uint32_t idx, vb;
+                if (src.fetch(s, dn, group_slot(&gs, i), idx, vb)) {
+                    const uint32_t key = vb & kAbs;
+                    cg += key > T;
+                    ce += key == T;
+                }
+            }
+            if (cg) atomicAdd(&g_gt[g], cg);
+            if (ce) atomicAdd(&g_eq[g], ce);
+        }
+    }
+    __syncthreads();
+
+    // exclusive scans over the groups (ng <= 2048: two per thread)
+    {
+        const uint32_t g0 = 2 * t, g1 = 2 * t + 1;
+        const uint32_t a0 = g0 < ng ? g_gt[g0] : 0u, a1 = g1 < ng ? g_gt[g1] : 0u;
+        const uint32_t e0 = g0 < ng ? g_eq[g0] : 0u, e1 = g1 < ng ? g_eq[g1] : 0u;
+        uint32_t tot;
+        const uint32_t ia = block_incl_scan(a0 + a1, s_wave, tot);
+        const uint32_t ie = block_incl_scan(e0 + e1, s_wave, tot);
+        uint32_t* og = st.off_gt + (size_t)s * st.maxgroups;
+        uint32_t* oe = st.off_eq + (size_t)s * st.maxgroups;
+        if (g0 < ng) { og[g0] = ia - a0 - a1; oe[g0] = ie - e0 - e1; }
+        if (g1 < ng) { og[g1] = ia - a1; oe[g1] = ie - e1; }
+    }
+    // leave the per-set scratch clear for the next select that uses it
+    uint32_t* hg = st.hist + (size_t)s * kHistBins;
+    for (uint32_t b = t; b < (uint32_t)kHistBins; b += kT) hg[b] = 0u;
+    if (t == 0) {
+        st.T[s] = T;
+        st.need[s] = need;
+        st.list_cnt[s] = 0u;
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// exact select, kernel 4: ordered emit
+// ---------------------------------------------------------------------------------
+
+// One block per group.  An entry is selected if key > T, or key == T and fewer than
+// `need` equal-key entries precede it in index order; its output slot is the number of
+// selected entries before it.  ZERO: also store +0.0 at its index in the set's dense
+// row (Algorithm 4 line 8).  DIVIDE: value / divisor (Eq. 3).  gbits != NULL: also set
+// bit `index` of that bitmap (the dense gMask of Algorithm 3 lines 21-22, one bit per
+// gradient element).
 template <class Src, bool ZERO, bool DIVIDE>
 __global__ __launch_bounds__(kBlock) void k_emit(
-        Src src, const uint32_t* __restrict__ st_T, const uint32_t* __restrict__ st_need,
-        const uint32_t* __restrict__ off_gt, const uint32_t* __restrict__ off_eq, uint32_t maxruns,
-        uint32_t k, uint32_t* __restrict__ out_idx, float* __restrict__ out_val, int64_t out_stride,
-        float* __restrict__ row, int64_t row_stride, float divisor) {
+        Src src, SelState st, uint32_t k, uint32_t* __restrict__ out_idx,
+        float* __restrict__ out_val, int64_t out_stride, float* __restrict__ row,
+        int64_t row_stride, float divisor, uint32_t* __restrict__ gbits) {
+    __shared__ GroupSegs gs;
+    __shared__ uint32_t s_eq[kBlock / kWave];
+    __shared__ uint32_t s_sel[kBlock / kWave];
     const int s = blockIdx.y;
-    const uint32_t r = blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
+    const uint32_t g = blockIdx.x;
     const bool dn = src.dense(s);
-    if (r >= src.nruns(s, dn)) return;
-    const uint2 rn = src.run(s, dn, r);
-    const uint32_t T = st_T[s], need = st_need[s];
-    const uint32_t lane = lane_id();
-    uint32_t eq_before = off_eq[(size_t)s * maxruns + r];
-    uint32_t outp = off_gt[(size_t)s * maxruns + r] + (eq_before < need ? eq_before : need);
-    for (uint32_t j0 = 0; j0 < rn.y; j0 += kWave) {
-        const uint32_t j = j0 + lane;
+    if (g >= src.ngroups(s, dn)) return;
+    const uint32_t T = st.T[s], need = st.need[s];
+    uint32_t eq_before = st.off_eq[(size_t)s * st.maxgroups + g];
+    uint32_t outp = st.off_gt[(size_t)s * st.maxgroups + g] + (eq_before < need ? eq_before : need);
+    const uint32_t total = load_group(src, s, dn, g, &gs);
+    const uint32_t wave = threadIdx.x / kWave;
+    for (uint32_t i0 = 0; i0 < total; i0 += kBlock) {
+        const uint32_t i = i0 + threadIdx.x;
         bool is_gt = false, is_eq = false;
         uint32_t idx = 0, vb = 0;
-        if (j < rn.y) {
-            if (src.fetch(s, dn, rn.x + j, idx, vb)) {
+        if (i < total) {
+            if (src.fetch(s, dn, group_slot(&gs, i), idx, vb)) {
                 const uint32_t key = vb & kAbs;
                 is_gt = key > T;
                 is_eq = key == T;
             }
         }
         const uint64_t eqm = __ballot(is_eq);
-        const bool sel = is_gt || (is_eq && (eq_before + rank_in(eqm) < need));
+        __syncthreads();                  // the previous step's s_eq / s_sel are no longer read
+        if (lane_id() == 0) s_eq[wave] = (uint32_t)__popcll(eqm);
+        __syncthreads();
+        uint32_t eq_base = eq_before, eq_all = 0;
+        for (uint32_t v = 0; v < kBlock / kWave; ++v) {
+            if (v < wave) eq_base += s_eq[v];
+            eq_all += s_eq[v];
+        }
+        const bool sel = is_gt || (is_eq && (eq_base + rank_in(eqm) < need));
         const uint64_t selm = __ballot(sel);
+        if (lane_id() == 0) s_sel[wave] = (uint32_t)__popcll(selm);
+        __syncthreads();
+        uint32_t sel_base = outp, sel_all = 0;
+        for (uint32_t v = 0; v < kBlock / kWave; ++v) {
+            if (v < wave) sel_base += s_sel[v];
+            sel_all += s_sel[v];
+        }
         if (sel) {
-            const uint32_t pos = outp + rank_in(selm);
+            const uint32_t pos = sel_base + rank_in(selm);
             if (pos < k) {      // always true when the select state is consistent
                 out_idx[(int64_t)s * out_stride + pos] = idx;
                 float v = __uint_as_float(vb);
@@ -493,9 +749,10 @@ __global__ __launch_bounds__(kBlock) void k_emit(
                 out_val[(int64_t)s * out_stride + pos] = v;
             }
             if (ZERO) row[(int64_t)s * row_stride + idx] = 0.0f;
+            if (gbits) atomicOr(&gbits[idx >> 5], 1u << (idx & 31));
         }
-        outp += (uint32_t)__popcll(selm);
-        eq_before += (uint32_t)__popcll(eqm);
+        outp += sel_all;
+        eq_before += eq_all;
     }
 }
 
@@ -503,29 +760,10 @@ __global__ __launch_bounds__(kBlock) void k_emit(
 // merge: index-ordered union of two k-sets into 2k slots
 // ---------------------------------------------------------------------------------
 
-// first position p in [0, n) with a[p] >= x (n if none)
-__device__ __forceinline__ uint32_t lower_bound(const uint32_t* a, uint32_t n, uint32_t x) {
-    uint32_t lo = 0, hi = n;
-    while (lo < hi) {
-        const uint32_t mid = (lo + hi) >> 1;
-        if (a[mid] < x) lo = mid + 1; else hi = mid;
-    }
-    return lo;
-}
-// first position p in [0, n) with a[p] > x (n if none)
-__device__ __forceinline__ uint32_t upper_bound(const uint32_t* a, uint32_t n, uint32_t x) {
-    uint32_t lo = 0, hi = n;
-    while (lo < hi) {
-        const uint32_t mid = (lo + hi) >> 1;
-        if (a[mid] <= x) lo = mid + 1; else hi = mid;
-    }
-    return lo;
-}
-
 // Entry x of A goes to slot x + #{B < A[x]}, entry y of B to slot y + #{A <= B[y]}:
 // a bijection onto [0, 2k) that lists the union in index order, A's copy first
 // where both hold an index.  A's copy then carries the sum (one fp32 add) and B's
-// slot becomes a tombstone.
+// slot becomes a tombstone.  Both binary searches advance in the same loop.
 __global__ __launch_bounds__(kBlock) void k_union(
         const uint32_t* __restrict__ a_idx, const float* __restrict__ a_val,
         const uint32_t* __restrict__ b_idx, const float* __restrict__ b_val, uint32_t k,
@@ -539,31 +777,38 @@ __global__ __launch_bounds__(kBlock) void k_union(
     const float* bv = b_val + (int64_t)s * in_stride;
     uint32_t* mi = m_idx + (size_t)s * 2 * k;
     float* mv = m_val + (size_t)s * 2 * k;
-    {
-        const uint32_t i = ai[x];
-        const uint32_t p = lower_bound(bi, k, i);
-        float v = av[x];
-        if (p < k && bi[p] == i) v = v + bv[p];
-        mi[x + p] = i;
-        mv[x + p] = v;
+    const uint32_t ia = ai[x], ib = bi[x];
+    // lo_a -> #{B < ia} (lower bound), lo_b -> #{A <= ib} (upper bound)
+    uint32_t lo_a = 0, hi_a = k, lo_b = 0, hi_b = k;
+    while (lo_a < hi_a || lo_b < hi_b) {
+        if (lo_a < hi_a) {
+            const uint32_t mid = (lo_a + hi_a) >> 1;
+            if (bi[mid] < ia) lo_a = mid + 1; else hi_a = mid;
+        }
+        if (lo_b < hi_b) {
+            const uint32_t mid = (lo_b + hi_b) >> 1;
+            if (ai[mid] <= ib) lo_b = mid + 1; else hi_b = mid;
+        }
     }
-    {
-        const uint32_t i = bi[x];
-        const uint32_t p = upper_bound(ai, k, i);
-        const bool dup = p > 0 && ai[p - 1] == i;
-        mi[x + p] = dup ? kTomb : i;
-        mv[x + p] = bv[x];
-    }
+    float va = av[x];
+    if (lo_a < k && bi[lo_a] == ia) va = va + bv[lo_a];
+    mi[x + lo_a] = ia;
+    mv[x + lo_a] = va;
+    const bool dup = lo_b > 0 && ai[lo_b - 1] == ib;
+    mi[x + lo_b] = dup ? kTomb : ib;
+    mv[x + lo_b] = bv[x];
 }
 
 // P == 1: the tree has no round; the global set is worker 0's set divided by 1.
 __global__ void k_copy_set(const uint32_t* __restrict__ in_idx, const float* __restrict__ in_val,
                            uint32_t k, uint32_t* __restrict__ out_idx, float* __restrict__ out_val,
-                           float divisor) {
+                           float divisor, uint32_t* __restrict__ gbits) {
     const uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t < k) {
-        out_idx[t] = in_idx[t];
+        const uint32_t i = in_idx[t];
+        out_idx[t] = i;
         out_val[t] = in_val[t] / divisor;
+        if (gbits) atomicOr(&gbits[i >> 5], 1u << (i & 31));
     }
 }
 
@@ -571,6 +816,17 @@ __global__ void k_copy_set(const uint32_t* __restrict__ in_idx, const float* __r
 // residual restore (Algorithm 4 line 10)
 // ---------------------------------------------------------------------------------
 
+__device__ __forceinline__ bool contains(const uint32_t* a, uint32_t n, uint32_t x) {
+    uint32_t lo = 0, hi = n;
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (a[mid] < x) lo = mid + 1; else hi = mid;
+    }
+    return lo < n && a[lo] == x;
+}
+
+// The literal form: the slots were zeroed by the local selection; add the value back
+// where the index is not in the global set.
 __global__ __launch_bounds__(kBlock) void k_restore(
         float* __restrict__ res, int64_t stride, uint32_t k, const uint32_t* __restrict__ loc_idx,
         const float* __restrict__ loc_val, const uint32_t* __restrict__ g_idx) {
@@ -578,10 +834,26 @@ __global__ __launch_bounds__(kBlock) void k_restore(
     const uint32_t t = blockIdx.x * kBlock + threadIdx.x;
     if (t >= k) return;
     const uint32_t i = loc_idx[(size_t)w * k + t];
-    const uint32_t p = lower_bound(g_idx, k, i);
-    if (p < k && g_idx[p] == i) return;          // index is in the global set: stays zero
+    if (contains(g_idx, k, i)) return;          // index is in the global set: stays zero
     float* slot = res + (int64_t)w * stride + i;
     *slot = *slot + loc_val[(size_t)w * k + t];
+}
+
+// The fused form used by gtopk_step, where the local selection did NOT zero its entries
+// (the row still holds acc there).  Zero-then-add-back leaves acc unchanged except that
+// +0.0 + (-0.0) = +0.0, so: an entry whose index is in the global set becomes +0.0, an
+// entry that is -0.0 becomes +0.0, every other entry is already what the literal form
+// produces.  gbits is the one-bit-per-element mask of the global set.
+__global__ __launch_bounds__(kBlock) void k_restore_fused(
+        float* __restrict__ res, int64_t stride, uint32_t k, const uint32_t* __restrict__ loc_idx,
+        const float* __restrict__ loc_val, const uint32_t* __restrict__ gbits) {
+    const int w = blockIdx.y;
+    const uint32_t t = blockIdx.x * kBlock + threadIdx.x;
+    if (t >= k) return;
+    const uint32_t i = loc_idx[(size_t)w * k + t];
+    const uint32_t vb = __float_as_uint(loc_val[(size_t)w * k + t]);
+    const bool in_g = (gbits[i >> 5] >> (i & 31)) & 1u;
+    if (in_g || vb == 0x80000000u) res[(int64_t)w * stride + i] = 0.0f;
 }
 
 // ---------------------------------------------------------------------------------
@@ -593,17 +865,6 @@ inline uint32_t ceil_div(uint64_t a, uint64_t b) { return (uint32_t)((a + b - 1)
 inline bool is_pow2(int64_t x) { return x > 0 && (x & (x - 1)) == 0; }
 inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
-struct SelectWs {          // scratch of the exact select, for up to `sets` sets
-    uint32_t* hist;        // [sets][4096]
-    uint32_t* st_prefix;   // [sets]  -> T after the third pass
-    uint32_t* st_krem;     // [sets]  -> number of key == T entries to take
-    uint32_t* run_gt;      // [sets][maxruns]
-    uint32_t* run_eq;
-    uint32_t* off_gt;
-    uint32_t* off_eq;
-    uint32_t maxruns;
-};
-
 struct Carver {
     char* base;
     size_t off = 0;
@@ -614,29 +875,45 @@ struct Carver {
     }
 };
 
-SelectWs carve_select(Carver& c, size_t sets, uint32_t maxruns) {
-    SelectWs s;
+// hist and list_cnt are carved back to back so that one clear covers them
+SelState carve_select(Carver& c, size_t sets, uint32_t list_cap, uint32_t maxgroups) {
+    SelState s;
     s.hist = c.take<uint32_t>(sets * kHistBins);
-    s.st_prefix = c.take<uint32_t>(sets);
-    s.st_krem = c.take<uint32_t>(sets);
-    s.run_gt = c.take<uint32_t>(sets * maxruns);
-    s.run_eq = c.take<uint32_t>(sets * maxruns);
-    s.off_gt = c.take<uint32_t>(sets * maxruns);
-    s.off_eq = c.take<uint32_t>(sets * maxruns);
-    s.maxruns = maxruns;
+    s.list_cnt = c.take<uint32_t>(sets);
+    s.d1 = c.take<uint32_t>(sets);
+    s.krem = c.take<uint32_t>(sets);
+    s.T = c.take<uint32_t>(sets);
+    s.need = c.take<uint32_t>(sets);
+    s.list = c.take<uint32_t>(sets * list_cap);
+    s.grp_gt = c.take<uint32_t>(sets * maxgroups);
+    s.off_gt = c.take<uint32_t>(sets * maxgroups);
+    s.off_eq = c.take<uint32_t>(sets * maxgroups);
+    s.list_cap = list_cap;
+    s.maxgroups = maxgroups;
     return s;
+}
+// words from s.hist to the end of s.list_cnt (padding included)
+inline size_t select_clear_words(const SelState& s) { return (size_t)(s.d1 - s.hist); }
+
+// slots per group of a merged array of 2k slots: at least 1024, at most 2048 groups
+uint32_t merged_group_slots(uint32_t k) {
+    uint32_t L = ceil_div(2ull * k, kMaxGroups);
+    L = (L + 255u) & ~255u;
+    return L < 1024u ? 1024u : L;
 }
 
 struct MergeWs {
-    SelectWs sel;
+    SelState sel;
     uint32_t* m_idx;   // [pairs][2k]
     float* m_val;
+    uint32_t L;
     size_t bytes;
 };
 
 MergeWs carve_merge(Carver& c, uint32_t k, size_t pairs) {
     MergeWs w;
-    w.sel = carve_select(c, pairs, ceil_div(2ull * k, kMergeRun));
+    w.L = merged_group_slots(k);
+    w.sel = carve_select(c, pairs, 2 * k, ceil_div(2ull * k, w.L));
     w.m_idx = c.take<uint32_t>(pairs * 2 * k);
     w.m_val = c.take<float>(pairs * 2 * k);
     w.bytes = c.off;
@@ -645,14 +922,14 @@ MergeWs carve_merge(Carver& c, uint32_t k, size_t pairs) {
 
 struct StepWs {
     // local select
-    uint32_t* samp_hist;   // [P][16384]
-    uint32_t* cand_count;  // [P]      (kept right behind samp_hist: one clear covers both)
+    uint32_t* samp_hist;   // [P][16384]   } cleared together
+    uint32_t* cand_count;  // [P]          }
     uint32_t* tspec;       // [P]
     uint32_t* cand_idx;    // [P][cap]
     float* cand_val;
     uint2* run_table;      // [P][nchunks]
-    SelectWs sel;          // [P] sets, maxruns = nchunks
-    uint32_t cap, nchunks;
+    SelState sel;          // P sets
+    uint32_t cap, nchunks, G;
     // tree
     MergeWs mrg;           // P/2 pairs
     uint32_t* x_idx;       // [P/2][k] ping
@@ -660,6 +937,8 @@ struct StepWs {
     uint32_t* y_idx;       // [P/4][k] pong
     float* y_val;
     // step
+    uint32_t* gbits;       // [ceil(m/32)] one bit per gradient element: the global set
+    size_t gbits_words;
     uint32_t* loc_idx;     // [P][k] when the caller does not want them
     float* loc_val;
     size_t bytes;
@@ -676,13 +955,15 @@ StepWs carve_step(void* ws, int64_t m, uint32_t k, uint32_t P) {
     StepWs s;
     s.cap = cand_capacity(m, k);
     s.nchunks = ceil_div((uint64_t)m, kChunk);
+    s.G = ceil_div(s.nchunks, kMaxGroups);
+    if (s.G < 16) s.G = 16;                       // <= 32 = kMaxSeg because m <= 2^31
     s.samp_hist = c.take<uint32_t>((size_t)P * kSampleBins);
     s.cand_count = c.take<uint32_t>(P);
     s.tspec = c.take<uint32_t>(P);
     s.cand_idx = c.take<uint32_t>((size_t)P * s.cap);
     s.cand_val = c.take<float>((size_t)P * s.cap);
     s.run_table = c.take<uint2>((size_t)P * s.nchunks);
-    s.sel = carve_select(c, P, s.nchunks);
+    s.sel = carve_select(c, P, s.cap, ceil_div(s.nchunks, s.G));
     const size_t pairs = P > 1 ? P / 2 : 1;
     s.mrg = carve_merge(c, k, pairs);
     s.x_idx = c.take<uint32_t>(pairs * k);
@@ -690,6 +971,8 @@ StepWs carve_step(void* ws, int64_t m, uint32_t k, uint32_t P) {
     const size_t quarter = P > 3 ? P / 4 : 1;
     s.y_idx = c.take<uint32_t>(quarter * k);
     s.y_val = c.take<float>(quarter * k);
+    s.gbits_words = (size_t)((m + 31) / 32);
+    s.gbits = c.take<uint32_t>(s.gbits_words);
     s.loc_idx = c.take<uint32_t>((size_t)P * k);
     s.loc_val = c.take<float>((size_t)P * k);
     s.bytes = c.off;
@@ -702,34 +985,35 @@ bool sizes_ok(int64_t m, int64_t k, int64_t P) {
 
 int launch_status() { return hipGetLastError() == hipSuccess ? GTOPK_OK : GTOPK_EHIP; }
 
-void zero_async(hipStream_t st, uint32_t* p0, size_t n0, uint32_t* p1 = nullptr, size_t n1 = 0,
-                uint32_t* p2 = nullptr, size_t n2 = 0) {
-    size_t n = n0 > n1 ? n0 : n1;
-    if (n2 > n) n = n2;
-    uint32_t blocks = (uint32_t)((n + 1023) / 1024 > 1024 ? 1024 : (n + 1023) / 1024);
-    hipLaunchKernelGGL(k_zero_u32, dim3(blocks ? blocks : 1), dim3(256), 0, st, p0, n0, p1, n1, p2, n2);
+// Instrumentation: events the next gtopk_step records at its stage boundaries.
+hipEvent_t g_stage_events[GTOPK_STAGE_EVENTS];
+bool g_stage_armed = false;
+
+void mark_stage(int i, bool armed, hipStream_t st) {
+    if (armed) (void)hipEventRecord(g_stage_events[i], st);
 }
 
-// exact select + ordered emit over `sets` sets of a source
+void zero_async(hipStream_t st, uint32_t* p0, size_t n0, uint32_t* p1 = nullptr, size_t n1 = 0,
+                uint32_t* p2 = nullptr, size_t n2 = 0, uint32_t* p3 = nullptr, size_t n3 = 0) {
+    ZeroJob job{{p0, p1, p2, p3}, {n0, n1, n2, n3}};
+    size_t n = 0;
+    for (int a = 0; a < 4; ++a) n = job.n[a] > n ? job.n[a] : n;
+    uint32_t blocks = (uint32_t)((n + 1023) / 1024 > 1024 ? 1024 : (n + 1023) / 1024);
+    hipLaunchKernelGGL(k_zero_u32, dim3(blocks ? blocks : 1), dim3(256), 0, st, job);
+}
+
+// histogram + bucket + finish + emit over `sets` sets of at most nphys_max slots each
 template <class Src, bool ZERO, bool DIVIDE>
-void run_select(const Src& src, const SelectWs& ws, uint32_t sets, uint32_t k, uint32_t hist_blocks,
+void run_select(const Src& src, const SelState& ss, uint32_t sets, uint32_t k, uint64_t nphys_max,
                 uint32_t* out_idx, float* out_val, int64_t out_stride, float* row,
-                int64_t row_stride, float divisor, hipStream_t st) {
-    for (int pass = 0; pass < 3; ++pass) {
-        hipLaunchKernelGGL((k_hist<Src>), dim3(hist_blocks, sets), dim3(kBlock), 0, st, src, pass,
-                           ws.hist, ws.st_prefix);
-        const int nbins = pass == 2 ? 128 : kHistBins;
-        hipLaunchKernelGGL(k_pick, dim3(sets), dim3(nbins < kBlock ? nbins : kBlock), 0, st, ws.hist,
-                           pass, k, ws.st_prefix, ws.st_krem);
-    }
-    const uint32_t run_blocks = ceil_div(ws.maxruns, kBlock / kWave);
-    hipLaunchKernelGGL((k_count<Src>), dim3(run_blocks, sets), dim3(kBlock), 0, st, src,
-                       ws.st_prefix, ws.run_gt, ws.run_eq, ws.maxruns);
-    hipLaunchKernelGGL((k_scan_runs<Src>), dim3(sets), dim3(1024), 0, st, src, ws.run_gt, ws.run_eq,
-                       ws.off_gt, ws.off_eq, ws.maxruns);
-    hipLaunchKernelGGL((k_emit<Src, ZERO, DIVIDE>), dim3(run_blocks, sets), dim3(kBlock), 0, st, src,
-                       ws.st_prefix, ws.st_krem, ws.off_gt, ws.off_eq, ws.maxruns, k, out_idx,
-                       out_val, out_stride, row, row_stride, divisor);
+                int64_t row_stride, float divisor, uint32_t* gbits, hipStream_t st) {
+    uint32_t hb = ceil_div(nphys_max, 4 * kHistBlock);
+    hb = hb < 1 ? 1 : (hb > 32 ? 32 : hb);
+    hipLaunchKernelGGL((k_hist<Src>), dim3(hb, sets), dim3(kHistBlock), 0, st, src, ss);
+    hipLaunchKernelGGL((k_bucket<Src>), dim3(ss.maxgroups, sets), dim3(kBlock), 0, st, src, ss, k);
+    hipLaunchKernelGGL((k_finish<Src>), dim3(sets), dim3(1024), 0, st, src, ss);
+    hipLaunchKernelGGL((k_emit<Src, ZERO, DIVIDE>), dim3(ss.maxgroups, sets), dim3(kBlock), 0, st, src,
+                       ss, k, out_idx, out_val, out_stride, row, row_stride, divisor, gbits);
 }
 
 // Sample plan for the speculative threshold: tiles of 256 contiguous elements,
@@ -766,61 +1050,71 @@ SamplePlan plan_sample(int64_t m, uint32_t k) {
     return p;
 }
 
+// `zero_rows`: store +0.0 at the selected entries (the stand-alone call); gtopk_step
+// passes false and settles the rows in k_restore_fused.  `pre_cleared`: the caller has
+// already cleared this call's counters and histograms.
 int do_local_select(const float* grad, float* residual, int64_t m, int64_t stride, uint32_t P,
-                    uint32_t k, uint32_t* out_idx, float* out_val, const StepWs& w, hipStream_t st) {
-    // clear the sample histograms, the candidate counters and the select histograms
-    zero_async(st, w.samp_hist, (size_t)P * kSampleBins, w.cand_count, P, w.sel.hist,
-               (size_t)P * kHistBins);
+                    uint32_t k, uint32_t* out_idx, float* out_val, const StepWs& w, bool zero_rows,
+                    bool pre_cleared, hipStream_t st, bool armed = false) {
+    if (!pre_cleared)
+        zero_async(st, w.samp_hist, (size_t)(w.tspec - w.samp_hist), w.sel.hist,
+                   select_clear_words(w.sel));
 
     const SamplePlan sp = plan_sample(m, k);
-    const uint32_t sblocks = sp.n_tiles < 64 ? sp.n_tiles : 64;
-    hipLaunchKernelGGL(k_sample_hist, dim3(sblocks, P), dim3(kBlock), 0, st, grad, residual,
+    uint32_t sblocks = ceil_div(sp.n_tiles, (kSampleBlock / kSampleTile) * 8);
+    if (sblocks > 16) sblocks = 16;
+    if (sblocks < 1) sblocks = 1;
+    hipLaunchKernelGGL(k_sample, dim3(sblocks, P), dim3(kSampleBlock), 0, st, grad, residual,
                        (uint32_t)m, stride, sp.tile_stride, sp.n_tiles, w.samp_hist);
-    hipLaunchKernelGGL(k_sample_pick, dim3(P), dim3(1024), 0, st, w.samp_hist, sp.target, w.tspec);
+    hipLaunchKernelGGL(k_sample_pick, dim3(P), dim3(kSampleBlock), 0, st, w.samp_hist, sp.target,
+                       w.tspec);
+    mark_stage(1, armed, st);
 
     const bool vec = (stride % 4 == 0);
     if (vec)
-        hipLaunchKernelGGL((k_accum_filter<true>), dim3(w.nchunks, P), dim3(kBlock), 0, st, grad,
+        hipLaunchKernelGGL((k_accum_filter<true>), dim3(w.nchunks, P), dim3(kSBlock), 0, st, grad,
                            residual, (uint32_t)m, stride, w.tspec, w.cand_idx, w.cand_val, w.cap,
                            w.cand_count, w.run_table, w.nchunks);
     else
-        hipLaunchKernelGGL((k_accum_filter<false>), dim3(w.nchunks, P), dim3(kBlock), 0, st, grad,
+        hipLaunchKernelGGL((k_accum_filter<false>), dim3(w.nchunks, P), dim3(kSBlock), 0, st, grad,
                            residual, (uint32_t)m, stride, w.tspec, w.cand_idx, w.cand_val, w.cap,
                            w.cand_count, w.run_table, w.nchunks);
+    mark_stage(2, armed, st);
 
-    CandSrc src{residual, stride, (uint32_t)m, k, w.cap, w.nchunks,
+    CandSrc src{residual, stride, (uint32_t)m, k, w.cap, w.nchunks, w.G,
                 w.cand_idx, w.cand_val, w.cand_count, w.run_table};
-    uint32_t hb = ceil_div(w.cap, 2048);
-    if (hb > 128) hb = 128;
-    run_select<CandSrc, true, false>(src, w.sel, P, k, hb, out_idx, out_val, (int64_t)k, residual,
-                                     stride, 1.0f, st);
+    if (zero_rows)
+        run_select<CandSrc, true, false>(src, w.sel, P, k, w.cap, out_idx, out_val, (int64_t)k,
+                                         residual, stride, 1.0f, nullptr, st);
+    else
+        run_select<CandSrc, false, false>(src, w.sel, P, k, w.cap, out_idx, out_val, (int64_t)k,
+                                          residual, stride, 1.0f, nullptr, st);
     return launch_status();
 }
 
-// one batch of merges: union + exact select + ordered emit
+// one batch of merges: union + exact select + ordered emit.
+// w.sel's hist and list_cnt must be clear on entry and are left clear.
 template <bool DIVIDE>
 void do_merge_batch(const uint32_t* a_idx, const float* a_val, const uint32_t* b_idx,
                     const float* b_val, uint32_t k, uint32_t batch, int64_t in_stride,
                     uint32_t* out_idx, float* out_val, int64_t out_stride, const MergeWs& w,
-                    float divisor, hipStream_t st) {
+                    float divisor, uint32_t* gbits, hipStream_t st) {
     hipLaunchKernelGGL(k_union, dim3(ceil_div(k, kBlock), batch), dim3(kBlock), 0, st, a_idx, a_val,
                        b_idx, b_val, k, in_stride, w.m_idx, w.m_val);
-    MergedSrc src{w.m_idx, w.m_val, 2 * k};
-    uint32_t hb = ceil_div(2ull * k, 2048);
-    if (hb > 128) hb = 128;
-    run_select<MergedSrc, false, DIVIDE>(src, w.sel, batch, k, hb, out_idx, out_val, out_stride,
-                                         nullptr, 0, divisor, st);
+    MergedSrc src{w.m_idx, w.m_val, 2 * k, w.L};
+    run_select<MergedSrc, false, DIVIDE>(src, w.sel, batch, k, 2ull * k, out_idx, out_val, out_stride,
+                                         nullptr, 0, divisor, gbits, st);
 }
 
 int do_tree(const uint32_t* loc_idx, const float* loc_val, uint32_t P, uint32_t k, uint32_t* g_idx,
-            float* g_val, const StepWs& w, hipStream_t st) {
+            float* g_val, const StepWs& w, uint32_t* gbits, bool pre_cleared, hipStream_t st) {
     const float divisor = (float)P;
     if (P == 1) {
         hipLaunchKernelGGL(k_copy_set, dim3(ceil_div(k, 256)), dim3(256), 0, st, loc_idx, loc_val, k,
-                           g_idx, g_val, divisor);
+                           g_idx, g_val, divisor, gbits);
         return launch_status();
     }
-    zero_async(st, w.mrg.sel.hist, (size_t)(P / 2) * kHistBins);
+    if (!pre_cleared) zero_async(st, w.mrg.sel.hist, select_clear_words(w.mrg.sel));
     // After every round the surviving sets are stored compactly, so round j always
     // merges set 2p with set 2p+1 of its input: exactly worker p*2^(j+1) with worker
     // p*2^(j+1) + 2^j of the original numbering.
@@ -832,22 +1126,15 @@ int do_tree(const uint32_t* loc_idx, const float* loc_val, uint32_t P, uint32_t 
         const bool last = pairs == 1;
         if (last) {
             do_merge_batch<true>(in_idx, in_val, in_idx + k, in_val + k, k, 1, 2 * (int64_t)k, g_idx,
-                                 g_val, k, w.mrg, divisor, st);
+                                 g_val, k, w.mrg, divisor, gbits, st);
         } else {
             do_merge_batch<false>(in_idx, in_val, in_idx + k, in_val + k, k, pairs, 2 * (int64_t)k,
-                                  ping_i, ping_v, k, w.mrg, 1.0f, st);
+                                  ping_i, ping_v, k, w.mrg, 1.0f, nullptr, st);
             in_idx = ping_i; in_val = ping_v;
             uint32_t* ti = ping_i; ping_i = pong_i; pong_i = ti;
             float* tv = ping_v; ping_v = pong_v; pong_v = tv;
         }
     }
-    return launch_status();
-}
-
-int do_restore(float* residual, int64_t stride, uint32_t P, uint32_t k, const uint32_t* loc_idx,
-               const float* loc_val, const uint32_t* g_idx, hipStream_t st) {
-    hipLaunchKernelGGL(k_restore, dim3(ceil_div(k, kBlock), P), dim3(kBlock), 0, st, residual, stride,
-                       k, loc_idx, loc_val, g_idx);
     return launch_status();
 }
 
@@ -888,7 +1175,7 @@ int gtopk_local_select(const float* grad, float* residual, int64_t m, int64_t st
     const StepWs w = carve_step(ws, m, (uint32_t)k, (uint32_t)P);
     if (ws_bytes < w.bytes) return GTOPK_EWORKSPACE;
     return do_local_select(grad, residual, m, stride, (uint32_t)P, (uint32_t)k, out_idx, out_val, w,
-                           (hipStream_t)stream);
+                           true, false, (hipStream_t)stream);
 }
 
 int gtopk_merge(const uint32_t* a_idx, const float* a_val, const uint32_t* b_idx, const float* b_val,
@@ -903,9 +1190,9 @@ int gtopk_merge(const uint32_t* a_idx, const float* a_val, const uint32_t* b_idx
     const MergeWs w = carve_merge(c, (uint32_t)k, (size_t)batch);
     if (ws_bytes < w.bytes) return GTOPK_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    zero_async(st, w.sel.hist, (size_t)batch * kHistBins);
+    zero_async(st, w.sel.hist, select_clear_words(w.sel));
     do_merge_batch<false>(a_idx, a_val, b_idx, b_val, (uint32_t)k, (uint32_t)batch, in_stride,
-                          out_idx, out_val, out_stride, w, 1.0f, st);
+                          out_idx, out_val, out_stride, w, 1.0f, nullptr, st);
     return launch_status();
 }
 
@@ -919,7 +1206,8 @@ int gtopk_tree(const uint32_t* loc_idx, const float* loc_val, int32_t P, int32_t
     // the tree's scratch sits inside the step workspace; m only sizes the parts it does not use
     const StepWs w = carve_step(ws, (int64_t)k, (uint32_t)k, (uint32_t)P);
     if (ws_bytes < w.bytes) return GTOPK_EWORKSPACE;
-    return do_tree(loc_idx, loc_val, (uint32_t)P, (uint32_t)k, g_idx, g_val, w, (hipStream_t)stream);
+    return do_tree(loc_idx, loc_val, (uint32_t)P, (uint32_t)k, g_idx, g_val, w, nullptr, false,
+                   (hipStream_t)stream);
 }
 
 int gtopk_residual_restore(float* residual, int64_t m, int64_t stride, int32_t P, int32_t k,
@@ -929,8 +1217,9 @@ int gtopk_residual_restore(float* residual, int64_t m, int64_t stride, int32_t P
     if (!sizes_ok(m, k, P) || stride < m) return GTOPK_EINVAL;
     if (!aligned16(residual) || !aligned16(loc_idx) || !aligned16(loc_val) || !aligned16(g_idx))
         return GTOPK_EALIGN;
-    return do_restore(residual, stride, (uint32_t)P, (uint32_t)k, loc_idx, loc_val, g_idx,
-                      (hipStream_t)stream);
+    hipLaunchKernelGGL(k_restore, dim3(ceil_div((uint32_t)k, kBlock), (uint32_t)P), dim3(kBlock), 0,
+                       (hipStream_t)stream, residual, stride, (uint32_t)k, loc_idx, loc_val, g_idx);
+    return launch_status();
 }
 
 int gtopk_step(const float* grad, float* residual, int64_t m, int64_t stride, int32_t P, int32_t k,
@@ -947,11 +1236,47 @@ int gtopk_step(const float* grad, float* residual, int64_t m, int64_t stride, in
     hipStream_t st = (hipStream_t)stream;
     uint32_t* li = loc_idx ? loc_idx : w.loc_idx;
     float* lv = loc_val ? loc_val : w.loc_val;
-    int rc = do_local_select(grad, residual, m, stride, (uint32_t)P, (uint32_t)k, li, lv, w, st);
+    const bool armed = g_stage_armed;
+    g_stage_armed = false;
+    mark_stage(0, armed, st);
+    // one clear for everything this step needs zeroed: the sampler's histograms and the
+    // candidate counters; both selects' histograms and tickets; the global-set bitmap
+    zero_async(st, w.samp_hist, (size_t)(w.tspec - w.samp_hist), w.sel.hist,
+               select_clear_words(w.sel), w.mrg.sel.hist, select_clear_words(w.mrg.sel), w.gbits,
+               w.gbits_words);
+    int rc = do_local_select(grad, residual, m, stride, (uint32_t)P, (uint32_t)k, li, lv, w, false,
+                             true, st, armed);
     if (rc != GTOPK_OK) return rc;
-    rc = do_tree(li, lv, (uint32_t)P, (uint32_t)k, g_idx, g_val, w, st);
+    mark_stage(3, armed, st);
+    rc = do_tree(li, lv, (uint32_t)P, (uint32_t)k, g_idx, g_val, w, w.gbits, true, st);
     if (rc != GTOPK_OK) return rc;
-    return do_restore(residual, stride, (uint32_t)P, (uint32_t)k, li, lv, g_idx, st);
+    mark_stage(4, armed, st);
+    hipLaunchKernelGGL(k_restore_fused, dim3(ceil_div((uint32_t)k, kBlock), (uint32_t)P), dim3(kBlock),
+                       0, st, residual, stride, (uint32_t)k, li, lv, w.gbits);
+    rc = launch_status();
+    mark_stage(5, armed, st);
+    return rc;
+}
+
+int gtopk_debug_candidate_counts(const void* ws, int64_t m, int32_t k, int32_t P,
+                                 uint32_t* host_counts, uint32_t* host_capacity) {
+    if (!ws || !host_counts || !host_capacity || !sizes_ok(m, k, P)) return GTOPK_EINVAL;
+    const StepWs w = carve_step(const_cast<void*>(ws), m, (uint32_t)k, (uint32_t)P);
+    *host_capacity = w.cap;
+    if (hipMemcpy(host_counts, w.cand_count, sizeof(uint32_t) * (size_t)P, hipMemcpyDeviceToHost) !=
+        hipSuccess)
+        return GTOPK_EHIP;
+    return GTOPK_OK;
+}
+
+int gtopk_arm_stage_events(void* const* events) {
+    if (!events) { g_stage_armed = false; return GTOPK_OK; }
+    for (int i = 0; i < GTOPK_STAGE_EVENTS; ++i) {
+        if (!events[i]) return GTOPK_EINVAL;
+        g_stage_events[i] = (hipEvent_t)events[i];
+    }
+    g_stage_armed = true;
+    return GTOPK_OK;
 }
 
 }  // extern "C"

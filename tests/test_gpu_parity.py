@@ -229,3 +229,28 @@ def test_step_is_deterministic():
         outs.append((gi.copy(), gv.copy(), dev.residual().copy(), idx_np(dev.loc_idx).copy()))
     assert np.array_equal(outs[0][0], outs[1][0]) and bits_equal(outs[0][1], outs[1][1])
     assert bits_equal(outs[0][2], outs[1][2]) and np.array_equal(outs[0][3], outs[1][3])
+
+
+def test_candidate_path_is_the_one_exercised():
+    """On the configs' recipes every worker must be served from its candidate list (the
+    fast path); on an all-equal-magnitude input the candidates overflow and the dense
+    row is read instead (the exact fallback).  Both were checked bit for bit above; this
+    test pins WHICH path ran."""
+    from paper_1901_04359_amd import binding as B
+    for base, m, P in (("C2", 269_722, 8), ("C4a", 2_000_000, 4), ("C4b", 1_000_000, 4),
+                       ("C3", 1_000_000, 4), ("C5", 1_500_000, 4)):
+        cfg = W.scaled(W.CONFIGS[base], m, P=P)
+        dev = Device(P, cfg.m, cfg.k)
+        dev.set_grad(W.gradients(cfg, 0))
+        say(f"path check {cfg.name}")
+        dev.local_select()
+        counts, cap = B.gtopk_debug_candidate_counts(dev.ws, cfg.m, cfg.k, P)
+        assert all(cfg.k <= c <= cap for c in counts), (cfg.name, counts, cap, cfg.k)
+        assert max(counts) <= 2.5 * cfg.k + 4096, (cfg.name, counts, cfg.k)
+    P, m, k = 2, 50_000, 777
+    dev = Device(P, m, k)
+    dev.set_grad(np.full((P, m), 0.125, dtype=np.float32))
+    say("path check all-equal")
+    dev.local_select()
+    counts, cap = B.gtopk_debug_candidate_counts(dev.ws, m, k, P)
+    assert all(c > cap for c in counts), (counts, cap)
