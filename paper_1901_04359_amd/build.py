@@ -10,7 +10,7 @@ import sys
 
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
-SRC = os.path.join(PKG, "csrc", "gtopk.hip")
+SRC = os.path.join(PKG, "csrc", "gtopk.hip")   # includes the *.hip.h kernel files beside it
 OUT = os.path.join(PKG, "libgtopk.so")
 
 HIPCC_FLAGS = [

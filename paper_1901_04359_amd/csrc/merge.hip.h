@@ -1,0 +1,177 @@
+// The Top-k operation between two sparse vectors (Definition 1): index-ordered union of
+// two k-sets with the values at shared indices added.  Also the residual restore of
+// Algorithm 4 line 10.
+#pragma once
+#include "common.hip.h"
+
+namespace gtopk {
+
+// Number of elements of the ascending array a[0..n) that are below x (UPPER: below or
+// equal).  The whole wave calls it with the same arguments and gets the same result:
+// each round the 64 lanes probe the last elements of 64 consecutive sub-ranges, so the
+// dependent chain is log64(n) loads long.
+template <bool UPPER>
+__device__ inline uint32_t wave_count_below(const uint32_t* __restrict__ a, uint32_t n, uint32_t x) {
+    uint32_t lo = 0, hi = n;              // the answer lies in [lo, hi]
+    const uint32_t lane = lane_id();
+    while (lo < hi) {
+        const uint32_t len = hi - lo;
+        const uint32_t step = (len + kWave - 1) / kWave;
+        const uint32_t start = lo + lane * step;                     // this lane's sub-range
+        const bool active = start < hi;
+        const uint32_t last = (start + step < hi ? start + step : hi) - 1;
+        bool below = false;
+        if (active) {
+            const uint32_t v = a[last];
+            below = UPPER ? v <= x : v < x;
+        }
+        // sortedness makes the lanes with `below` a prefix of the active ones
+        const uint32_t c = (uint32_t)__popcll(__ballot(below));
+        const uint32_t nlo = lo + c * step < hi ? lo + c * step : hi;
+        const uint32_t cstart = lo + c * step;                       // sub-range of lane c
+        uint32_t nhi = hi;
+        if (c < (uint32_t)kWave && cstart < hi)
+            nhi = (cstart + step < hi ? cstart + step : hi) - 1;
+        lo = nlo;
+        hi = nhi;
+    }
+    return lo;
+}
+
+// count of elements of a below x (UPPER: below or equal), known to lie in [lo, hi]
+template <bool UPPER>
+__device__ __forceinline__ uint32_t count_below_in(const uint32_t* __restrict__ a, uint32_t lo,
+                                                   uint32_t hi, uint32_t x) {
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        const uint32_t v = a[mid];
+        if (UPPER ? v <= x : v < x) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+__device__ __forceinline__ uint32_t wave_min(uint32_t v) {
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const uint32_t o = __shfl_xor(v, d);
+        v = o < v ? o : v;
+    }
+    return v;
+}
+
+// Entry x of A goes to slot x + #{B < A[x]}, entry y of B to slot y + #{A <= B[y]}:
+// a bijection onto [0, 2k) that lists the union in index order, A's copy first
+// where both hold an index.  A's copy then carries the sum (one fp32 add) and B's
+// slot becomes a tombstone.
+// A block takes 256 consecutive entries of A and of B.  Its four waves first find, each
+// with one 64-ary search, the counts for the block's first and last entry of either
+// side; every thread then searches only between those two counts, a short range that
+// the block's threads share in cache.  The block also folds the smallest key of its
+// entries of either operand into inv_min[pair][0..1] (as ~key under atomicMax, so that
+// a cleared word means "none yet").
+__global__ __launch_bounds__(kBlock) void k_union(
+        const uint32_t* __restrict__ a_idx, const float* __restrict__ a_val,
+        const uint32_t* __restrict__ b_idx, const float* __restrict__ b_val, uint32_t k,
+        int64_t in_stride, uint32_t* __restrict__ m_idx, float* __restrict__ m_val,
+        uint32_t* __restrict__ inv_min) {
+    __shared__ uint32_t s_bound[4];
+    __shared__ uint32_t s_min[2][kBlock / kWave];
+    const int s = blockIdx.y;
+    const uint32_t x0 = blockIdx.x * kBlock;            // < k by the launch grid
+    const uint32_t x1 = x0 + kBlock - 1 < k ? x0 + kBlock - 1 : k - 1;
+    const uint32_t* ai = a_idx + (int64_t)s * in_stride;
+    const float* av = a_val + (int64_t)s * in_stride;
+    const uint32_t* bi = b_idx + (int64_t)s * in_stride;
+    const float* bv = b_val + (int64_t)s * in_stride;
+    uint32_t* mi = m_idx + (size_t)s * 2 * k;
+    float* mv = m_val + (size_t)s * 2 * k;
+    const uint32_t wave = threadIdx.x / kWave;
+    const uint32_t x = x0 + threadIdx.x;
+    const bool live = x < k;
+    // this thread's two entries (loads overlap with the boundary searches)
+    const uint32_t ia = live ? ai[x] : 0u, ib = live ? bi[x] : 0u;
+    const float fa = live ? av[x] : 0.0f, fb = live ? bv[x] : 0.0f;
+    uint32_t bound;
+    if (wave == 0) bound = wave_count_below<false>(bi, k, ai[x0]);
+    else if (wave == 1) bound = wave_count_below<false>(bi, k, ai[x1]);
+    else if (wave == 2) bound = wave_count_below<true>(ai, k, bi[x0]);
+    else bound = wave_count_below<true>(ai, k, bi[x1]);
+    const uint32_t ka = wave_min(live ? (__float_as_uint(fa) & kAbs) : 0xFFFFFFFFu);
+    const uint32_t kb = wave_min(live ? (__float_as_uint(fb) & kAbs) : 0xFFFFFFFFu);
+    if (lane_id() == 0) { s_bound[wave] = bound; s_min[0][wave] = ka; s_min[1][wave] = kb; }
+    __syncthreads();
+    if (threadIdx.x < 2) {
+        uint32_t v = 0xFFFFFFFFu;
+        for (int i = 0; i < kBlock / kWave; ++i) v = s_min[threadIdx.x][i] < v ? s_min[threadIdx.x][i] : v;
+        atomicMax(&inv_min[2 * s + threadIdx.x], ~v);
+    }
+    if (!live) return;
+    const uint32_t pa = count_below_in<false>(bi, s_bound[0], s_bound[1], ia);   // #{B < ia}
+    const uint32_t pb = count_below_in<true>(ai, s_bound[2], s_bound[3], ib);    // #{A <= ib}
+    float sum = fa;
+    if (pa < k && bi[pa] == ia) sum = sum + bv[pa];
+    mi[x + pa] = ia;
+    mv[x + pa] = sum;
+    const bool dup = pb > 0 && ai[pb - 1] == ib;
+    mi[x + pb] = dup ? kTomb : ib;
+    mv[x + pb] = fb;
+}
+
+// P == 1: the tree has no round; the global set is worker 0's set divided by 1.
+__global__ void k_copy_set(const uint32_t* __restrict__ in_idx, const float* __restrict__ in_val,
+                           uint32_t k, uint32_t* __restrict__ out_idx, float* __restrict__ out_val,
+                           float divisor, uint32_t* __restrict__ gbits) {
+    const uint32_t t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t < k) {
+        const uint32_t i = in_idx[t];
+        out_idx[t] = i;
+        out_val[t] = in_val[t] / divisor;
+        if (gbits) atomicOr(&gbits[i >> 5], 1u << (i & 31));
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// residual restore (Algorithm 4 line 10)
+// ---------------------------------------------------------------------------------
+
+__device__ __forceinline__ bool contains(const uint32_t* a, uint32_t n, uint32_t x) {
+    uint32_t lo = 0, hi = n;
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (a[mid] < x) lo = mid + 1; else hi = mid;
+    }
+    return lo < n && a[lo] == x;
+}
+
+// The literal form: the slots were zeroed by the local selection; add the value back
+// where the index is not in the global set.
+__global__ __launch_bounds__(kBlock) void k_restore(
+        float* __restrict__ res, int64_t stride, uint32_t k, const uint32_t* __restrict__ loc_idx,
+        const float* __restrict__ loc_val, const uint32_t* __restrict__ g_idx) {
+    const int w = blockIdx.y;
+    const uint32_t t = blockIdx.x * kBlock + threadIdx.x;
+    if (t >= k) return;
+    const uint32_t i = loc_idx[(size_t)w * k + t];
+    if (contains(g_idx, k, i)) return;          // index is in the global set: stays zero
+    float* slot = res + (int64_t)w * stride + i;
+    *slot = *slot + loc_val[(size_t)w * k + t];
+}
+
+// The fused form used by gtopk_step, where the local selection did NOT zero its entries
+// (the row still holds acc there).  Zero-then-add-back leaves acc unchanged except that
+// +0.0 + (-0.0) = +0.0, so: an entry whose index is in the global set becomes +0.0, an
+// entry that is -0.0 becomes +0.0, every other entry is already what the literal form
+// produces.  gbits is the one-bit-per-element mask of the global set.
+__global__ __launch_bounds__(kBlock) void k_restore_fused(
+        float* __restrict__ res, int64_t stride, uint32_t k, const uint32_t* __restrict__ loc_idx,
+        const float* __restrict__ loc_val, const uint32_t* __restrict__ gbits) {
+    const int w = blockIdx.y;
+    const uint32_t t = blockIdx.x * kBlock + threadIdx.x;
+    if (t >= k) return;
+    const uint32_t i = loc_idx[(size_t)w * k + t];
+    const uint32_t vb = __float_as_uint(loc_val[(size_t)w * k + t]);
+    const bool in_g = (gbits[i >> 5] >> (i & 31)) & 1u;
+    if (in_g || vb == 0x80000000u) res[(int64_t)w * stride + i] = 0.0f;
+}
+
+}  // namespace gtopk

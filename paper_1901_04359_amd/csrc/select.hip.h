@@ -1,0 +1,545 @@
+// Exact selection of the k entries with the largest keys out of a set, written out in
+// index order: the common core of the local selection (Algorithm 4 lines 5-7) and of the
+// Top-k operation between two sparse vectors (Definition 1).
+//
+// Four kernels per batch of sets:
+//   k_hist    4096-bin histogram of the keys' first digit
+//   k_bucket  every block picks, from that histogram, the bin d1 that holds the k-th
+//             key; then, per group of slots: count of keys above the bin; keys inside
+//             the bin are appended (with their group) to a short list.  For the local
+//             selection this walk also copies the candidates, which the streaming pass
+//             left as runs in arbitrary order, into index order.
+//   k_finish  one block per set: LDS radix passes over the list give the exact key T
+//             and the number of ties to take; per-group counts are completed from the
+//             list and scanned into output offsets
+//   k_emit    per group: ordered compaction of the selected entries
+#pragma once
+#include "common.hip.h"
+
+namespace gtopk {
+
+// per-set state of the exact select
+struct SelState {
+    // ---- zero between uses (cleared by the caller once, re-cleared by k_finish) ----
+    uint32_t* hist;       // [sets][4096]
+    uint32_t* list_cnt;   // [sets]
+    uint32_t* grp_gt;     // [sets][maxgroups] entries of the group above bin d1
+    uint32_t* inv_min;    // [sets][2] ~(smallest key) of either merge operand (0 = none seen)
+    // --------------------------------------------------------------------------------
+    uint32_t* d1;         // [sets] bin of the k-th key
+    uint32_t* krem;       // [sets] rank of the k-th key inside bin d1 (1-based, from the top)
+    uint32_t* T;          // [sets] the k-th largest key
+    uint32_t* need;       // [sets] entries with key == T to take (>= 1)
+    uint2* list;          // [sets][list_cap]  (key, group)
+    uint32_t* off_gt;     // [sets][maxgroups] exclusive scans over groups
+    uint32_t* off_eq;
+    uint32_t list_cap, maxgroups;
+};
+
+// ---------------------------------------------------------------------------------
+// item sources
+// ---------------------------------------------------------------------------------
+// A source presents, per set s, nphys(s) "physical" slots in storage order and the same
+// items in "logical" = index order, cut into groups of group_slots() consecutive logical
+// positions.  logical() maps a physical slot to its logical position; kIdentity says the
+// two orders coincide.  fetch_*() return false for a slot that holds nothing.
+
+// Local select: the candidate list of worker s, or - when the speculative threshold
+// left fewer than k candidates or more than the list holds - the worker's dense row.
+struct CandSrc {
+    static constexpr bool kIdentity = false;
+    static constexpr bool kRunScan = true;
+    const float* res;
+    int64_t stride;
+    uint32_t m, k, cap, nchunks;
+    uint32_t Lc, Ld;                      // slots per group: candidate list / dense row
+    const uint32_t* cand_idx;             // [P][cap] runs in reservation order
+    const float* cand_val;
+    const uint32_t* cand_count;           // [P]
+    const uint32_t* tspec;                // [P] speculative threshold = lower bound of all candidates
+    const uint2* run_table;               // [P][nchunks] (first physical slot, count)
+    uint32_t* run_off;                    // [P][nchunks] first logical position of the run
+    uint32_t* ord_idx;                    // [P][cap] candidates in index order
+    float* ord_val;
+
+    __device__ bool dense(int s) const {
+        const uint32_t c = cand_count[s];
+        return c < k || c > cap;
+    }
+    __device__ uint32_t nphys(int s, bool dn) const { return dn ? m : cand_count[s]; }
+    __device__ uint32_t group_slots(bool dn) const { return dn ? Ld : Lc; }
+    __device__ Digit digit(int s, bool dn, const SelState&) const {
+        return dn ? Digit{0u, (uint32_t)kCoarseShift} : Digit{tspec[s], (uint32_t)kFineShift};
+    }
+    __device__ bool fetch_phys(int s, bool dn, uint32_t p, uint32_t& idx, uint32_t& bits) const {
+        if (dn) {
+            idx = p;
+            bits = __float_as_uint(res[(int64_t)s * stride + p]);
+        } else {
+            idx = cand_idx[(size_t)s * cap + p];
+            bits = __float_as_uint(cand_val[(size_t)s * cap + p]);
+        }
+        return true;
+    }
+    __device__ bool fetch_key_phys(int s, bool dn, uint32_t p, uint32_t& key) const {
+        key = __float_as_uint(dn ? res[(int64_t)s * stride + p] : cand_val[(size_t)s * cap + p]) & kAbs;
+        return true;
+    }
+    __device__ uint32_t logical(int s, bool dn, uint32_t p, uint32_t idx) const {
+        if (dn) return p;
+        const size_t r = (size_t)s * nchunks + (idx >> kChunkLog2);
+        return run_off[r] + (p - run_table[r].x);
+    }
+    __device__ void store_ordered(int s, bool dn, uint32_t lp, uint32_t idx, uint32_t bits) const {
+        if (!dn) {
+            ord_idx[(size_t)s * cap + lp] = idx;
+            ord_val[(size_t)s * cap + lp] = __uint_as_float(bits);
+        }
+    }
+    __device__ bool fetch_ord(int s, bool dn, uint32_t lp, uint32_t& idx, uint32_t& bits) const {
+        if (dn) {
+            idx = lp;
+            bits = __float_as_uint(res[(int64_t)s * stride + lp]);
+        } else {
+            idx = ord_idx[(size_t)s * cap + lp];
+            bits = __float_as_uint(ord_val[(size_t)s * cap + lp]);
+        }
+        return true;
+    }
+    // exclusive scan of the run counts of worker s, by one block of kHistBlock threads
+    __device__ void scan_runs(int s, uint32_t* s_wave) const {
+        uint32_t carry = 0;
+        for (uint32_t c0 = 0; c0 < nchunks; c0 += kHistBlock) {
+            const uint32_t c = c0 + threadIdx.x;
+            const uint32_t v = c < nchunks ? run_table[(size_t)s * nchunks + c].y : 0u;
+            uint32_t tot;
+            const uint32_t incl = block_incl_scan(v, s_wave, tot);
+            if (c < nchunks) run_off[(size_t)s * nchunks + c] = carry + incl - v;
+            carry += tot;
+        }
+    }
+};
+
+// Merge: n = 2k slots per pair, index-ascending, a slot with index kTomb holds nothing.
+// Every key of the union that is a plain copy of an operand's entry is at least that
+// operand's smallest key, so the larger of the two smallest keys bounds the k-th key of
+// the union from below (sums that cancel can fall under it; they land in bin 0).
+struct MergedSrc {
+    static constexpr bool kIdentity = true;
+    static constexpr bool kRunScan = false;
+    const uint32_t* idx;
+    const float* val;
+    uint32_t n, L;       // L slots per group
+    __device__ bool dense(int) const { return false; }
+    __device__ uint32_t nphys(int, bool) const { return n; }
+    __device__ uint32_t group_slots(bool) const { return L; }
+    __device__ Digit digit(int s, bool, const SelState& st) const {
+        const uint32_t ia = st.inv_min[2 * s], ib = st.inv_min[2 * s + 1];
+        if (ia == 0u || ib == 0u) return Digit{0u, (uint32_t)kCoarseShift};
+        const uint32_t ma = ~ia, mb = ~ib;
+        return Digit{ma > mb ? ma : mb, (uint32_t)kFineShift};
+    }
+    __device__ bool fetch_phys(int s, bool, uint32_t p, uint32_t& i, uint32_t& bits) const {
+        i = idx[(size_t)s * n + p];
+        bits = __float_as_uint(val[(size_t)s * n + p]);
+        return i != kTomb;
+    }
+    __device__ bool fetch_key_phys(int s, bool, uint32_t p, uint32_t& key) const {
+        key = __float_as_uint(val[(size_t)s * n + p]) & kAbs;
+        return idx[(size_t)s * n + p] != kTomb;
+    }
+    __device__ uint32_t logical(int, bool, uint32_t p, uint32_t) const { return p; }
+    __device__ void store_ordered(int, bool, uint32_t, uint32_t, uint32_t) const {}
+    __device__ bool fetch_ord(int s, bool dn, uint32_t lp, uint32_t& i, uint32_t& bits) const {
+        return fetch_phys(s, dn, lp, i, bits);
+    }
+    __device__ void scan_runs(int, uint32_t*) const {}
+};
+
+// ---------------------------------------------------------------------------------
+// kernel 1: histogram of the first digit
+// ---------------------------------------------------------------------------------
+
+// Few, large blocks per set: a popular bin receives one global atomic per block.  For a
+// source whose runs need ordering, one extra block per set scans the run counts.
+template <class Src>
+__global__ __launch_bounds__(kHistBlock) void k_hist(Src src, SelState st, uint32_t hist_blocks) {
+    __shared__ uint32_t h[kHistBins];
+    __shared__ uint32_t s_wave[kHistBlock / kWave];
+    const int s = blockIdx.y;
+    if (Src::kRunScan && blockIdx.x == hist_blocks) {
+        src.scan_runs(s, s_wave);
+        return;
+    }
+    for (int b = threadIdx.x; b < kHistBins; b += kHistBlock) h[b] = 0u;
+    __syncthreads();
+    const bool dn = src.dense(s);
+    const uint32_t n = src.nphys(s, dn);
+    const Digit dg = src.digit(s, dn, st);
+    const uint64_t step = (uint64_t)hist_blocks * kHistBlock;
+    for (uint64_t p0 = (uint64_t)blockIdx.x * kHistBlock + threadIdx.x; p0 < n; p0 += step * kBatch) {
+        uint32_t key[kBatch];
+        bool ok[kBatch];
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            const uint64_t p = p0 + j * step;
+            key[j] = 0;
+            ok[j] = p < n && src.fetch_key_phys(s, dn, (uint32_t)p, key[j]);
+        }
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j)
+            if (ok[j]) atomicAdd(&h[dg.bin(key[j])], 1u);
+    }
+    __syncthreads();
+    uint32_t* out = st.hist + (size_t)s * kHistBins;
+    for (int b = threadIdx.x; b < kHistBins; b += kHistBlock) {
+        const uint32_t c = h[b];
+        if (c) atomicAdd(&out[b], c);
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// kernel 2: pick the bin; per group, count keys above it, list keys inside it
+// ---------------------------------------------------------------------------------
+
+// Block g of set s walks the physical slots [g*L, (g+1)*L).
+template <class Src>
+__global__ __launch_bounds__(kBlock) void k_bucket(Src src, SelState st, uint32_t k) {
+    __shared__ uint32_t s_wave[kBlock / kWave];
+    __shared__ uint32_t s_out[3];
+    __shared__ uint32_t s_gt[kBlock / kWave];
+    __shared__ uint32_t s_in[kBlock / kWave];
+    __shared__ uint32_t s_base;
+    const int s = blockIdx.y;
+    const uint32_t g = blockIdx.x;
+    const bool dn = src.dense(s);
+    const uint32_t n = src.nphys(s, dn);
+    const uint32_t L = src.group_slots(dn);
+    const uint64_t first = (uint64_t)g * L;
+    if (first >= n) return;
+    const uint32_t end = (uint32_t)(first + L < n ? first + L : n);
+    const Digit dg = src.digit(s, dn, st);
+    // every block picks the bin of the k-th key from the set's histogram
+    {
+        constexpr int kPer = kHistBins / kBlock;      // thread t owns 16 consecutive bins
+        const uint32_t* hist = st.hist + (size_t)s * kHistBins;
+        uint32_t loc[kPer];
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) loc[j] = hist[threadIdx.x * kPer + j];
+        suffix_pick<kPer>(loc, k, s_wave, s_out);
+    }
+    const uint32_t d1 = s_out[0];
+    if (g == 0 && threadIdx.x == 0) {
+        st.d1[s] = d1;
+        st.krem[s] = k - s_out[1];
+    }
+    const uint32_t wave = threadIdx.x / kWave;
+    const bool single = end - (uint32_t)first <= (uint32_t)(kBlock * kBatch);
+    uint32_t* ggt = st.grp_gt + (size_t)s * st.maxgroups;
+    uint32_t gt = 0, in = 0;     // wave-uniform
+    // kept from the (only) round when the group fits in one: no second fetch then
+    uint32_t key[kBatch], lg[kBatch];
+    bool inside[kBatch];
+    for (uint32_t i0 = (uint32_t)first; i0 < end; i0 += kBlock * kBatch) {
+        uint32_t idx[kBatch], bits[kBatch];
+        bool ok[kBatch];
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            const uint32_t p = i0 + j * kBlock + threadIdx.x;
+            idx[j] = 0; bits[j] = 0;
+            ok[j] = p < end && src.fetch_phys(s, dn, p, idx[j], bits[j]);
+        }
+        uint32_t lp[kBatch];
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            const uint32_t p = i0 + j * kBlock + threadIdx.x;
+            lp[j] = p < end ? src.logical(s, dn, p, idx[j]) : 0u;
+        }
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            const uint32_t p = i0 + j * kBlock + threadIdx.x;
+            if (p < end) src.store_ordered(s, dn, lp[j], idx[j], bits[j]);
+            key[j] = bits[j] & kAbs;
+            const uint32_t d = dg.bin(key[j]);
+            const bool above = ok[j] && d > d1;
+            inside[j] = ok[j] && d == d1;
+            lg[j] = Src::kIdentity ? g : lp[j] / L;
+            if (Src::kIdentity) gt += (uint32_t)__popcll(__ballot(above));
+            else add_grouped(above, lg[j], ggt);
+            in += (uint32_t)__popcll(__ballot(inside[j]));
+        }
+    }
+    if (lane_id() == 0) { s_gt[wave] = gt; s_in[wave] = in; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t tg = 0, ti = 0;
+        for (int v = 0; v < kBlock / kWave; ++v) { tg += s_gt[v]; ti += s_in[v]; }
+        if (Src::kIdentity) ggt[g] = tg;
+        s_base = ti ? atomicAdd(&st.list_cnt[s], ti) : 0u;     // one reservation per block
+    }
+    __syncthreads();
+    if (in == 0) return;
+    // second walk: this wave's in-bin entries go to its slice of the block's reservation
+    uint32_t off = s_base;
+    for (uint32_t v = 0; v < wave; ++v) off += s_in[v];
+    uint2* list = st.list + (size_t)s * st.list_cap;
+    for (uint32_t i0 = (uint32_t)first; i0 < end; i0 += kBlock * kBatch) {
+        if (!single) {
+            uint32_t idx[kBatch], bits[kBatch];
+            bool ok[kBatch];
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+                const uint32_t p = i0 + j * kBlock + threadIdx.x;
+                idx[j] = 0; bits[j] = 0;
+                ok[j] = p < end && src.fetch_phys(s, dn, p, idx[j], bits[j]);
+            }
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+                const uint32_t p = i0 + j * kBlock + threadIdx.x;
+                key[j] = bits[j] & kAbs;
+                inside[j] = ok[j] && dg.bin(key[j]) == d1;
+                lg[j] = Src::kIdentity ? g : (inside[j] ? src.logical(s, dn, p, idx[j]) / L : 0u);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            const uint64_t inm = __ballot(inside[j]);
+            if (inside[j]) {
+                const uint32_t pos = off + rank_in(inm);
+                if (pos < st.list_cap) list[pos] = make_uint2(key[j], lg[j]);
+            }
+            off += (uint32_t)__popcll(inm);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// kernel 3: one block per set finishes the key and scans the groups
+// ---------------------------------------------------------------------------------
+
+template <class Src>
+__global__ __launch_bounds__(1024) void k_finish(Src src, SelState st) {
+    constexpr int kT = 1024;
+    __shared__ uint32_t h[2048];
+    __shared__ uint32_t g_gt[kMaxGroups];
+    __shared__ uint32_t g_eq[kMaxGroups];
+    __shared__ uint32_t s_wave[kT / kWave];
+    __shared__ uint32_t s_out[3];
+    const int s = blockIdx.x;
+    const uint32_t t = threadIdx.x;
+    const bool dn = src.dense(s);
+    const uint32_t nphys = src.nphys(s, dn);
+    const uint32_t L = src.group_slots(dn);
+    const uint32_t ng = (uint32_t)(((uint64_t)nphys + L - 1) / L);
+    const Digit dg = src.digit(s, dn, st);
+    const uint32_t d1 = st.d1[s];
+    uint32_t krem = st.krem[s];
+    const uint32_t nlist = st.list_cnt[s];
+    const bool overflow = nlist > st.list_cap;       // the list is incomplete: read the set itself
+    const uint2* list = st.list + (size_t)s * st.list_cap;
+    const uint32_t lo = dg.lo(d1), width = dg.width(d1);    // bin d1 = [lo, lo + width)
+
+    // a short list is read once and kept in registers
+    constexpr int kCache = 8;
+    constexpr uint32_t kNone = 0xFFFFFFFFu;            // no key has bit 31 set
+    const bool cached = !overflow && nlist <= (uint32_t)(kCache * kT);
+    uint2 ent[kCache];
+#pragma unroll
+    for (int j = 0; j < kCache; ++j) {
+        const uint32_t i = t + (uint32_t)j * kT;
+        ent[j] = (cached && i < nlist) ? list[i] : make_uint2(kNone, 0u);
+    }
+    // f(key, group) is called by every thread the same number of times; key == kNone = nothing
+    auto for_each_entry = [&](auto&& f) {
+        if (cached) {
+#pragma unroll
+            for (int j = 0; j < kCache; ++j) f(ent[j].x, ent[j].y);
+        } else if (!overflow) {
+            for (uint32_t i0 = 0; i0 < nlist; i0 += kT * kBatch) {
+                uint2 e[kBatch];
+#pragma unroll
+                for (int j = 0; j < kBatch; ++j) {
+                    const uint32_t i = i0 + j * kT + t;
+                    e[j] = i < nlist ? list[i] : make_uint2(kNone, 0u);
+                }
+#pragma unroll
+                for (int j = 0; j < kBatch; ++j) f(e[j].x, e[j].y);
+            }
+        } else {
+            // every item of the set in logical order; items outside bin d1 are skipped
+            for (uint64_t p0 = 0; p0 < nphys; p0 += (uint64_t)kT * kBatch) {
+                uint32_t key[kBatch], grp[kBatch];
+#pragma unroll
+                for (int j = 0; j < kBatch; ++j) {
+                    const uint64_t p = p0 + (uint64_t)j * kT + t;
+                    uint32_t idx, bits = 0;
+                    const bool ok = p < nphys && src.fetch_ord(s, dn, (uint32_t)p, idx, bits);
+                    key[j] = (ok && dg.bin(bits & kAbs) == d1) ? (bits & kAbs) : kNone;
+                    grp[j] = (uint32_t)(p / L);
+                }
+#pragma unroll
+                for (int j = 0; j < kBatch; ++j) f(key[j], grp[j]);
+            }
+        }
+    };
+
+    // radix passes over rel = key - lo: bits 30..20, 19..10, 9..0; a pass whose bits are
+    // zero for the whole bin is skipped
+    uint32_t prefix = 0;          // value of the rel bits above the current pass
+    for (int pass = 0; pass < 3; ++pass) {
+        const int shift = pass == 0 ? 20 : (pass == 1 ? 10 : 0);
+        const int bits = pass == 0 ? 11 : 10;
+        if (shift > 0 && width <= (1u << shift)) continue;       // uniform
+        h[t] = 0u;
+        h[t + kT] = 0u;
+        __syncthreads();
+        for_each_entry([&](uint32_t key, uint32_t) {
+            if (key != kNone) {
+                const uint32_t rel = key - lo;
+                if ((rel >> (shift + bits)) == prefix)
+                    atomicAdd(&h[(rel >> shift) & ((1u << bits) - 1u)], 1u);
+            }
+        });
+        __syncthreads();
+        const uint32_t loc[2] = {h[2 * t], h[2 * t + 1]};
+        suffix_pick<2>(loc, krem, s_wave, s_out);
+        prefix = (prefix << bits) | s_out[0];
+        krem -= s_out[1];
+    }
+    const uint32_t T = lo + prefix;
+    const uint32_t need = krem;
+
+    // per-group counts of selected-for-sure (key > T) and tied (key == T) entries
+    for (uint32_t g = t; g < ng; g += kT) {
+        g_gt[g] = st.grp_gt[(size_t)s * st.maxgroups + g];
+        g_eq[g] = 0u;
+    }
+    __syncthreads();
+    for_each_entry([&](uint32_t key, uint32_t g) {
+        g &= (uint32_t)kMaxGroups - 1;
+        add_grouped(key != kNone && key > T, g, g_gt);
+        add_grouped(key != kNone && key == T, g, g_eq);
+    });
+    __syncthreads();
+
+    // exclusive scans over the groups (ng <= 2048: two per thread)
+    {
+        const uint32_t g0 = 2 * t, g1 = 2 * t + 1;
+        const uint32_t a0 = g0 < ng ? g_gt[g0] : 0u, a1 = g1 < ng ? g_gt[g1] : 0u;
+        const uint32_t e0 = g0 < ng ? g_eq[g0] : 0u, e1 = g1 < ng ? g_eq[g1] : 0u;
+        uint32_t tot;
+        const uint32_t ia = block_incl_scan(a0 + a1, s_wave, tot);
+        const uint32_t ie = block_incl_scan(e0 + e1, s_wave, tot);
+        uint32_t* og = st.off_gt + (size_t)s * st.maxgroups;
+        uint32_t* oe = st.off_eq + (size_t)s * st.maxgroups;
+        if (g0 < ng) { og[g0] = ia - a0 - a1; oe[g0] = ie - e0 - e1; }
+        if (g1 < ng) { og[g1] = ia - a1; oe[g1] = ie - e1; }
+    }
+    // leave the per-set scratch clear for the next select that uses it
+    uint32_t* hg = st.hist + (size_t)s * kHistBins;
+    for (uint32_t b = t; b < (uint32_t)kHistBins; b += kT) hg[b] = 0u;
+    for (uint32_t g = t; g < ng; g += kT) st.grp_gt[(size_t)s * st.maxgroups + g] = 0u;
+    if (t == 0) {
+        st.T[s] = T;
+        st.need[s] = need;
+        st.list_cnt[s] = 0u;
+        st.inv_min[2 * s] = 0u;
+        st.inv_min[2 * s + 1] = 0u;
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// kernel 4: ordered emit
+// ---------------------------------------------------------------------------------
+
+// One block per group of logical positions.  An entry is selected if key > T, or
+// key == T and fewer than `need` equal-key entries precede it in index order; its output
+// slot is the number of selected entries before it.  ZERO: also store +0.0 at its index
+// in the set's dense row (Algorithm 4 line 8).  DIVIDE: value / divisor (Eq. 3).
+// gbits != NULL: also set bit `index` of that bitmap (the dense gMask of Algorithm 3
+// lines 21-22, one bit per gradient element).  A block takes 1024 positions per round:
+// their order inside a round is (sub-step j, wave, lane).
+template <class Src, bool ZERO, bool DIVIDE>
+__global__ __launch_bounds__(kBlock) void k_emit(
+        Src src, SelState st, uint32_t k, uint32_t* __restrict__ out_idx,
+        float* __restrict__ out_val, int64_t out_stride, float* __restrict__ row,
+        int64_t row_stride, float divisor, uint32_t* __restrict__ gbits) {
+    constexpr int kWaves = kBlock / kWave;
+    __shared__ uint32_t s_eq[kBatch * kWaves];
+    __shared__ uint32_t s_sel[kBatch * kWaves];
+    const int s = blockIdx.y;
+    const uint32_t g = blockIdx.x;
+    const bool dn = src.dense(s);
+    const uint32_t n = src.nphys(s, dn);
+    const uint32_t L = src.group_slots(dn);
+    const uint64_t first = (uint64_t)g * L;
+    if (first >= n) return;
+    const uint32_t end = (uint32_t)(first + L < n ? first + L : n);
+    const uint32_t T = st.T[s], need = st.need[s];
+    uint32_t eq_before = st.off_eq[(size_t)s * st.maxgroups + g];
+    uint32_t outp = st.off_gt[(size_t)s * st.maxgroups + g] + (eq_before < need ? eq_before : need);
+    const uint32_t wave = threadIdx.x / kWave;
+    for (uint32_t i0 = (uint32_t)first; i0 < end; i0 += kBlock * kBatch) {
+        uint32_t idx[kBatch], vb[kBatch];
+        bool ok[kBatch];
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            const uint32_t p = i0 + j * kBlock + threadIdx.x;
+            idx[j] = 0; vb[j] = 0;
+            ok[j] = p < end && src.fetch_ord(s, dn, p, idx[j], vb[j]);
+        }
+        bool is_gt[kBatch], is_eq[kBatch];
+        uint64_t eqm[kBatch];
+        __syncthreads();                  // the previous round's s_eq / s_sel are no longer read
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            const uint32_t key = vb[j] & kAbs;
+            is_gt[j] = ok[j] && key > T;
+            is_eq[j] = ok[j] && key == T;
+            eqm[j] = __ballot(is_eq[j]);
+            if (lane_id() == 0) s_eq[j * kWaves + wave] = (uint32_t)__popcll(eqm[j]);
+        }
+        __syncthreads();
+        bool sel[kBatch];
+        uint64_t selm[kBatch];
+        uint32_t eq_all = 0;
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            uint32_t eq_base = eq_before + eq_all;
+            for (uint32_t v = 0; v < (uint32_t)kWaves; ++v) {
+                const uint32_t c = s_eq[j * kWaves + v];
+                if (v < wave) eq_base += c;
+                eq_all += c;
+            }
+            sel[j] = is_gt[j] || (is_eq[j] && (eq_base + rank_in(eqm[j]) < need));
+            selm[j] = __ballot(sel[j]);
+            if (lane_id() == 0) s_sel[j * kWaves + wave] = (uint32_t)__popcll(selm[j]);
+        }
+        __syncthreads();
+        uint32_t sel_all = 0;
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            uint32_t sel_base = outp + sel_all;
+            for (uint32_t v = 0; v < (uint32_t)kWaves; ++v) {
+                const uint32_t c = s_sel[j * kWaves + v];
+                if (v < wave) sel_base += c;
+                sel_all += c;
+            }
+            if (sel[j]) {
+                const uint32_t pos = sel_base + rank_in(selm[j]);
+                if (pos < k) {      // always true when the select state is consistent
+                    out_idx[(int64_t)s * out_stride + pos] = idx[j];
+                    float v = __uint_as_float(vb[j]);
+                    if (DIVIDE) v = v / divisor;
+                    out_val[(int64_t)s * out_stride + pos] = v;
+                }
+                if (ZERO) row[(int64_t)s * row_stride + idx[j]] = 0.0f;
+                if (gbits) atomicOr(&gbits[idx[j] >> 5], 1u << (idx[j] & 31));
+            }
+        }
+        outp += sel_all;
+        eq_before += eq_all;
+    }
+}
+
+}  // namespace gtopk

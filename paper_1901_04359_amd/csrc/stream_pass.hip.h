@@ -1,0 +1,176 @@
+// Local selection, Algorithm 4 lines 4-8, the part that touches all P*m elements:
+// a sampled histogram that yields a speculative threshold, and the one streaming pass
+// that accumulates (line 4) and keeps the entries at or above that threshold.
+#pragma once
+#include "common.hip.h"
+
+namespace gtopk {
+
+// Sample tile t of a row covers [t*tile_stride, t*tile_stride + 256) (clipped to m).  A
+// block of 1024 threads takes four tiles per round, eight rounds of loads in flight.
+__global__ __launch_bounds__(kSampleBlock) void k_sample(
+        const float* __restrict__ grad, const float* __restrict__ res, uint32_t m, int64_t stride,
+        uint32_t tile_stride, uint32_t n_tiles, uint32_t* __restrict__ samp_hist) {
+    __shared__ uint32_t h[kSampleBins];
+    const int w = blockIdx.y;
+    for (int b = threadIdx.x; b < kSampleBins; b += kSampleBlock) h[b] = 0u;
+    __syncthreads();
+    const float* g = grad + (int64_t)w * stride;
+    const float* r = res + (int64_t)w * stride;
+    const uint32_t sub = threadIdx.x / kSampleTile, el = threadIdx.x % kSampleTile;
+    constexpr int kUnroll = 8;
+    const uint64_t tiles_per_round = (uint64_t)(kSampleBlock / kSampleTile) * gridDim.x;
+    for (uint64_t t0 = (uint64_t)blockIdx.x * (kSampleBlock / kSampleTile) + sub; t0 < n_tiles;
+         t0 += tiles_per_round * kUnroll) {
+        float gv[kUnroll], rv[kUnroll];
+        bool ok[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            const uint64_t t = t0 + (uint64_t)u * tiles_per_round;
+            const uint64_t q = t * tile_stride + el;
+            ok[u] = t < n_tiles && q < m;
+            gv[u] = ok[u] ? g[q] : 0.0f;
+            rv[u] = ok[u] ? r[q] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            if (ok[u]) {
+                const uint32_t key = __float_as_uint(rv[u] + gv[u]) & kAbs;
+                atomicAdd(&h[key >> kSampleShift], 1u);
+            }
+        }
+    }
+    __syncthreads();
+    uint32_t* out = samp_hist + (size_t)w * kSampleBins;
+    for (int b = threadIdx.x; b < kSampleBins; b += kSampleBlock) {
+        const uint32_t c = h[b];
+        if (c) atomicAdd(&out[b], c);
+    }
+}
+
+// One block per worker turns the worker's sample histogram into the speculative
+// threshold: the lower edge of the bucket at which the count from the top reaches
+// `target`.
+__global__ __launch_bounds__(kSampleBlock) void k_sample_pick(
+        const uint32_t* __restrict__ samp_hist, uint32_t target, uint32_t* __restrict__ tspec) {
+    __shared__ uint32_t s_wave[kSampleBlock / kWave];
+    __shared__ uint32_t s_out[3];
+    const int w = blockIdx.x;
+    constexpr int kPer = kSampleBins / kSampleBlock;
+    const uint32_t* hist = samp_hist + (size_t)w * kSampleBins;
+    uint32_t loc[kPer];
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) loc[j] = hist[threadIdx.x * kPer + j];
+    suffix_pick<kPer>(loc, target, s_wave, s_out);
+    if (threadIdx.x == 0) tspec[w] = s_out[2] ? (s_out[0] << kSampleShift) : 0u;
+}
+
+// Block (chunk, w) handles elements [chunk*32768, +32768) of worker w; each of its 8
+// waves a contiguous 4096 of them, 16 float4 per lane, all held in registers.  Phase 1
+// loads, adds, stores and counts the entries whose key reaches the speculative
+// threshold; one atomicAdd per block reserves a contiguous range ("run") of the worker's
+// candidate list; phase 2 writes the block's candidates there in index order.
+// Blocks reserve in any order, nobody waits for anybody; run_table[w][chunk] =
+// (first slot, count) lets the select put the runs back into index order.
+template <bool ALIGNED>
+__global__ __launch_bounds__(kSBlock) void k_accum_filter(
+        const float* __restrict__ grad, float* __restrict__ res, uint32_t m, int64_t stride,
+        const uint32_t* __restrict__ tspec, uint32_t* __restrict__ cand_idx,
+        float* __restrict__ cand_val, uint32_t cap, uint32_t* __restrict__ cand_count,
+        uint2* __restrict__ run_table, uint32_t nchunks) {
+    constexpr int kWaves = kSBlock / kWave;
+    __shared__ uint32_t s_cnt[kWaves];
+    __shared__ uint32_t s_base;
+    const int w = blockIdx.y;
+    const uint32_t chunk = blockIdx.x;
+    const uint32_t lane = lane_id();
+    const uint32_t wave = threadIdx.x / kWave;
+    const float* g = grad + (int64_t)w * stride;
+    float* r = res + (int64_t)w * stride;
+    const uint32_t ts = tspec[w];
+    // m <= 2^31 and chunk < ceil(m / 32768), so none of the offsets below wraps
+    const uint32_t wbase = chunk * (uint32_t)kChunk + wave * (uint32_t)kWaveSpan;
+
+    float a[kIters][4];
+    const bool whole = ALIGNED && (wbase + (uint32_t)kWaveSpan <= m);   // wave-uniform
+    if (whole) {
+        floatx4 gv[kIters], rv[kIters];
+#pragma unroll
+        for (int i = 0; i < kIters; ++i) {
+            const uint32_t q = wbase + i * 256 + lane * 4;
+            gv[i] = __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(g + q));
+            rv[i] = __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(r + q));
+        }
+#pragma unroll
+        for (int i = 0; i < kIters; ++i) {
+            const uint32_t q = wbase + i * 256 + lane * 4;
+            const floatx4 s = rv[i] + gv[i];          // four independent fp32 adds
+            __builtin_nontemporal_store(s, reinterpret_cast<floatx4*>(r + q));
+            a[i][0] = s.x; a[i][1] = s.y; a[i][2] = s.z; a[i][3] = s.w;
+        }
+    } else {
+#pragma unroll
+        for (int i = 0; i < kIters; ++i) {
+            const uint32_t q = wbase + i * 256 + lane * 4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float s = 0.0f;
+                if (q + e < m) {
+                    s = r[q + e] + g[q + e];
+                    r[q + e] = s;
+                }
+                a[i][e] = s;
+            }
+        }
+    }
+
+    uint32_t cnt = 0;   // wave-uniform
+#pragma unroll
+    for (int i = 0; i < kIters; ++i) {
+        const uint32_t q = wbase + i * 256 + lane * 4;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const bool c = (q + e < m) && ((__float_as_uint(a[i][e]) & kAbs) >= ts);
+            cnt += (uint32_t)__popcll(__ballot(c));
+        }
+    }
+    if (lane == 0) s_cnt[wave] = cnt;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t total = 0;
+        for (int v = 0; v < kWaves; ++v) total += s_cnt[v];
+        uint32_t base = 0;
+        if (total) base = atomicAdd(&cand_count[w], total);
+        run_table[(size_t)w * nchunks + chunk] = make_uint2(base, total);
+        s_base = base;
+    }
+    __syncthreads();
+    if (cnt == 0) return;
+    uint32_t off = s_base;
+    for (uint32_t v = 0; v < wave; ++v) off += s_cnt[v];
+    uint32_t* ci = cand_idx + (size_t)w * cap;
+    float* cv = cand_val + (size_t)w * cap;
+#pragma unroll
+    for (int i = 0; i < kIters; ++i) {
+        const uint32_t q = wbase + i * 256 + lane * 4;
+        bool c[4];
+        uint64_t b[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            c[e] = (q + e < m) && ((__float_as_uint(a[i][e]) & kAbs) >= ts);
+            b[e] = __ballot(c[e]);
+        }
+        if ((b[0] | b[1] | b[2] | b[3]) == 0) continue;
+        uint32_t pos = off + rank_in(b[0]) + rank_in(b[1]) + rank_in(b[2]) + rank_in(b[3]);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (c[e]) {
+                if (pos < cap) { ci[pos] = q + e; cv[pos] = a[i][e]; }
+                ++pos;
+            }
+        }
+        off += (uint32_t)(__popcll(b[0]) + __popcll(b[1]) + __popcll(b[2]) + __popcll(b[3]));
+    }
+}
+
+}  // namespace gtopk
