@@ -134,7 +134,7 @@ StepWs carve_step(void* ws, int64_t m, uint32_t k, uint32_t P) {
     Carver c{reinterpret_cast<char*>(ws)};
     StepWs s;
     s.cap = cand_capacity(m, k);
-    s.nchunks = ceil_div((uint64_t)m, kChunk);
+    s.nchunks = ceil_div((uint64_t)m + 3, kChunk);      // a row may start up to 3 elements into a chunk
     s.Lc = group_slots_for(s.cap, kMaxGroups);
     const uint32_t gcand = ceil_div(s.cap, s.Lc);
     s.Ld = group_slots_for((uint64_t)m, gcand > 256 ? gcand : 256);   // a fallback: coarse groups
@@ -257,15 +257,9 @@ int do_local_select(const float* grad, float* residual, int64_t m, int64_t strid
                        w.tspec);
     mark_stage(1, armed, st);
 
-    const bool vec = (stride % 4 == 0);
-    if (vec)
-        hipLaunchKernelGGL((k_accum_filter<true>), dim3(w.nchunks, P), dim3(kSBlock), 0, st, grad,
-                           residual, (uint32_t)m, stride, w.tspec, w.cand_idx, w.cand_val, w.cap,
-                           w.cand_count, w.run_table, w.nchunks);
-    else
-        hipLaunchKernelGGL((k_accum_filter<false>), dim3(w.nchunks, P), dim3(kSBlock), 0, st, grad,
-                           residual, (uint32_t)m, stride, w.tspec, w.cand_idx, w.cand_val, w.cap,
-                           w.cand_count, w.run_table, w.nchunks);
+    hipLaunchKernelGGL(k_accum_filter, dim3(w.nchunks, P), dim3(kSBlock), 0, st, grad, residual,
+                       (uint32_t)m, stride, w.tspec, w.cand_idx, w.cand_val, w.cap, w.cand_count,
+                       w.run_table, w.nchunks);
     mark_stage(2, armed, st);
 
     CandSrc src{residual, stride, (uint32_t)m, k, w.cap, w.nchunks, w.Lc, w.Ld,

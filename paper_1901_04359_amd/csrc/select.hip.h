@@ -87,7 +87,9 @@ struct CandSrc {
     }
     __device__ uint32_t logical(int s, bool dn, uint32_t p, uint32_t idx) const {
         if (dn) return p;
-        const size_t r = (size_t)s * nchunks + (idx >> kChunkLog2);
+        // the streaming pass cuts a row into chunks at multiples of 32768 of idx + head
+        const uint32_t head = (uint32_t)(((int64_t)s * stride) & 3);
+        const size_t r = (size_t)s * nchunks + ((idx + head) >> kChunkLog2);
         return run_off[r] + (p - run_table[r].x);
     }
     __device__ void store_ordered(int s, bool dn, uint32_t lp, uint32_t idx, uint32_t bits) const {

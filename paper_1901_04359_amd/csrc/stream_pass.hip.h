@@ -65,14 +65,19 @@ __global__ __launch_bounds__(kSampleBlock) void k_sample_pick(
     if (threadIdx.x == 0) tspec[w] = s_out[2] ? (s_out[0] << kSampleShift) : 0u;
 }
 
-// Block (chunk, w) handles elements [chunk*32768, +32768) of worker w; each of its 8
-// waves a contiguous 4096 of them, 16 float4 per lane, all held in registers.  Phase 1
-// loads, adds, stores and counts the entries whose key reaches the speculative
+// Rows need not start on a 16-byte boundary (stride and m are arbitrary).  With
+// head = (w * stride) mod 4, element j of row w sits at "virtual" position v = j + head
+// of a 16-byte aligned array that starts head elements before the row; chunks and
+// float4 accesses are laid out on v, so every vector access is aligned and only the
+// few lanes that straddle a row end fall back to scalar accesses.
+//
+// Block (chunk, w) handles virtual positions [chunk*32768, +32768) of worker w; each of
+// its 8 waves a contiguous 4096 of them, 16 float4 per lane, all held in registers.
+// Phase 1 loads, adds, stores and counts the entries whose key reaches the speculative
 // threshold; one atomicAdd per block reserves a contiguous range ("run") of the worker's
 // candidate list; phase 2 writes the block's candidates there in index order.
 // Blocks reserve in any order, nobody waits for anybody; run_table[w][chunk] =
 // (first slot, count) lets the select put the runs back into index order.
-template <bool ALIGNED>
 __global__ __launch_bounds__(kSBlock) void k_accum_filter(
         const float* __restrict__ grad, float* __restrict__ res, uint32_t m, int64_t stride,
         const uint32_t* __restrict__ tspec, uint32_t* __restrict__ cand_idx,
@@ -85,41 +90,51 @@ __global__ __launch_bounds__(kSBlock) void k_accum_filter(
     const uint32_t chunk = blockIdx.x;
     const uint32_t lane = lane_id();
     const uint32_t wave = threadIdx.x / kWave;
-    const float* g = grad + (int64_t)w * stride;
-    float* r = res + (int64_t)w * stride;
+    const uint32_t head = (uint32_t)(((int64_t)w * stride) & 3);
+    // aligned array that holds the row at [head, head + m)
+    const float* g = grad + (int64_t)w * stride - head;
+    float* r = res + (int64_t)w * stride - head;
+    const uint32_t vend = head + m;          // <= 2^31 + 3
     const uint32_t ts = tspec[w];
-    // m <= 2^31 and chunk < ceil(m / 32768), so none of the offsets below wraps
+    // chunk < ceil((m + 3) / 32768), so none of the offsets below wraps
     const uint32_t wbase = chunk * (uint32_t)kChunk + wave * (uint32_t)kWaveSpan;
 
     float a[kIters][4];
-    const bool whole = ALIGNED && (wbase + (uint32_t)kWaveSpan <= m);   // wave-uniform
+    const bool whole = wbase >= head && wbase + (uint32_t)kWaveSpan <= vend;   // wave-uniform
     if (whole) {
         floatx4 gv[kIters], rv[kIters];
 #pragma unroll
         for (int i = 0; i < kIters; ++i) {
-            const uint32_t q = wbase + i * 256 + lane * 4;
-            gv[i] = __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(g + q));
-            rv[i] = __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(r + q));
+            const uint32_t v = wbase + i * 256 + lane * 4;
+            gv[i] = __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(g + v));
+            rv[i] = __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(r + v));
         }
 #pragma unroll
         for (int i = 0; i < kIters; ++i) {
-            const uint32_t q = wbase + i * 256 + lane * 4;
+            const uint32_t v = wbase + i * 256 + lane * 4;
             const floatx4 s = rv[i] + gv[i];          // four independent fp32 adds
-            __builtin_nontemporal_store(s, reinterpret_cast<floatx4*>(r + q));
+            __builtin_nontemporal_store(s, reinterpret_cast<floatx4*>(r + v));
             a[i][0] = s.x; a[i][1] = s.y; a[i][2] = s.z; a[i][3] = s.w;
         }
     } else {
 #pragma unroll
         for (int i = 0; i < kIters; ++i) {
-            const uint32_t q = wbase + i * 256 + lane * 4;
+            const uint32_t v = wbase + i * 256 + lane * 4;
+            if (v >= head && v + 4 <= vend) {
+                const floatx4 s = *reinterpret_cast<const floatx4*>(r + v) +
+                                  *reinterpret_cast<const floatx4*>(g + v);
+                *reinterpret_cast<floatx4*>(r + v) = s;
+                a[i][0] = s.x; a[i][1] = s.y; a[i][2] = s.z; a[i][3] = s.w;
+            } else {
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                float s = 0.0f;
-                if (q + e < m) {
-                    s = r[q + e] + g[q + e];
-                    r[q + e] = s;
+                for (int e = 0; e < 4; ++e) {
+                    float s = 0.0f;
+                    if (v + e >= head && v + e < vend) {
+                        s = r[v + e] + g[v + e];
+                        r[v + e] = s;
+                    }
+                    a[i][e] = s;
                 }
-                a[i][e] = s;
             }
         }
     }
@@ -127,10 +142,11 @@ __global__ __launch_bounds__(kSBlock) void k_accum_filter(
     uint32_t cnt = 0;   // wave-uniform
 #pragma unroll
     for (int i = 0; i < kIters; ++i) {
-        const uint32_t q = wbase + i * 256 + lane * 4;
+        const uint32_t v = wbase + i * 256 + lane * 4;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            const bool c = (q + e < m) && ((__float_as_uint(a[i][e]) & kAbs) >= ts);
+            const bool c = (v + e >= head) && (v + e < vend) &&
+                           ((__float_as_uint(a[i][e]) & kAbs) >= ts);
             cnt += (uint32_t)__popcll(__ballot(c));
         }
     }
@@ -152,12 +168,12 @@ __global__ __launch_bounds__(kSBlock) void k_accum_filter(
     float* cv = cand_val + (size_t)w * cap;
 #pragma unroll
     for (int i = 0; i < kIters; ++i) {
-        const uint32_t q = wbase + i * 256 + lane * 4;
+        const uint32_t v = wbase + i * 256 + lane * 4;
         bool c[4];
         uint64_t b[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            c[e] = (q + e < m) && ((__float_as_uint(a[i][e]) & kAbs) >= ts);
+            c[e] = (v + e >= head) && (v + e < vend) && ((__float_as_uint(a[i][e]) & kAbs) >= ts);
             b[e] = __ballot(c[e]);
         }
         if ((b[0] | b[1] | b[2] | b[3]) == 0) continue;
@@ -165,7 +181,7 @@ __global__ __launch_bounds__(kSBlock) void k_accum_filter(
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             if (c[e]) {
-                if (pos < cap) { ci[pos] = q + e; cv[pos] = a[i][e]; }
+                if (pos < cap) { ci[pos] = v + e - head; cv[pos] = a[i][e]; }
                 ++pos;
             }
         }
