@@ -21,7 +21,7 @@ constexpr int kCoarseShift = 19;            // bin width 2^19 keys (exponent + 4
 constexpr int kSampleBits = 14;             // sample histogram: exponent + 6 mantissa bits
 constexpr int kSampleBins = 1 << kSampleBits;
 constexpr int kSampleShift = 31 - kSampleBits;
-constexpr int kSampleTile = 256;            // contiguous elements per sample tile
+constexpr int kSampleTile = 64;             // contiguous elements per sample tile: one wave
 constexpr int kSampleBlock = 1024;
 constexpr int kHistBlock = 1024;
 constexpr uint32_t kTomb = 0xFFFFFFFFu;     // index of a merged slot that holds nothing

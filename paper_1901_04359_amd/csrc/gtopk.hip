@@ -202,23 +202,25 @@ void run_select(const Src& src, const SelState& ss, uint32_t sets, uint32_t k, u
                        ss, k, out_idx, out_val, out_stride, row, row_stride, divisor, gbits);
 }
 
-// Sample plan for the speculative threshold: tiles of 256 contiguous elements,
-// evenly spaced, about kSampleMean / rho elements per worker (all of them if the row
-// is short).  `target` is the rank in the sample whose bucket edge is taken: the
+// Sample plan for the speculative threshold: tiles of 64 contiguous elements, evenly
+// spaced, about kSampleMean / rho elements per worker but at least 4096 tiles (all
+// elements if the row is short).  `target` is the rank in the sample whose bucket edge is taken: the
 // expected sample rank of the k-th key plus 5.5 standard deviations, so that the
 // candidate list holds at least k entries except with probability ~1e-8 per worker
 // (and then that worker is merely selected from its dense row).
 struct SamplePlan { uint32_t tile_stride, n_tiles, target; };
 
 SamplePlan plan_sample(int64_t m, uint32_t k) {
-    const double kSampleMean = 256.0;
+    const double kSampleMean = 256.0;        // expected sample rank of the k-th key, at least
+    const double kMinTiles = 4096.0;         // spread: a layer of 1 % of the row still gets ~40 tiles
     SamplePlan p;
     double want = kSampleMean * (double)m / (double)k;
+    if (want < kMinTiles * kSampleTile) want = kMinTiles * kSampleTile;
     if (want >= (double)m) {
         p.tile_stride = kSampleTile;
     } else {
         const uint64_t tiles = (uint64_t)(want / kSampleTile) + 1;
-        uint64_t ts = ((uint64_t)m / tiles) & ~(uint64_t)3;
+        const uint64_t ts = (uint64_t)m / tiles;
         p.tile_stride = (uint32_t)(ts < (uint64_t)kSampleTile ? kSampleTile : ts);
     }
     p.n_tiles = ceil_div((uint64_t)m, p.tile_stride);
@@ -228,8 +230,9 @@ SamplePlan plan_sample(int64_t m, uint32_t k) {
     if (sampled >= (uint64_t)m) {
         p.target = k;                        // the "sample" is the whole row: exact count
     } else {
+        // 5.5 standard deviations of the count, plus 3 % for the tiles' placement error
         const double mean = (double)k * (double)sampled / (double)m;
-        double t = mean + 5.5 * __builtin_sqrt(mean) + 2.0;
+        double t = 1.03 * mean + 5.5 * __builtin_sqrt(mean) + 2.0;
         if (t > (double)sampled) t = (double)sampled;
         p.target = (uint32_t)t;
         if (p.target < 1) p.target = 1;

@@ -6,8 +6,9 @@
 
 namespace gtopk {
 
-// Sample tile t of a row covers [t*tile_stride, t*tile_stride + 256) (clipped to m).  A
-// block of 1024 threads takes four tiles per round, eight rounds of loads in flight.
+// Sample tile t of a row covers [t*tile_stride, t*tile_stride + 64) (clipped to m): one
+// wave per tile.  A block of 1024 threads takes sixteen tiles per round and keeps eight
+// rounds of loads in flight.
 __global__ __launch_bounds__(kSampleBlock) void k_sample(
         const float* __restrict__ grad, const float* __restrict__ res, uint32_t m, int64_t stride,
         uint32_t tile_stride, uint32_t n_tiles, uint32_t* __restrict__ samp_hist) {

@@ -1,0 +1,60 @@
+"""GPU parity at the configs' FULL sizes, in the launch configuration bench.py times
+(gtopk_step on all P workers at once, residual carried from step to step): every
+output of every worker is compared bit for bit with the CPU oracle.  The oracle's
+per-worker calls run in a thread pool only to keep the wall time down; each call is
+the plain oracle function."""
+import os
+from concurrent.futures import ThreadPoolExecutor
+
+import numpy as np
+import pytest
+
+from oracle import gtopk_oracle as orc
+from paper_1901_04359_amd import workloads as W
+from tests.gpu_harness import Device, bits_equal, first_diff, say, idx_np, val_np
+
+pytestmark = pytest.mark.gpu
+
+THREADS = min(16, os.cpu_count() or 8)
+
+
+def oracle_step_parallel(res, grad, k):
+    P = grad.shape[0]
+    with ThreadPoolExecutor(max_workers=THREADS) as ex:
+        sel = list(ex.map(lambda w: orc.local_select(res[w], grad[w], k), range(P)))
+    loc_idx = [s[0] for s in sel]
+    loc_val = [s[1] for s in sel]
+    g_idx, g_val = orc.tree(loc_idx, loc_val, k)
+    with ThreadPoolExecutor(max_workers=THREADS) as ex:
+        out = list(ex.map(lambda w: orc.residual_restore(sel[w][2], loc_idx[w], loc_val[w], g_idx),
+                          range(P)))
+    return loc_idx, loc_val, g_idx, g_val, out
+
+
+@pytest.mark.parametrize("name,iters", [("C3", 2), ("C4a", 2), ("C4b", 1), ("C5", 1)])
+def test_full_size_step(name, iters):
+    cfg = W.CONFIGS[name]
+    P, m, k = cfg.P, cfg.m, cfg.k
+    dev = Device(P, m, k)
+    res = np.zeros((P, m), dtype=np.float32)
+    for it in range(iters):
+        say(f"full size {name} it={it}: generating P={P} m={m}")
+        g = W.gradients(cfg, it, threads=THREADS)
+        dev.set_grad(g)
+        say(f"full size {name} it={it}: gtopk_step k={k}")
+        gi, gv = dev.step()
+        li, lv = idx_np(dev.loc_idx), val_np(dev.loc_val)
+        out = dev.residual()
+        say(f"full size {name} it={it}: oracle")
+        o_li, o_lv, o_gi, o_gv, o_res = oracle_step_parallel(res, g, k)
+        for w in range(P):
+            assert np.array_equal(li[w], o_li[w]), f"it={it} w={w} loc_idx {first_diff(li[w], o_li[w])}"
+            assert bits_equal(lv[w], o_lv[w]), f"it={it} w={w} loc_val {first_diff(lv[w], o_lv[w])}"
+        assert np.array_equal(gi, o_gi), f"it={it} g_idx {first_diff(gi, o_gi)}"
+        assert bits_equal(gv, o_gv), f"it={it} g_val {first_diff(gv, o_gv)}"
+        for w in range(P):
+            assert bits_equal(out[w], o_res[w]), f"it={it} w={w} residual {first_diff(out[w], o_res[w])}"
+            res[w] = o_res[w]
+        # every worker must have been served from its candidate list (the timed path)
+        counts, cap = dev.B.gtopk_debug_candidate_counts(dev.ws, m, k, P)
+        assert all(k <= c <= cap for c in counts), (name, it, min(counts), max(counts), cap)
