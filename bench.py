@@ -73,6 +73,9 @@ def main() -> int:
     ap.add_argument("--workload", default="C4a")
     ap.add_argument("--batches", type=int, default=2, help="distinct gradient batches staged in HBM")
     ap.add_argument("--cpu-workers", type=int, default=4, help="workers in the oracle sample (0 = skip)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="only run a plain 1 GiB device-to-device copy a few times (reference "
+                         "reading for the rocprofv3 FETCH_SIZE / WRITE_SIZE counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (all P workers are buffers on one device); "
@@ -87,6 +90,15 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
+    if args.copy_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda")      # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4,
+                          "copies": 5}))
+        return 0
     cfg = W.CONFIGS[args.workload]
     P, m, k = cfg.P, cfg.m, cfg.k
     K, Wm = args.steps, args.warmup
