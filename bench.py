@@ -48,9 +48,20 @@ def read_traffic_note(workload: str):
     return None
 
 
-def cpu_baseline(cfg, n_workers: int):
+def cpu_baseline(cfg, n_workers: int, budget_s: float = 15.0):
+    """The oracle as it stands on the first n_workers workers of the config (a power of
+    two, so that the tree is a real one).  n_workers < 0: probe one worker's local
+    selection first and take as many workers as fit in about `budget_s` seconds."""
     from oracle import gtopk_oracle as orc
     from paper_1901_04359_amd import workloads as W
+    if n_workers < 0:
+        g1 = W.gradient(cfg, 0, 0)
+        t0 = time.perf_counter()
+        orc.local_select(np.zeros_like(g1), g1, cfg.k)
+        per_worker = max(time.perf_counter() - t0, 1e-3)
+        n_workers = 2
+        while n_workers * 2 <= cfg.P and n_workers * 2 * per_worker * 1.3 <= budget_s:
+            n_workers *= 2
     g = W.gradients(cfg, 0, workers=range(n_workers))
     r = np.zeros_like(g)
     t0 = time.perf_counter()
@@ -72,7 +83,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C4a")
     ap.add_argument("--batches", type=int, default=2, help="distinct gradient batches staged in HBM")
-    ap.add_argument("--cpu-workers", type=int, default=4, help="workers in the oracle sample (0 = skip)")
+    ap.add_argument("--cpu-workers", type=int, default=-1,
+                    help="workers in the oracle sample (0 = skip, -1 = as many as fit in ~15 s)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy a few times (reference "
                          "reading for the rocprofv3 FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -163,7 +175,7 @@ def main() -> int:
                      "algorithmic_bytes_per_launch": alg_bytes},
         "input_generation_s": round(t_gen, 1),
     }
-    if args.cpu_workers > 0:
+    if args.cpu_workers != 0:
         out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_workers)
     print(json.dumps(out))
     return 0
