@@ -50,17 +50,17 @@ struct Carver {
     }
 };
 
-// hist, list_cnt, grp_gt and inv_min are carved back to back so that one clear covers them
+// hist, list_cnt and grp_gt are carved back to back so that one clear covers them
 SelState carve_select(Carver& c, size_t sets, uint32_t list_cap, uint32_t maxgroups) {
     SelState s;
     s.hist = c.take<uint32_t>(sets * kHistBins);
     s.list_cnt = c.take<uint32_t>(sets);
     s.grp_gt = c.take<uint32_t>(sets * maxgroups);
-    s.inv_min = c.take<uint32_t>(2 * sets);
     s.d1 = c.take<uint32_t>(sets);
     s.krem = c.take<uint32_t>(sets);
     s.T = c.take<uint32_t>(sets);
     s.need = c.take<uint32_t>(sets);
+    s.T_out = nullptr;
     s.list = c.take<uint2>(sets * list_cap);
     s.off_gt = c.take<uint32_t>(sets * maxgroups);
     s.off_eq = c.take<uint32_t>(sets * maxgroups);
@@ -68,7 +68,7 @@ SelState carve_select(Carver& c, size_t sets, uint32_t list_cap, uint32_t maxgro
     s.maxgroups = maxgroups;
     return s;
 }
-// words from s.hist to the end of s.inv_min (padding included)
+// words from s.hist to the end of s.grp_gt (padding included)
 inline size_t select_clear_words(const SelState& s) { return (size_t)(s.d1 - s.hist); }
 
 // slots per group of an array of n slots: a multiple of 256, at least 1024, and large
@@ -83,6 +83,7 @@ struct MergeWs {
     SelState sel;
     uint32_t* m_idx;   // [pairs][2k]
     float* m_val;
+    uint32_t* tmin[2]; // [pairs] smallest key of each output set, alternating between rounds
     uint32_t L;
     size_t bytes;
 };
@@ -93,6 +94,8 @@ MergeWs carve_merge(Carver& c, uint32_t k, size_t pairs) {
     w.sel = carve_select(c, pairs, 2 * k, ceil_div(2ull * k, w.L));
     w.m_idx = c.take<uint32_t>(pairs * 2 * k);
     w.m_val = c.take<float>(pairs * 2 * k);
+    w.tmin[0] = c.take<uint32_t>(pairs);
+    w.tmin[1] = c.take<uint32_t>(pairs);
     w.bytes = c.off;
     return w;
 }
@@ -283,16 +286,26 @@ template <bool DIVIDE>
 void do_merge_batch(const uint32_t* a_idx, const float* a_val, const uint32_t* b_idx,
                     const float* b_val, uint32_t k, uint32_t batch, int64_t in_stride,
                     uint32_t* out_idx, float* out_val, int64_t out_stride, const MergeWs& w,
-                    float divisor, uint32_t* gbits, hipStream_t st) {
-    hipLaunchKernelGGL(k_union, dim3(ceil_div(k, kBlock), batch), dim3(kBlock), 0, st, a_idx, a_val,
-                       b_idx, b_val, k, in_stride, w.m_idx, w.m_val, w.sel.inv_min);
-    MergedSrc src{w.m_idx, w.m_val, 2 * k, w.L};
-    run_select<MergedSrc, false, DIVIDE>(src, w.sel, batch, k, 2ull * k, out_idx, out_val, out_stride,
+                    const uint32_t* in_min, uint32_t* out_min, float divisor, uint32_t* gbits,
+                    hipStream_t st) {
+    if (k <= 65536)
+        hipLaunchKernelGGL(k_union<1>, dim3(ceil_div(k, kBlock), batch), dim3(kBlock), 0, st, a_idx,
+                           a_val, b_idx, b_val, k, in_stride, w.m_idx, w.m_val);
+    else
+        hipLaunchKernelGGL(k_union<8>, dim3(ceil_div(k, kBlock * 8), batch), dim3(kBlock), 0, st, a_idx,
+                           a_val, b_idx, b_val, k, in_stride, w.m_idx, w.m_val);
+    MergedSrc src{w.m_idx, w.m_val, 2 * k, w.L, in_min};
+    SelState ss = w.sel;
+    ss.T_out = out_min;
+    run_select<MergedSrc, false, DIVIDE>(src, ss, batch, k, 2ull * k, out_idx, out_val, out_stride,
                                          nullptr, 0, divisor, gbits, st);
 }
 
-int do_tree(const uint32_t* loc_idx, const float* loc_val, uint32_t P, uint32_t k, uint32_t* g_idx,
-            float* g_val, const StepWs& w, uint32_t* gbits, bool pre_cleared, hipStream_t st) {
+// loc_min: the smallest key of each of the P input sets (the local selection's T), or NULL
+// when the caller supplied the sets
+int do_tree(const uint32_t* loc_idx, const float* loc_val, const uint32_t* loc_min, uint32_t P,
+            uint32_t k, uint32_t* g_idx, float* g_val, const StepWs& w, uint32_t* gbits,
+            bool pre_cleared, hipStream_t st) {
     const float divisor = (float)P;
     if (P == 1) {
         hipLaunchKernelGGL(k_copy_set, dim3(ceil_div(k, 256)), dim3(256), 0, st, loc_idx, loc_val, k,
@@ -307,14 +320,18 @@ int do_tree(const uint32_t* loc_idx, const float* loc_val, uint32_t P, uint32_t 
     const float* in_val = loc_val;
     uint32_t* ping_i = w.x_idx; float* ping_v = w.x_val;
     uint32_t* pong_i = w.y_idx; float* pong_v = w.y_val;
-    for (uint32_t pairs = P / 2; pairs >= 1; pairs /= 2) {
+    const uint32_t* in_min = loc_min;
+    int round = 0;
+    for (uint32_t pairs = P / 2; pairs >= 1; pairs /= 2, ++round) {
         const bool last = pairs == 1;
+        uint32_t* out_min = w.mrg.tmin[round & 1];
         if (last) {
             do_merge_batch<true>(in_idx, in_val, in_idx + k, in_val + k, k, 1, 2 * (int64_t)k, g_idx,
-                                 g_val, k, w.mrg, divisor, gbits, st);
+                                 g_val, k, w.mrg, in_min, out_min, divisor, gbits, st);
         } else {
             do_merge_batch<false>(in_idx, in_val, in_idx + k, in_val + k, k, pairs, 2 * (int64_t)k,
-                                  ping_i, ping_v, k, w.mrg, 1.0f, nullptr, st);
+                                  ping_i, ping_v, k, w.mrg, in_min, out_min, 1.0f, nullptr, st);
+            in_min = out_min;
             in_idx = ping_i; in_val = ping_v;
             uint32_t* ti = ping_i; ping_i = pong_i; pong_i = ti;
             float* tv = ping_v; ping_v = pong_v; pong_v = tv;
@@ -377,7 +394,7 @@ int gtopk_merge(const uint32_t* a_idx, const float* a_val, const uint32_t* b_idx
     hipStream_t st = (hipStream_t)stream;
     zero_async(st, w.sel.hist, select_clear_words(w.sel));
     do_merge_batch<false>(a_idx, a_val, b_idx, b_val, (uint32_t)k, (uint32_t)batch, in_stride,
-                          out_idx, out_val, out_stride, w, 1.0f, nullptr, st);
+                          out_idx, out_val, out_stride, w, nullptr, nullptr, 1.0f, nullptr, st);
     return launch_status();
 }
 
@@ -391,8 +408,8 @@ int gtopk_tree(const uint32_t* loc_idx, const float* loc_val, int32_t P, int32_t
     // the tree's scratch sits inside the step workspace; m only sizes the parts it does not use
     const StepWs w = carve_step(ws, (int64_t)k, (uint32_t)k, (uint32_t)P);
     if (ws_bytes < w.bytes) return GTOPK_EWORKSPACE;
-    return do_tree(loc_idx, loc_val, (uint32_t)P, (uint32_t)k, g_idx, g_val, w, nullptr, false,
-                   (hipStream_t)stream);
+    return do_tree(loc_idx, loc_val, nullptr, (uint32_t)P, (uint32_t)k, g_idx, g_val, w, nullptr,
+                   false, (hipStream_t)stream);
 }
 
 int gtopk_residual_restore(float* residual, int64_t m, int64_t stride, int32_t P, int32_t k,
@@ -433,7 +450,7 @@ int gtopk_step(const float* grad, float* residual, int64_t m, int64_t stride, in
                              true, st, armed);
     if (rc != GTOPK_OK) return rc;
     mark_stage(3, armed, st);
-    rc = do_tree(li, lv, (uint32_t)P, (uint32_t)k, g_idx, g_val, w, w.gbits, true, st);
+    rc = do_tree(li, lv, w.sel.T, (uint32_t)P, (uint32_t)k, g_idx, g_val, w, w.gbits, true, st);
     if (rc != GTOPK_OK) return rc;
     mark_stage(4, armed, st);
     hipLaunchKernelGGL(k_restore_fused, dim3(ceil_div((uint32_t)k, kBlock), (uint32_t)P), dim3(kBlock),

@@ -50,35 +50,24 @@ __device__ __forceinline__ uint32_t count_below_in(const uint32_t* __restrict__ 
     return lo;
 }
 
-__device__ __forceinline__ uint32_t wave_min(uint32_t v) {
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) {
-        const uint32_t o = __shfl_xor(v, d);
-        v = o < v ? o : v;
-    }
-    return v;
-}
-
 // Entry x of A goes to slot x + #{B < A[x]}, entry y of B to slot y + #{A <= B[y]}:
 // a bijection onto [0, 2k) that lists the union in index order, A's copy first
 // where both hold an index.  A's copy then carries the sum (one fp32 add) and B's
 // slot becomes a tombstone.
-// A block takes 256 consecutive entries of A and of B.  Its four waves first find, each
-// with one 64-ary search, the counts for the block's first and last entry of either
-// side; every thread then searches only between those two counts, a short range that
-// the block's threads share in cache.  The block also folds the smallest key of its
-// entries of either operand into inv_min[pair][0..1] (as ~key under atomicMax, so that
-// a cleared word means "none yet").
+// A block takes 256*EPT consecutive entries of A and of B.  Its four waves first find,
+// each with one 64-ary search, the counts for the block's first and last entry of
+// either side; every thread then searches only between those two counts, a short range
+// that the block's threads share in cache.  EPT > 1 spreads the cost of the boundary
+// searches over more entries (large k).
+template <int EPT>
 __global__ __launch_bounds__(kBlock) void k_union(
         const uint32_t* __restrict__ a_idx, const float* __restrict__ a_val,
         const uint32_t* __restrict__ b_idx, const float* __restrict__ b_val, uint32_t k,
-        int64_t in_stride, uint32_t* __restrict__ m_idx, float* __restrict__ m_val,
-        uint32_t* __restrict__ inv_min) {
+        int64_t in_stride, uint32_t* __restrict__ m_idx, float* __restrict__ m_val) {
     __shared__ uint32_t s_bound[4];
-    __shared__ uint32_t s_min[2][kBlock / kWave];
     const int s = blockIdx.y;
-    const uint32_t x0 = blockIdx.x * kBlock;            // < k by the launch grid
-    const uint32_t x1 = x0 + kBlock - 1 < k ? x0 + kBlock - 1 : k - 1;
+    const uint32_t x0 = blockIdx.x * (kBlock * EPT);            // < k by the launch grid
+    const uint32_t x1 = x0 + kBlock * EPT - 1 < k ? x0 + kBlock * EPT - 1 : k - 1;
     const uint32_t* ai = a_idx + (int64_t)s * in_stride;
     const float* av = a_val + (int64_t)s * in_stride;
     const uint32_t* bi = b_idx + (int64_t)s * in_stride;
@@ -86,35 +75,81 @@ __global__ __launch_bounds__(kBlock) void k_union(
     uint32_t* mi = m_idx + (size_t)s * 2 * k;
     float* mv = m_val + (size_t)s * 2 * k;
     const uint32_t wave = threadIdx.x / kWave;
-    const uint32_t x = x0 + threadIdx.x;
-    const bool live = x < k;
-    // this thread's two entries (loads overlap with the boundary searches)
-    const uint32_t ia = live ? ai[x] : 0u, ib = live ? bi[x] : 0u;
-    const float fa = live ? av[x] : 0.0f, fb = live ? bv[x] : 0.0f;
+    // this thread's entries (loads overlap with the boundary searches)
+    uint32_t ia[EPT], ib[EPT];
+    float fa[EPT], fb[EPT];
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        const uint32_t x = x0 + j * kBlock + threadIdx.x;
+        const bool live = x < k;
+        ia[j] = live ? ai[x] : 0u;
+        ib[j] = live ? bi[x] : 0u;
+        fa[j] = live ? av[x] : 0.0f;
+        fb[j] = live ? bv[x] : 0.0f;
+    }
     uint32_t bound;
     if (wave == 0) bound = wave_count_below<false>(bi, k, ai[x0]);
     else if (wave == 1) bound = wave_count_below<false>(bi, k, ai[x1]);
     else if (wave == 2) bound = wave_count_below<true>(ai, k, bi[x0]);
     else bound = wave_count_below<true>(ai, k, bi[x1]);
-    const uint32_t ka = wave_min(live ? (__float_as_uint(fa) & kAbs) : 0xFFFFFFFFu);
-    const uint32_t kb = wave_min(live ? (__float_as_uint(fb) & kAbs) : 0xFFFFFFFFu);
-    if (lane_id() == 0) { s_bound[wave] = bound; s_min[0][wave] = ka; s_min[1][wave] = kb; }
+    if (lane_id() == 0) s_bound[wave] = bound;
     __syncthreads();
-    if (threadIdx.x < 2) {
-        uint32_t v = 0xFFFFFFFFu;
-        for (int i = 0; i < kBlock / kWave; ++i) v = s_min[threadIdx.x][i] < v ? s_min[threadIdx.x][i] : v;
-        atomicMax(&inv_min[2 * s + threadIdx.x], ~v);
+    // pa = #{B < ia} lies in [b_lo, b_hi], pb = #{A <= ib} in [a_lo, a_hi].  The searches
+    // read bi[b_lo .. b_hi-1]; the match test reads bi/bv[pa] (pa <= b_hi) and the duplicate
+    // test ai[pb-1] (pb-1 >= a_lo-1).  When those ranges fit, they are staged in LDS with
+    // coalesced loads and searched there; otherwise the same code reads global memory.
+    const uint32_t b_lo = s_bound[0], b_hi = s_bound[1], a_lo = s_bound[2], a_hi = s_bound[3];
+    constexpr uint32_t kCap = 2u * kBlock * EPT + 2u;
+    __shared__ uint32_t s_bi[kCap];
+    __shared__ float s_bv[kCap];
+    __shared__ uint32_t s_ai[kCap];
+    const uint32_t b_n = (b_hi < k ? b_hi + 1 : k) - b_lo;        // bi[b_lo .. min(b_hi, k-1)]
+    const uint32_t a_first = a_lo > 0 ? a_lo - 1 : 0;
+    const uint32_t a_n = a_hi - a_first;                          // ai[a_first .. a_hi-1]
+    const bool staged = b_n <= kCap && a_n <= kCap;               // block-uniform
+    if (staged) {
+        for (uint32_t i = threadIdx.x; i < b_n; i += kBlock) { s_bi[i] = bi[b_lo + i]; s_bv[i] = bv[b_lo + i]; }
+        for (uint32_t i = threadIdx.x; i < a_n; i += kBlock) s_ai[i] = ai[a_first + i];
+        __syncthreads();
     }
-    if (!live) return;
-    const uint32_t pa = count_below_in<false>(bi, s_bound[0], s_bound[1], ia);   // #{B < ia}
-    const uint32_t pb = count_below_in<true>(ai, s_bound[2], s_bound[3], ib);    // #{A <= ib}
-    float sum = fa;
-    if (pa < k && bi[pa] == ia) sum = sum + bv[pa];
-    mi[x + pa] = ia;
-    mv[x + pa] = sum;
-    const bool dup = pb > 0 && ai[pb - 1] == ib;
-    mi[x + pb] = dup ? kTomb : ib;
-    mv[x + pb] = fb;
+    auto B_idx = [&](uint32_t p) { return staged ? s_bi[p - b_lo] : bi[p]; };
+    auto B_val = [&](uint32_t p) { return staged ? s_bv[p - b_lo] : bv[p]; };
+    auto A_idx = [&](uint32_t p) { return staged ? s_ai[p - a_first] : ai[p]; };
+    // all 2*EPT binary searches of a thread advance together, one load each per step
+    uint32_t pa[EPT], pb[EPT], ha[EPT], hb[EPT];
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        pa[j] = b_lo; ha[j] = b_hi;
+        pb[j] = a_lo; hb[j] = a_hi;
+    }
+    const uint32_t ra = b_hi - b_lo, rb = a_hi - a_lo;
+    const uint32_t rmax = ra > rb ? ra : rb;
+    const int steps = rmax ? 32 - __builtin_clz(rmax) : 0;      // halvings until every range is empty
+    for (int it = 0; it < steps; ++it) {
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) {
+            if (pa[j] < ha[j]) {
+                const uint32_t mid = (pa[j] + ha[j]) >> 1;        // b_lo <= mid < b_hi
+                if (B_idx(mid) < ia[j]) pa[j] = mid + 1; else ha[j] = mid;
+            }
+            if (pb[j] < hb[j]) {
+                const uint32_t mid = (pb[j] + hb[j]) >> 1;        // a_lo <= mid < a_hi
+                if (A_idx(mid) <= ib[j]) pb[j] = mid + 1; else hb[j] = mid;
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        const uint32_t x = x0 + j * kBlock + threadIdx.x;
+        if (x >= k) continue;
+        float sum = fa[j];
+        if (pa[j] < k && B_idx(pa[j]) == ia[j]) sum = sum + B_val(pa[j]);
+        mi[x + pa[j]] = ia[j];
+        mv[x + pa[j]] = sum;
+        const bool dup = pb[j] > 0 && A_idx(pb[j] - 1) == ib[j];
+        mi[x + pb[j]] = dup ? kTomb : ib[j];
+        mv[x + pb[j]] = fb[j];
+    }
 }
 
 // P == 1: the tree has no round; the global set is worker 0's set divided by 1.

@@ -24,11 +24,11 @@ struct SelState {
     uint32_t* hist;       // [sets][4096]
     uint32_t* list_cnt;   // [sets]
     uint32_t* grp_gt;     // [sets][maxgroups] entries of the group above bin d1
-    uint32_t* inv_min;    // [sets][2] ~(smallest key) of either merge operand (0 = none seen)
     // --------------------------------------------------------------------------------
     uint32_t* d1;         // [sets] bin of the k-th key
     uint32_t* krem;       // [sets] rank of the k-th key inside bin d1 (1-based, from the top)
-    uint32_t* T;          // [sets] the k-th largest key
+    uint32_t* T;          // [sets] the k-th largest key = the smallest key of the output set
+    uint32_t* T_out;      // [sets] optional second copy of T that outlives the next select (or NULL)
     uint32_t* need;       // [sets] entries with key == T to take (>= 1)
     uint2* list;          // [sets][list_cap]  (key, group)
     uint32_t* off_gt;     // [sets][maxgroups] exclusive scans over groups
@@ -126,19 +126,21 @@ struct CandSrc {
 // Every key of the union that is a plain copy of an operand's entry is at least that
 // operand's smallest key, so the larger of the two smallest keys bounds the k-th key of
 // the union from below (sums that cancel can fall under it; they land in bin 0).
+// in_min[2s], in_min[2s+1] are those smallest keys when the operands came out of a
+// select of this library (its T); NULL when the caller supplied the sets.
 struct MergedSrc {
     static constexpr bool kIdentity = true;
     static constexpr bool kRunScan = false;
     const uint32_t* idx;
     const float* val;
     uint32_t n, L;       // L slots per group
+    const uint32_t* in_min;
     __device__ bool dense(int) const { return false; }
     __device__ uint32_t nphys(int, bool) const { return n; }
     __device__ uint32_t group_slots(bool) const { return L; }
-    __device__ Digit digit(int s, bool, const SelState& st) const {
-        const uint32_t ia = st.inv_min[2 * s], ib = st.inv_min[2 * s + 1];
-        if (ia == 0u || ib == 0u) return Digit{0u, (uint32_t)kCoarseShift};
-        const uint32_t ma = ~ia, mb = ~ib;
+    __device__ Digit digit(int s, bool, const SelState&) const {
+        if (!in_min) return Digit{0u, (uint32_t)kCoarseShift};
+        const uint32_t ma = in_min[2 * s], mb = in_min[2 * s + 1];
         return Digit{ma > mb ? ma : mb, (uint32_t)kFineShift};
     }
     __device__ bool fetch_phys(int s, bool, uint32_t p, uint32_t& i, uint32_t& bits) const {
@@ -444,9 +446,8 @@ __global__ __launch_bounds__(1024) void k_finish(Src src, SelState st) {
     if (t == 0) {
         st.T[s] = T;
         st.need[s] = need;
+        if (st.T_out) st.T_out[s] = T;
         st.list_cnt[s] = 0u;
-        st.inv_min[2 * s] = 0u;
-        st.inv_min[2 * s + 1] = 0u;
     }
 }
 
