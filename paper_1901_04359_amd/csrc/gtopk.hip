@@ -288,12 +288,9 @@ void do_merge_batch(const uint32_t* a_idx, const float* a_val, const uint32_t* b
                     uint32_t* out_idx, float* out_val, int64_t out_stride, const MergeWs& w,
                     const uint32_t* in_min, uint32_t* out_min, float divisor, uint32_t* gbits,
                     hipStream_t st) {
-    if (k <= 65536)
-        hipLaunchKernelGGL(k_union<1>, dim3(ceil_div(k, kBlock), batch), dim3(kBlock), 0, st, a_idx,
-                           a_val, b_idx, b_val, k, in_stride, w.m_idx, w.m_val);
-    else
-        hipLaunchKernelGGL(k_union<8>, dim3(ceil_div(k, kBlock * 8), batch), dim3(kBlock), 0, st, a_idx,
-                           a_val, b_idx, b_val, k, in_stride, w.m_idx, w.m_val);
+    // one entry of either operand per thread measured best at k = 25,557 and k = 255,570
+    hipLaunchKernelGGL(k_union<1>, dim3(ceil_div(k, kBlock), batch), dim3(kBlock), 0, st, a_idx, a_val,
+                       b_idx, b_val, k, in_stride, w.m_idx, w.m_val);
     MergedSrc src{w.m_idx, w.m_val, 2 * k, w.L, in_min};
     SelState ss = w.sel;
     ss.T_out = out_min;

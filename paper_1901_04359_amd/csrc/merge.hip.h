@@ -38,18 +38,6 @@ __device__ inline uint32_t wave_count_below(const uint32_t* __restrict__ a, uint
     return lo;
 }
 
-// count of elements of a below x (UPPER: below or equal), known to lie in [lo, hi]
-template <bool UPPER>
-__device__ __forceinline__ uint32_t count_below_in(const uint32_t* __restrict__ a, uint32_t lo,
-                                                   uint32_t hi, uint32_t x) {
-    while (lo < hi) {
-        const uint32_t mid = (lo + hi) >> 1;
-        const uint32_t v = a[mid];
-        if (UPPER ? v <= x : v < x) lo = mid + 1; else hi = mid;
-    }
-    return lo;
-}
-
 // Entry x of A goes to slot x + #{B < A[x]}, entry y of B to slot y + #{A <= B[y]}:
 // a bijection onto [0, 2k) that lists the union in index order, A's copy first
 // where both hold an index.  A's copy then carries the sum (one fp32 add) and B's
@@ -108,8 +96,23 @@ __global__ __launch_bounds__(kBlock) void k_union(
     const uint32_t a_n = a_hi - a_first;                          // ai[a_first .. a_hi-1]
     const bool staged = b_n <= kCap && a_n <= kCap;               // block-uniform
     if (staged) {
-        for (uint32_t i = threadIdx.x; i < b_n; i += kBlock) { s_bi[i] = bi[b_lo + i]; s_bv[i] = bv[b_lo + i]; }
-        for (uint32_t i = threadIdx.x; i < a_n; i += kBlock) s_ai[i] = ai[a_first + i];
+        // all loads first, then the LDS stores: one memory round trip for the whole stage
+        constexpr int kRounds = (int)((kCap + kBlock - 1) / kBlock);
+        uint32_t tb[kRounds], ta[kRounds];
+        float tv[kRounds];
+#pragma unroll
+        for (int r = 0; r < kRounds; ++r) {
+            const uint32_t i = r * kBlock + threadIdx.x;
+            tb[r] = i < b_n ? bi[b_lo + i] : 0u;
+            tv[r] = i < b_n ? bv[b_lo + i] : 0.0f;
+            ta[r] = i < a_n ? ai[a_first + i] : 0u;
+        }
+#pragma unroll
+        for (int r = 0; r < kRounds; ++r) {
+            const uint32_t i = r * kBlock + threadIdx.x;
+            if (i < b_n) { s_bi[i] = tb[r]; s_bv[i] = tv[r]; }
+            if (i < a_n) s_ai[i] = ta[r];
+        }
         __syncthreads();
     }
     auto B_idx = [&](uint32_t p) { return staged ? s_bi[p - b_lo] : bi[p]; };
