@@ -131,6 +131,24 @@ int gtopk_step(const float* grad, float* residual, int64_t m, int64_t stride,
                void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * Model update, Algorithm 4 line 11: W_i = W_{i-1} - eta * G~_i, applied at the k entries
+ * of the global set (every other entry of G~_i is zero): for each of `copies` replicas
+ * of the weights (row c starts at weights + c*stride, m floats; in the paper every
+ * worker holds one replica, on one GPU one is enough),
+ *     weights[c][g_idx[t]] = weights[c][g_idx[t]] - lr * g_val[t]
+ * as one fp32 multiply followed by one fp32 subtract.  g_idx must be distinct and < m.
+ * Needs no workspace.
+ */
+int gtopk_apply_update(float* weights, int64_t m, int64_t stride, int32_t copies, int32_t k,
+                       const uint32_t* g_idx, const float* g_val, float lr, void* stream);
+
+/*
+ * The dense gMask that gTopKAllReduce returns (Algorithm 3 lines 20-22): mask[i] = 1 for
+ * every i in g_idx, 0 elsewhere; mask has m bytes (16-byte aligned).  Needs no workspace.
+ */
+int gtopk_dense_mask(const uint32_t* g_idx, int32_t k, int64_t m, uint8_t* mask, void* stream);
+
+/*
  * Instrumentation for benchmarks (not part of the method): arm the NEXT
  * gtopk_step call on this process to record the given HOST handles of six
  * hipEvent_t (created by the caller, passed as void*) on its stream at its

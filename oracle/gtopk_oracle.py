@@ -14,6 +14,7 @@ order, so that it can be checked against the paper by eye:
   * Eq. 3 (S-SGD averages over the P workers)                  -> the /P in `tree`
   * Algorithm 3 lines 19-23 (broadcast, gMask) and Algorithm 4 line 10
     (extra residual)                                            -> `residual_restore`
+  * Algorithm 4 line 11 (model update) and the dense gMask      -> `apply_update`, `dense_mask`
 
 Precision: the paper trains in 32-bit floating point (note under Table III), so
 every add here is ONE IEEE-754 binary32 round-to-nearest add, in a fixed order;
@@ -184,6 +185,22 @@ def residual_restore(residual: np.ndarray, loc_idx: np.ndarray, loc_val: np.ndar
     back = ~globally_kept
     out[loc_idx[back]] = (out[loc_idx[back]] + loc_val[back]).astype(np.float32)
     return out
+
+
+def apply_update(weights: np.ndarray, g_idx: np.ndarray, g_val: np.ndarray, lr) -> np.ndarray:
+    """Algorithm 4 line 11: W_i = W_{i-1} - eta * G~_i.  G~_i is zero outside g_idx, so
+    only those k weights move: one fp32 multiply, then one fp32 subtract."""
+    out = weights.copy()
+    prod = (np.float32(lr) * g_val.astype(np.float32)).astype(np.float32)
+    out[g_idx] = (out[g_idx] - prod).astype(np.float32)
+    return out
+
+
+def dense_mask(g_idx: np.ndarray, m: int) -> np.ndarray:
+    """Algorithm 3 lines 20-22: gMask has m entries, 1 at the global indices, 0 elsewhere."""
+    mask = np.zeros(m, dtype=np.uint8)
+    mask[g_idx] = 1
+    return mask
 
 
 def step(residual: np.ndarray, grad: np.ndarray, k: int):

@@ -19,6 +19,7 @@ _lib: Optional[ctypes.CDLL] = None
 EXPORTS = (
     "gtopk_status_string", "gtopk_workspace_bytes", "gtopk_merge_workspace_bytes",
     "gtopk_local_select", "gtopk_merge", "gtopk_tree", "gtopk_residual_restore", "gtopk_step",
+    "gtopk_apply_update", "gtopk_dense_mask",
     "gtopk_arm_stage_events", "gtopk_debug_candidate_counts",
 )
 
@@ -63,6 +64,10 @@ def load() -> ctypes.CDLL:
     lib.gtopk_residual_restore.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp]
     lib.gtopk_step.restype = c.c_int
     lib.gtopk_step.argtypes = [vp, vp, i64, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.gtopk_apply_update.restype = c.c_int
+    lib.gtopk_apply_update.argtypes = [vp, i64, i64, i32, i32, vp, vp, c.c_float, vp]
+    lib.gtopk_dense_mask.restype = c.c_int
+    lib.gtopk_dense_mask.argtypes = [vp, i32, i64, vp, vp]
     lib.gtopk_arm_stage_events.restype = c.c_int
     lib.gtopk_arm_stage_events.argtypes = [c.POINTER(c.c_void_p)]
     lib.gtopk_debug_candidate_counts.restype = c.c_int
@@ -200,6 +205,25 @@ def gtopk_step(grad, residual, k: int, g_idx, g_val, loc_idx, loc_val, ws) -> No
         _ptr(loc_val, torch.float32, "loc_val", allow_none=True),
         _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream())
     _check(rc, "gtopk_step")
+
+
+def gtopk_apply_update(weights, k: int, g_idx, g_val, lr: float) -> None:
+    """weights: [copies][m] (rows contiguous) or [m]."""
+    torch = _torch()
+    w2 = weights if weights.dim() == 2 else weights.view(1, -1)
+    m, stride = _rows(w2, "weights")
+    rc = load().gtopk_apply_update(
+        _ptr(w2, torch.float32, "weights"), m, stride, w2.shape[0], k,
+        _ptr(g_idx, torch.int32, "g_idx"), _ptr(g_val, torch.float32, "g_val"),
+        ctypes.c_float(lr), _stream())
+    _check(rc, "gtopk_apply_update")
+
+
+def gtopk_dense_mask(g_idx, k: int, mask) -> None:
+    torch = _torch()
+    rc = load().gtopk_dense_mask(_ptr(g_idx, torch.int32, "g_idx"), k, mask.numel(),
+                                 _ptr(mask, torch.uint8, "mask"), _stream())
+    _check(rc, "gtopk_dense_mask")
 
 
 def gtopk_arm_stage_events(events) -> None:

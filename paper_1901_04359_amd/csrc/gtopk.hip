@@ -26,6 +26,7 @@
 #include "stream_pass.hip.h"
 #include "select.hip.h"
 #include "merge.hip.h"
+#include "apply.hip.h"
 
 using namespace gtopk;
 
@@ -455,6 +456,32 @@ int gtopk_step(const float* grad, float* residual, int64_t m, int64_t stride, in
     rc = launch_status();
     mark_stage(5, armed, st);
     return rc;
+}
+
+int gtopk_apply_update(float* weights, int64_t m, int64_t stride, int32_t copies, int32_t k,
+                       const uint32_t* g_idx, const float* g_val, float lr, void* stream) {
+    if (!weights || !g_idx || !g_val) return GTOPK_EINVAL;
+    if (m < 1 || m > ((int64_t)1 << 31) || k < 1 || k > m || stride < m || copies < 1 ||
+        copies > 65535)
+        return GTOPK_EINVAL;
+    if (!aligned16(weights) || !aligned16(g_idx) || !aligned16(g_val)) return GTOPK_EALIGN;
+    hipLaunchKernelGGL(k_apply_update, dim3(ceil_div((uint32_t)k, kBlock), (uint32_t)copies),
+                       dim3(kBlock), 0, (hipStream_t)stream, weights, stride, (uint32_t)k, g_idx, g_val,
+                       lr);
+    return launch_status();
+}
+
+int gtopk_dense_mask(const uint32_t* g_idx, int32_t k, int64_t m, uint8_t* mask, void* stream) {
+    if (!g_idx || !mask) return GTOPK_EINVAL;
+    if (m < 1 || m > ((int64_t)1 << 31) || k < 1 || k > m) return GTOPK_EINVAL;
+    if (!aligned16(g_idx) || !aligned16(mask)) return GTOPK_EALIGN;
+    hipStream_t st = (hipStream_t)stream;
+    uint32_t blocks = ceil_div((uint64_t)m, 256 * 16);
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(k_mask_clear, dim3(blocks), dim3(256), 0, st, mask, (uint64_t)m);
+    hipLaunchKernelGGL(k_mask_set, dim3(ceil_div((uint32_t)k, kBlock)), dim3(kBlock), 0, st, mask,
+                       (uint32_t)k, g_idx);
+    return launch_status();
 }
 
 int gtopk_debug_candidate_counts(const void* ws, int64_t m, int32_t k, int32_t P,

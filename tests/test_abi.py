@@ -111,3 +111,21 @@ def test_binding_refuses_cpu_tensors():
     t = torch.zeros(2, 8)
     with pytest.raises(TypeError):
         B.gtopk_residual_restore(t, 1, t.int(), t, t.int())
+
+
+def test_argument_errors_apply_and_mask():
+    lib = B.load()
+    ap = lambda **kw: lib.gtopk_apply_update(
+        kw.get("w", FAKE), kw.get("m", 100), kw.get("stride", 100), kw.get("copies", 1),
+        kw.get("k", 10), FAKE, kw.get("gv", FAKE), ctypes.c_float(0.1), None)
+    assert ap(w=None) == B.GTOPK_EINVAL
+    assert ap(k=101) == B.GTOPK_EINVAL
+    assert ap(copies=0) == B.GTOPK_EINVAL
+    assert ap(stride=10) == B.GTOPK_EINVAL
+    assert ap(gv=ODD) == B.GTOPK_EALIGN
+    mk = lambda **kw: lib.gtopk_dense_mask(kw.get("g", FAKE), kw.get("k", 10), kw.get("m", 100),
+                                           kw.get("mask", FAKE), None)
+    assert mk(g=None) == B.GTOPK_EINVAL
+    assert mk(k=0) == B.GTOPK_EINVAL
+    assert mk(m=5) == B.GTOPK_EINVAL
+    assert mk(mask=ODD) == B.GTOPK_EALIGN

@@ -254,3 +254,42 @@ def test_candidate_path_is_the_one_exercised():
     dev.local_select()
     counts, cap = B.gtopk_debug_candidate_counts(dev.ws, m, k, P)
     assert all(c > cap for c in counts), (counts, cap)
+
+
+@pytest.mark.parametrize("m,k,copies", [(1000, 1000, 1), (65_536, 66, 4), (2_000_003, 20_000, 2)])
+def test_apply_update_and_dense_mask(m, k, copies):
+    import torch
+    from paper_1901_04359_amd import binding as B
+    rng = np.random.default_rng(m + k)
+    Wt = rng.standard_normal((copies, m)).astype(np.float32)
+    g_idx = np.sort(rng.choice(m, k, replace=False)).astype(np.uint32)
+    g_val = (rng.standard_normal(k) * 1e-3).astype(np.float32)
+    g_val[::11] = 0.0
+    d_w = to_dev(Wt)
+    say(f"apply_update m={m} k={k} copies={copies}")
+    for lr in (0.1, 0.01):
+        B.gtopk_apply_update(d_w, k, to_dev(g_idx), to_dev(g_val), lr)
+        torch.cuda.synchronize()
+        for c in range(copies):
+            Wt[c] = orc.apply_update(Wt[c], g_idx, g_val, lr)
+        out = d_w.cpu().numpy()
+        assert bits_equal(out, Wt), first_diff(out, Wt)
+    mask = torch.full((m,), 7, dtype=torch.uint8, device="cuda")
+    B.gtopk_dense_mask(to_dev(g_idx), k, mask)
+    torch.cuda.synchronize()
+    assert np.array_equal(mask.cpu().numpy(), orc.dense_mask(g_idx, m))
+
+
+@pytest.mark.parametrize("rho", [0.25, 0.0725, 0.015, 0.005, 0.004, 0.0005])
+def test_step_density_schedule(rho):
+    """The densities of the paper's warm-up schedule (Section IV-B: 0.25, 0.0725, 0.015,
+    0.004), the LSTM density 0.005 and the smallest density of its sensitivity study."""
+    m, P = 1_000_003, 4
+    cfg = W.scaled(W.CONFIGS["C4a"], m, k=max(1, int(round(rho * m))), P=P, name=f"rho={rho}")
+    check_steps(cfg, lambda it: W.gradients(cfg, it), 2, cfg.name)
+    from paper_1901_04359_amd import binding as B
+    dev = Device(P, cfg.m, cfg.k)
+    dev.set_grad(W.gradients(cfg, 0))
+    dev.local_select()
+    counts, cap = B.gtopk_debug_candidate_counts(dev.ws, cfg.m, cfg.k, P)
+    assert all(cfg.k <= c <= cap for c in counts), (rho, counts, cap, cfg.k)

@@ -378,7 +378,39 @@ def pin_step_feedback_and_bounds():
         res = out["residual"]
 
 
-PINS = [pin_local_select_bruteforce, pin_local_select_library_topk, pin_local_select_invariants,
+def pin_apply_update_and_mask():
+    """Model update against per-element Python arithmetic with explicit float32 rounding of
+    each of the two operations; eta = 0 leaves W unchanged; a power-of-two eta is exact."""
+    rng = np.random.default_rng(41)
+    m, k = 300, 37
+    Wt = rng.standard_normal(m).astype(np.float32)
+    g_idx = np.sort(rng.choice(m, k, replace=False)).astype(np.uint32)
+    g_val = rng.standard_normal(k).astype(np.float32)
+    for lr in (0.1, 0.01, 1.0, 0.0, 0.25):
+        out = orc.apply_update(Wt, g_idx, g_val, lr)
+        exp = Wt.copy()
+        for i, v in zip(g_idx.tolist(), g_val.tolist()):
+            p = f32(f32(lr) * f32(v))
+            exp[i] = f32(f32(exp[i]) - p)
+        assert same_bits(out, exp), lr
+        untouched = np.ones(m, dtype=bool)
+        untouched[g_idx] = False
+        assert same_bits(out[untouched], Wt[untouched])
+    assert same_bits(orc.apply_update(Wt, g_idx, g_val, 0.0), Wt)
+    quarter = orc.apply_update(np.zeros(m, dtype=np.float32), g_idx, g_val, 0.25)
+    assert same_bits(quarter[g_idx] * f32(-4), g_val)
+    mask = orc.dense_mask(g_idx, m)
+    assert mask.dtype == np.uint8 and mask.sum() == k
+    assert [i for i in range(m) if mask[i]] == g_idx.tolist()
+
+
+def _mut_apply_plus(weights, g_idx, g_val, lr):
+    out = weights.copy()
+    out[g_idx] = out[g_idx] + np.float32(lr) * g_val
+    return out
+
+
+PINS = [pin_apply_update_and_mask, pin_local_select_bruteforce, pin_local_select_library_topk, pin_local_select_invariants,
         pin_local_select_special_k, pin_denormals_not_flushed, pin_merge_dense_definition,
         pin_merge_special_supports, pin_tree_p1_p2, pin_tree_shared_support,
         pin_tree_order_by_composition, pin_tree_not_the_dense_topk, pin_average_is_exact_scale,
@@ -465,6 +497,7 @@ MUTANTS = [
     ("residual_restore", _mut_restore_all),
     ("residual_restore", _mut_restore_none),
     ("residual_restore", _mut_restore_store),
+    ("apply_update", _mut_apply_plus),
 ]
 
 
