@@ -83,6 +83,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="C4a")
     ap.add_argument("--batches", type=int, default=2, help="distinct gradient batches staged in HBM")
+    ap.add_argument("--k", type=int, default=0, help="override the workload's k (density studies)")
     ap.add_argument("--cpu-workers", type=int, default=-1,
                     help="workers in the oracle sample (0 = skip, -1 = as many as fit in ~15 s)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -112,6 +113,8 @@ def main() -> int:
                           "copies": 5}))
         return 0
     cfg = W.CONFIGS[args.workload]
+    if args.k > 0:
+        cfg = W.scaled(cfg, cfg.m, k=args.k, name=f"{cfg.name}/k={args.k}")
     P, m, k = cfg.P, cfg.m, cfg.k
     K, Wm = args.steps, args.warmup
 
@@ -157,12 +160,14 @@ def main() -> int:
     alg_bytes = 12.0 * P * m
     achieved = alg_bytes / (kern_ms * 1e-3) / 1e9
     traffic = read_traffic_note(cfg.name)
+    label = {"C1": "tiny", "C2": "ResNet-20-sized", "C3": "VGG-16-sized", "C4a": "ResNet-50-sized",
+             "C4b": "ResNet-50-sized", "C5": "AlexNet-sized"}.get(args.workload, "")
     out = {
         "metric": "gTop-k step throughput (P*m gradient elem/s) + achieved HBM GB/s vs peak",
         "value": value, "unit": "gradient elements/s", "n_gpus": 1, "steps": K, "warmup": Wm,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: ResNet-50-sized, m={m} fp32 per worker, P={P} workers "
+        "config": {"workload": f"{cfg.name}: {label}, m={m} fp32 per worker, P={P} workers "
                                f"on one GPU, k={k} (rho={cfg.rho:.4g}), {len(grads)} gradient "
                                f"batches cycled, residual carried across steps",
                    "m": m, "P": P, "k": k},

@@ -293,3 +293,59 @@ def test_step_density_schedule(rho):
     dev.local_select()
     counts, cap = B.gtopk_debug_candidate_counts(dev.ws, cfg.m, cfg.k, P)
     assert all(cfg.k <= c <= cap for c in counts), (rho, counts, cap, cfg.k)
+
+
+@pytest.mark.parametrize("P,m,k,stride", [
+    (1, 100_000, 100, None),          # P = 1: no tree round, g = loc / 1
+    (2, 5_000, 5_000, None),          # k = m: everything is selected everywhere
+    (4, 32_768, 33, None),            # exactly one streaming block per worker
+    (4, 32_769, 33, 32_771),          # one element into a second block; rows not 16-byte aligned
+    (8, 131_071, 1, None),            # k = 1
+    (64, 40_000, 40, None),           # more workers than the configs use (six rounds)
+    (4, 300_001, 3_000, 300_005),     # padded rows, odd stride
+])
+def test_step_shapes(P, m, k, stride):
+    rng = np.random.default_rng(P * 7 + m + k)
+    dev = Device(P, m, k, stride=stride)
+    res = np.zeros((P, m), dtype=np.float32)
+    dev.set_res(res)
+    for it in range(2):
+        g = (rng.standard_normal((P, m)) * 1e-3).astype(np.float32)
+        dev.set_grad(g)
+        say(f"step shapes P={P} m={m} k={k} stride={stride} it={it}")
+        gi, gv = dev.step()
+        exp = orc.step(res, g, k)
+        assert np.array_equal(idx_np(dev.loc_idx), exp["loc_idx"])
+        assert bits_equal(val_np(dev.loc_val), exp["loc_val"])
+        assert np.array_equal(gi, exp["g_idx"]) and bits_equal(gv, exp["g_val"])
+        out = dev.residual()
+        assert bits_equal(out, exp["residual"]), first_diff(out, exp["residual"])
+        res = exp["residual"]
+    if stride is not None:      # the padding between rows must be untouched
+        pad = dev.res_buf[: P * stride].view(P, stride)[:, m:].cpu().numpy()
+        assert not pad.any()
+
+
+def test_step_matches_the_three_calls():
+    """gtopk_step (which fuses zeroing and restore) against gtopk_local_select + gtopk_tree +
+    gtopk_residual_restore on the same inputs, including -0.0 entries that get selected."""
+    P, m, k = 4, 50_000, 30_000            # k so large that zeros and -0.0 are selected
+    rng = np.random.default_rng(99)
+    g = (rng.standard_normal((P, m)) * 1e-3).astype(np.float32)
+    g[:, ::2] = 0.0
+    g[:, ::6] = -0.0
+    a = Device(P, m, k)
+    b = Device(P, m, k)
+    for dev in (a, b):
+        dev.set_grad(g)
+    say("step vs three calls")
+    gi_a, gv_a = a.step()
+    b.local_select()
+    gi_b, gv_b = b.tree()
+    b.restore()
+    assert np.array_equal(gi_a, gi_b) and bits_equal(gv_a, gv_b)
+    assert np.array_equal(idx_np(a.loc_idx), idx_np(b.loc_idx))
+    assert bits_equal(val_np(a.loc_val), val_np(b.loc_val))
+    assert bits_equal(a.residual(), b.residual()), first_diff(a.residual(), b.residual())
+    exp = orc.step(np.zeros((P, m), dtype=np.float32), g, k)
+    assert bits_equal(a.residual(), exp["residual"])
