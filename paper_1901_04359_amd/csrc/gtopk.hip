@@ -196,8 +196,13 @@ template <class Src, bool ZERO, bool DIVIDE>
 void run_select(const Src& src, const SelState& ss, uint32_t sets, uint32_t k, uint64_t nphys_max,
                 uint32_t* out_idx, float* out_val, int64_t out_stride, float* row,
                 int64_t row_stride, float divisor, uint32_t* gbits, hipStream_t st) {
+    // few blocks per set (a popular bin takes one same-address atomic per block): one batch
+    // of 4 slots per thread up to 32 blocks, then more slots per thread, then up to 256 blocks
     uint32_t hb = ceil_div(nphys_max, 4 * kHistBlock);
-    hb = hb < 1 ? 1 : (hb > 32 ? 32 : hb);
+    if (hb > 32) {
+        hb = ceil_div(nphys_max, 16 * kHistBlock);
+        hb = hb < 32 ? 32 : (hb > 256 ? 256 : hb);
+    }
     hipLaunchKernelGGL((k_hist<Src>), dim3(hb + (Src::kRunScan ? 1 : 0), sets), dim3(kHistBlock), 0,
                        st, src, ss, hb);
     hipLaunchKernelGGL((k_bucket<Src>), dim3(ss.maxgroups, sets), dim3(kBlock), 0, st, src, ss, k);
@@ -289,9 +294,14 @@ void do_merge_batch(const uint32_t* a_idx, const float* a_val, const uint32_t* b
                     uint32_t* out_idx, float* out_val, int64_t out_stride, const MergeWs& w,
                     const uint32_t* in_min, uint32_t* out_min, float divisor, uint32_t* gbits,
                     hipStream_t st) {
-    // one entry of either operand per thread measured best at k = 25,557 and k = 255,570
-    hipLaunchKernelGGL(k_union<1>, dim3(ceil_div(k, kBlock), batch), dim3(kBlock), 0, st, a_idx, a_val,
-                       b_idx, b_val, k, in_stride, w.m_idx, w.m_val);
+    // one entry of either operand per thread measured best at k = 25,557 and k = 255,570; for
+    // very large sets the boundary searches' scattered probes dominate, so a block takes more
+    if (k <= (1u << 20))
+        hipLaunchKernelGGL(k_union<1>, dim3(ceil_div(k, kBlock), batch), dim3(kBlock), 0, st, a_idx,
+                           a_val, b_idx, b_val, k, in_stride, w.m_idx, w.m_val);
+    else
+        hipLaunchKernelGGL(k_union<8>, dim3(ceil_div(k, kBlock * 8), batch), dim3(kBlock), 0, st, a_idx,
+                           a_val, b_idx, b_val, k, in_stride, w.m_idx, w.m_val);
     MergedSrc src{w.m_idx, w.m_val, 2 * k, w.L, in_min};
     SelState ss = w.sel;
     ss.T_out = out_min;
