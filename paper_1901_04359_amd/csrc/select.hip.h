@@ -223,6 +223,24 @@ __global__ __launch_bounds__(kBlock) void k_bucket(Src src, SelState st, uint32_
     if (first >= n) return;
     const uint32_t end = (uint32_t)(first + L < n ? first + L : n);
     const Digit dg = src.digit(s, dn, st);
+    // one round of the walk: the block's next 1024 slots, their items and logical positions
+    uint32_t idx[kBatch], bits[kBatch], lp[kBatch];
+    bool ok[kBatch];
+    auto load_round = [&](uint32_t i0) {
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            const uint32_t p = i0 + j * kBlock + threadIdx.x;
+            idx[j] = 0; bits[j] = 0;
+            ok[j] = p < end && src.fetch_phys(s, dn, p, idx[j], bits[j]);
+        }
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            const uint32_t p = i0 + j * kBlock + threadIdx.x;
+            lp[j] = p < end ? src.logical(s, dn, p, idx[j]) : 0u;
+        }
+    };
+    // the first round is fetched before the pick, so that its latency overlaps with it
+    load_round((uint32_t)first);
     // every block picks the bin of the k-th key from the set's histogram
     {
         constexpr int kPer = kHistBins / kBlock;      // thread t owns 16 consecutive bins
@@ -245,20 +263,7 @@ __global__ __launch_bounds__(kBlock) void k_bucket(Src src, SelState st, uint32_
     uint32_t key[kBatch], lg[kBatch];
     bool inside[kBatch];
     for (uint32_t i0 = (uint32_t)first; i0 < end; i0 += kBlock * kBatch) {
-        uint32_t idx[kBatch], bits[kBatch];
-        bool ok[kBatch];
-#pragma unroll
-        for (int j = 0; j < kBatch; ++j) {
-            const uint32_t p = i0 + j * kBlock + threadIdx.x;
-            idx[j] = 0; bits[j] = 0;
-            ok[j] = p < end && src.fetch_phys(s, dn, p, idx[j], bits[j]);
-        }
-        uint32_t lp[kBatch];
-#pragma unroll
-        for (int j = 0; j < kBatch; ++j) {
-            const uint32_t p = i0 + j * kBlock + threadIdx.x;
-            lp[j] = p < end ? src.logical(s, dn, p, idx[j]) : 0u;
-        }
+        if (i0 != (uint32_t)first) load_round(i0);
 #pragma unroll
         for (int j = 0; j < kBatch; ++j) {
             const uint32_t p = i0 + j * kBlock + threadIdx.x;
@@ -289,20 +294,12 @@ __global__ __launch_bounds__(kBlock) void k_bucket(Src src, SelState st, uint32_
     uint2* list = st.list + (size_t)s * st.list_cap;
     for (uint32_t i0 = (uint32_t)first; i0 < end; i0 += kBlock * kBatch) {
         if (!single) {
-            uint32_t idx[kBatch], bits[kBatch];
-            bool ok[kBatch];
+            load_round(i0);
 #pragma unroll
             for (int j = 0; j < kBatch; ++j) {
-                const uint32_t p = i0 + j * kBlock + threadIdx.x;
-                idx[j] = 0; bits[j] = 0;
-                ok[j] = p < end && src.fetch_phys(s, dn, p, idx[j], bits[j]);
-            }
-#pragma unroll
-            for (int j = 0; j < kBatch; ++j) {
-                const uint32_t p = i0 + j * kBlock + threadIdx.x;
                 key[j] = bits[j] & kAbs;
                 inside[j] = ok[j] && dg.bin(key[j]) == d1;
-                lg[j] = Src::kIdentity ? g : (inside[j] ? src.logical(s, dn, p, idx[j]) / L : 0u);
+                lg[j] = Src::kIdentity ? g : lp[j] / L;
             }
         }
 #pragma unroll
@@ -342,6 +339,9 @@ __global__ __launch_bounds__(1024) void k_finish(Src src, SelState st) {
     const bool overflow = nlist > st.list_cap;       // the list is incomplete: read the set itself
     const uint2* list = st.list + (size_t)s * st.list_cap;
     const uint32_t lo = dg.lo(d1), width = dg.width(d1);    // bin d1 = [lo, lo + width)
+    // per-group counts of keys above the bin (two groups per thread), loaded early
+    const uint32_t ggt0 = 2 * t < ng ? st.grp_gt[(size_t)s * st.maxgroups + 2 * t] : 0u;
+    const uint32_t ggt1 = 2 * t + 1 < ng ? st.grp_gt[(size_t)s * st.maxgroups + 2 * t + 1] : 0u;
 
     // a short list is read once and kept in registers
     constexpr int kCache = 8;
@@ -414,10 +414,10 @@ __global__ __launch_bounds__(1024) void k_finish(Src src, SelState st) {
     const uint32_t need = krem;
 
     // per-group counts of selected-for-sure (key > T) and tied (key == T) entries
-    for (uint32_t g = t; g < ng; g += kT) {
-        g_gt[g] = st.grp_gt[(size_t)s * st.maxgroups + g];
-        g_eq[g] = 0u;
-    }
+    g_gt[2 * t] = ggt0;
+    g_gt[2 * t + 1] = ggt1;
+    g_eq[2 * t] = 0u;
+    g_eq[2 * t + 1] = 0u;
     __syncthreads();
     for_each_entry([&](uint32_t key, uint32_t g) {
         g &= (uint32_t)kMaxGroups - 1;
