@@ -14,7 +14,7 @@ constexpr int kChunk = 1 << kChunkLog2;                  // 32768 elements per b
 static_assert(kChunk == kWaveSpan * (kSBlock / kWave), "a block covers exactly one chunk");
 constexpr int kBlock = 256;                 // threads per block of the select kernels
 constexpr int kBatch = 4;                   // items a thread loads before it processes any
-constexpr int kMaxGroups = 2048;            // groups per set, at most (LDS arrays in k_finish)
+constexpr int kMaxGroups = 2048;            // groups per set, at most
 constexpr int kHistBins = 4096;             // bins of the first digit
 constexpr int kFineShift = 10;              // bin width 2^10 keys when a lower bound of T is known
 constexpr int kCoarseShift = 19;            // bin width 2^19 keys (exponent + 4 mantissa bits) otherwise
@@ -135,14 +135,15 @@ struct Digit {
 
 // ---- clearing ----------------------------------------------------------------------
 
-struct ZeroJob { uint32_t* p[4]; size_t n[4]; };
+constexpr int kZeroSlots = 6;
+struct ZeroJob { uint32_t* p[kZeroSlots]; size_t n[kZeroSlots]; };
 
-// clears up to four arrays in one launch (an array with n == 0 is skipped)
+// clears up to six arrays in one launch (an array with n == 0 is skipped)
 __global__ void k_zero_u32(ZeroJob job) {
     const size_t step = (size_t)gridDim.x * blockDim.x;
     const size_t first = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int a = 0; a < kZeroSlots; ++a)
         for (size_t i = first; i < job.n[a]; i += step) job.p[a][i] = 0u;
 }
 

@@ -63,14 +63,25 @@ SelState carve_select(Carver& c, size_t sets, uint32_t list_cap, uint32_t maxgro
     s.need = c.take<uint32_t>(sets);
     s.T_out = nullptr;
     s.list = c.take<uint2>(sets * list_cap);
-    s.off_gt = c.take<uint32_t>(sets * maxgroups);
-    s.off_eq = c.take<uint32_t>(sets * maxgroups);
     s.list_cap = list_cap;
     s.maxgroups = maxgroups;
     return s;
 }
 // words from s.hist to the end of s.grp_gt (padding included)
 inline size_t select_clear_words(const SelState& s) { return (size_t)(s.d1 - s.hist); }
+
+// A second copy of the three arrays that must be zero when a select starts; everything
+// else is shared with `base`.  Two such states alternate between the rounds of the tree,
+// so that one can be cleared while the other is in use.
+SelState carve_select_alt(Carver& c, const SelState& base, size_t sets, size_t* clear_words) {
+    SelState s = base;
+    s.hist = c.take<uint32_t>(sets * kHistBins);
+    s.list_cnt = c.take<uint32_t>(sets);
+    s.grp_gt = c.take<uint32_t>(sets * base.maxgroups);
+    uint32_t* end = c.take<uint32_t>(1);
+    *clear_words = base.hist ? (size_t)(end - s.hist) : 0;
+    return s;
+}
 
 // slots per group of an array of n slots: a multiple of 256, at least 1024, and large
 // enough that there are at most max_groups (<= kMaxGroups) groups
@@ -81,7 +92,9 @@ uint32_t group_slots_for(uint64_t n, uint32_t max_groups) {
 }
 
 struct MergeWs {
-    SelState sel;
+    SelState sel;      // state of even rounds
+    SelState sel_alt;  // state of odd rounds (own hist / list_cnt / grp_gt)
+    size_t alt_clear_words;
     uint32_t* m_idx;   // [pairs][2k]
     float* m_val;
     uint32_t* tmin[2]; // [pairs] smallest key of each output set, alternating between rounds
@@ -93,6 +106,7 @@ MergeWs carve_merge(Carver& c, uint32_t k, size_t pairs) {
     MergeWs w;
     w.L = group_slots_for(2ull * k, kMaxGroups);
     w.sel = carve_select(c, pairs, 2 * k, ceil_div(2ull * k, w.L));
+    w.sel_alt = carve_select_alt(c, w.sel, pairs, &w.alt_clear_words);
     w.m_idx = c.take<uint32_t>(pairs * 2 * k);
     w.m_val = c.take<float>(pairs * 2 * k);
     w.tmin[0] = c.take<uint32_t>(pairs);
@@ -183,19 +197,20 @@ void mark_stage(int i, bool armed, hipStream_t st) {
 }
 
 void zero_async(hipStream_t st, uint32_t* p0, size_t n0, uint32_t* p1 = nullptr, size_t n1 = 0,
-                uint32_t* p2 = nullptr, size_t n2 = 0, uint32_t* p3 = nullptr, size_t n3 = 0) {
-    ZeroJob job{{p0, p1, p2, p3}, {n0, n1, n2, n3}};
+                uint32_t* p2 = nullptr, size_t n2 = 0, uint32_t* p3 = nullptr, size_t n3 = 0,
+                uint32_t* p4 = nullptr, size_t n4 = 0) {
+    ZeroJob job{{p0, p1, p2, p3, p4, nullptr}, {n0, n1, n2, n3, n4, 0}};
     size_t n = 0;
-    for (int a = 0; a < 4; ++a) n = job.n[a] > n ? job.n[a] : n;
+    for (int a = 0; a < kZeroSlots; ++a) n = job.n[a] > n ? job.n[a] : n;
     uint32_t blocks = (uint32_t)((n + 1023) / 1024 > 1024 ? 1024 : (n + 1023) / 1024);
     hipLaunchKernelGGL(k_zero_u32, dim3(blocks ? blocks : 1), dim3(256), 0, st, job);
 }
 
-// histogram + bucket + finish + emit over `sets` sets of at most nphys_max slots each
-template <class Src, bool ZERO, bool DIVIDE>
+// histogram + bucket + emit over `sets` sets of at most nphys_max slots each
+template <class Src, bool DIVIDE>
 void run_select(const Src& src, const SelState& ss, uint32_t sets, uint32_t k, uint64_t nphys_max,
-                uint32_t* out_idx, float* out_val, int64_t out_stride, float* row,
-                int64_t row_stride, float divisor, uint32_t* gbits, hipStream_t st) {
+                uint32_t* out_idx, float* out_val, int64_t out_stride, float divisor,
+                uint32_t* gbits, hipStream_t st) {
     // few blocks per set (a popular bin takes one same-address atomic per block): one batch
     // of 4 slots per thread up to 32 blocks, then more slots per thread, then up to 256 blocks
     uint32_t hb = ceil_div(nphys_max, 4 * kHistBlock);
@@ -206,9 +221,8 @@ void run_select(const Src& src, const SelState& ss, uint32_t sets, uint32_t k, u
     hipLaunchKernelGGL((k_hist<Src>), dim3(hb + (Src::kRunScan ? 1 : 0), sets), dim3(kHistBlock), 0,
                        st, src, ss, hb);
     hipLaunchKernelGGL((k_bucket<Src>), dim3(ss.maxgroups, sets), dim3(kBlock), 0, st, src, ss, k);
-    hipLaunchKernelGGL((k_finish<Src>), dim3(sets), dim3(1024), 0, st, src, ss);
-    hipLaunchKernelGGL((k_emit<Src, ZERO, DIVIDE>), dim3(ss.maxgroups, sets), dim3(kBlock), 0, st, src,
-                       ss, k, out_idx, out_val, out_stride, row, row_stride, divisor, gbits);
+    hipLaunchKernelGGL((k_emit<Src, DIVIDE>), dim3(ss.maxgroups, sets), dim3(kBlock), 0, st, src, ss,
+                       k, out_idx, out_val, out_stride, divisor, gbits);
 }
 
 // Sample plan for the speculative threshold: tiles of 64 contiguous elements, evenly
@@ -277,36 +291,40 @@ int do_local_select(const float* grad, float* residual, int64_t m, int64_t strid
     CandSrc src{residual, stride, (uint32_t)m, k, w.cap, w.nchunks, w.Lc, w.Ld,
                 w.cand_idx, w.cand_val, w.cand_count, w.tspec, w.run_table, w.run_off,
                 w.ord_idx, w.ord_val};
+    run_select<CandSrc, false>(src, w.sel, P, k, w.cap, out_idx, out_val, (int64_t)k, 1.0f, nullptr,
+                               st);
+    // a kernel of its own: while the select runs, a dense row may still be read as a whole
     if (zero_rows)
-        run_select<CandSrc, true, false>(src, w.sel, P, k, w.cap, out_idx, out_val, (int64_t)k,
-                                         residual, stride, 1.0f, nullptr, st);
-    else
-        run_select<CandSrc, false, false>(src, w.sel, P, k, w.cap, out_idx, out_val, (int64_t)k,
-                                          residual, stride, 1.0f, nullptr, st);
+        hipLaunchKernelGGL(k_zero_selected, dim3(ceil_div(k, kBlock), P), dim3(kBlock), 0, st, out_idx,
+                           k, residual, stride);
     return launch_status();
 }
 
-// one batch of merges: union + exact select + ordered emit.
-// w.sel's cleared fields must be clear on entry and are left clear.
+// one batch of merges: union + exact select + ordered emit.  `round` picks which of the
+// two select states is used (it must be clear on entry); the other one is cleared on the
+// side for the next round.
 template <bool DIVIDE>
 void do_merge_batch(const uint32_t* a_idx, const float* a_val, const uint32_t* b_idx,
                     const float* b_val, uint32_t k, uint32_t batch, int64_t in_stride,
                     uint32_t* out_idx, float* out_val, int64_t out_stride, const MergeWs& w,
-                    const uint32_t* in_min, uint32_t* out_min, float divisor, uint32_t* gbits,
-                    hipStream_t st) {
+                    int round, const uint32_t* in_min, uint32_t* out_min, float divisor,
+                    uint32_t* gbits, hipStream_t st) {
+    const bool odd = (round & 1) != 0;
+    uint32_t* zp = odd ? w.sel.hist : w.sel_alt.hist;
+    const uint32_t zw = (uint32_t)(odd ? select_clear_words(w.sel) : w.alt_clear_words);
     // one entry of either operand per thread measured best at k = 25,557 and k = 255,570; for
     // very large sets the boundary searches' scattered probes dominate, so a block takes more
     if (k <= (1u << 20))
         hipLaunchKernelGGL(k_union<1>, dim3(ceil_div(k, kBlock), batch), dim3(kBlock), 0, st, a_idx,
-                           a_val, b_idx, b_val, k, in_stride, w.m_idx, w.m_val);
+                           a_val, b_idx, b_val, k, in_stride, w.m_idx, w.m_val, zp, zw);
     else
         hipLaunchKernelGGL(k_union<8>, dim3(ceil_div(k, kBlock * 8), batch), dim3(kBlock), 0, st, a_idx,
-                           a_val, b_idx, b_val, k, in_stride, w.m_idx, w.m_val);
+                           a_val, b_idx, b_val, k, in_stride, w.m_idx, w.m_val, zp, zw);
     MergedSrc src{w.m_idx, w.m_val, 2 * k, w.L, in_min};
-    SelState ss = w.sel;
+    SelState ss = odd ? w.sel_alt : w.sel;
     ss.T_out = out_min;
-    run_select<MergedSrc, false, DIVIDE>(src, ss, batch, k, 2ull * k, out_idx, out_val, out_stride,
-                                         nullptr, 0, divisor, gbits, st);
+    run_select<MergedSrc, DIVIDE>(src, ss, batch, k, 2ull * k, out_idx, out_val, out_stride, divisor,
+                                  gbits, st);
 }
 
 // loc_min: the smallest key of each of the P input sets (the local selection's T), or NULL
@@ -320,7 +338,9 @@ int do_tree(const uint32_t* loc_idx, const float* loc_val, const uint32_t* loc_m
                            g_idx, g_val, divisor, gbits);
         return launch_status();
     }
-    if (!pre_cleared) zero_async(st, w.mrg.sel.hist, select_clear_words(w.mrg.sel));
+    if (!pre_cleared)
+        zero_async(st, w.mrg.sel.hist, select_clear_words(w.mrg.sel), w.mrg.sel_alt.hist,
+                   w.mrg.alt_clear_words);
     // After every round the surviving sets are stored compactly, so round j always
     // merges set 2p with set 2p+1 of its input: exactly worker p*2^(j+1) with worker
     // p*2^(j+1) + 2^j of the original numbering.
@@ -335,10 +355,11 @@ int do_tree(const uint32_t* loc_idx, const float* loc_val, const uint32_t* loc_m
         uint32_t* out_min = w.mrg.tmin[round & 1];
         if (last) {
             do_merge_batch<true>(in_idx, in_val, in_idx + k, in_val + k, k, 1, 2 * (int64_t)k, g_idx,
-                                 g_val, k, w.mrg, in_min, out_min, divisor, gbits, st);
+                                 g_val, k, w.mrg, round, in_min, out_min, divisor, gbits, st);
         } else {
             do_merge_batch<false>(in_idx, in_val, in_idx + k, in_val + k, k, pairs, 2 * (int64_t)k,
-                                  ping_i, ping_v, k, w.mrg, in_min, out_min, 1.0f, nullptr, st);
+                                  ping_i, ping_v, k, w.mrg, round, in_min, out_min, 1.0f, nullptr,
+                                  st);
             in_min = out_min;
             in_idx = ping_i; in_val = ping_v;
             uint32_t* ti = ping_i; ping_i = pong_i; pong_i = ti;
@@ -402,7 +423,7 @@ int gtopk_merge(const uint32_t* a_idx, const float* a_val, const uint32_t* b_idx
     hipStream_t st = (hipStream_t)stream;
     zero_async(st, w.sel.hist, select_clear_words(w.sel));
     do_merge_batch<false>(a_idx, a_val, b_idx, b_val, (uint32_t)k, (uint32_t)batch, in_stride,
-                          out_idx, out_val, out_stride, w, nullptr, nullptr, 1.0f, nullptr, st);
+                          out_idx, out_val, out_stride, w, 0, nullptr, nullptr, 1.0f, nullptr, st);
     return launch_status();
 }
 
@@ -452,8 +473,8 @@ int gtopk_step(const float* grad, float* residual, int64_t m, int64_t stride, in
     // one clear for everything this step needs zeroed: the sampler's histograms and the
     // candidate counters; both selects' histograms and tickets; the global-set bitmap
     zero_async(st, w.samp_hist, (size_t)(w.tspec - w.samp_hist), w.sel.hist,
-               select_clear_words(w.sel), w.mrg.sel.hist, select_clear_words(w.mrg.sel), w.gbits,
-               w.gbits_words);
+               select_clear_words(w.sel), w.mrg.sel.hist, select_clear_words(w.mrg.sel),
+               w.mrg.sel_alt.hist, w.mrg.alt_clear_words, w.gbits, w.gbits_words);
     int rc = do_local_select(grad, residual, m, stride, (uint32_t)P, (uint32_t)k, li, lv, w, false,
                              true, st, armed);
     if (rc != GTOPK_OK) return rc;

@@ -47,13 +47,22 @@ __device__ inline uint32_t wave_count_below(const uint32_t* __restrict__ a, uint
 // either side; every thread then searches only between those two counts, a short range
 // that the block's threads share in cache.  EPT > 1 spreads the cost of the boundary
 // searches over more entries (large k).
+// On the side, the grid clears zero_words words at zero_ptr: the select state that the
+// NEXT round of the tree will use (this round's is in use, the other one is free).
 template <int EPT>
 __global__ __launch_bounds__(kBlock) void k_union(
         const uint32_t* __restrict__ a_idx, const float* __restrict__ a_val,
         const uint32_t* __restrict__ b_idx, const float* __restrict__ b_val, uint32_t k,
-        int64_t in_stride, uint32_t* __restrict__ m_idx, float* __restrict__ m_val) {
+        int64_t in_stride, uint32_t* __restrict__ m_idx, float* __restrict__ m_val,
+        uint32_t* __restrict__ zero_ptr, uint32_t zero_words) {
     __shared__ uint32_t s_bound[4];
     const int s = blockIdx.y;
+    {
+        const uint32_t nthreads = gridDim.x * gridDim.y * kBlock;
+        for (uint32_t i = (blockIdx.y * gridDim.x + blockIdx.x) * kBlock + threadIdx.x; i < zero_words;
+             i += nthreads)
+            zero_ptr[i] = 0u;
+    }
     const uint32_t x0 = blockIdx.x * (kBlock * EPT);            // < k by the launch grid
     const uint32_t x1 = x0 + kBlock * EPT - 1 < k ? x0 + kBlock * EPT - 1 : k - 1;
     const uint32_t* ai = a_idx + (int64_t)s * in_stride;

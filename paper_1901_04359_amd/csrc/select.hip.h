@@ -2,17 +2,16 @@
 // index order: the common core of the local selection (Algorithm 4 lines 5-7) and of the
 // Top-k operation between two sparse vectors (Definition 1).
 //
-// Four kernels per batch of sets:
+// Three kernels per batch of sets:
 //   k_hist    4096-bin histogram of the keys' first digit
 //   k_bucket  every block picks, from that histogram, the bin d1 that holds the k-th
 //             key; then, per group of slots: count of keys above the bin; keys inside
 //             the bin are appended (with their group) to a short list.  For the local
 //             selection this walk also copies the candidates, which the streaming pass
 //             left as runs in arbitrary order, into index order.
-//   k_finish  one block per set: LDS radix passes over the list give the exact key T
-//             and the number of ties to take; per-group counts are completed from the
-//             list and scanned into output offsets
-//   k_emit    per group: ordered compaction of the selected entries
+//   k_emit    every block: LDS radix passes over the list give the exact key T and the
+//             number of ties to take, and the block's output offsets; then, per group:
+//             ordered compaction of the selected entries
 #pragma once
 #include "common.hip.h"
 
@@ -20,7 +19,7 @@ namespace gtopk {
 
 // per-set state of the exact select
 struct SelState {
-    // ---- zero between uses (cleared by the caller once, re-cleared by k_finish) ----
+    // ---- must be zero when a select starts (cleared by the host side / the union) -------
     uint32_t* hist;       // [sets][4096]
     uint32_t* list_cnt;   // [sets]
     uint32_t* grp_gt;     // [sets][maxgroups] entries of the group above bin d1
@@ -31,8 +30,6 @@ struct SelState {
     uint32_t* T_out;      // [sets] optional second copy of T that outlives the next select (or NULL)
     uint32_t* need;       // [sets] entries with key == T to take (>= 1)
     uint2* list;          // [sets][list_cap]  (key, group)
-    uint32_t* off_gt;     // [sets][maxgroups] exclusive scans over groups
-    uint32_t* off_eq;
     uint32_t list_cap, maxgroups;
 };
 
@@ -315,23 +312,65 @@ __global__ __launch_bounds__(kBlock) void k_bucket(Src src, SelState st, uint32_
 }
 
 // ---------------------------------------------------------------------------------
-// kernel 3: one block per set finishes the key and scans the groups
+// kernel 3: finish the key, then ordered emit
 // ---------------------------------------------------------------------------------
 
-template <class Src>
-__global__ __launch_bounds__(1024) void k_finish(Src src, SelState st) {
-    constexpr int kT = 1024;
+// One block per group of logical positions.
+//
+// Every block first finishes the select of its set on its own - the list of keys inside
+// bin d1 is short, so doing it per block is cheaper than a kernel in between: LDS radix
+// passes over the list give the exact k-th key T and the number `need` of entries with
+// key == T to take; the block's output offsets are the counts, over the groups before its
+// own, of keys above the bin (grp_gt) plus list keys above T, and of list keys equal to T.
+// (If the list overflowed - only possible for a dense row with masses of equal keys -
+// every block reads the whole set instead: correct, slow.)
+//
+// Then the emit: an entry is selected if key > T, or key == T and fewer than `need`
+// equal-key entries precede it in index order; its output slot is the number of selected
+// entries before it.  DIVIDE: value / divisor (Eq. 3).  gbits != NULL: also set bit
+// `index` of that bitmap (the dense gMask of Algorithm 3 lines 21-22, one bit per gradient
+// element).  A block takes 1024 positions per round: their order inside a round is
+// (sub-step j, wave, lane).
+// The kernel writes nothing that a source reads: in the overflow case other blocks of the
+// set are still reading all of it.
+template <class Src, bool DIVIDE>
+__global__ __launch_bounds__(kBlock) void k_emit(
+        Src src, SelState st, uint32_t k, uint32_t* __restrict__ out_idx,
+        float* __restrict__ out_val, int64_t out_stride, float divisor,
+        uint32_t* __restrict__ gbits) {
+    constexpr int kWaves = kBlock / kWave;
+    constexpr int kT = kBlock;
     __shared__ uint32_t h[2048];
-    __shared__ uint32_t g_gt[kMaxGroups];
-    __shared__ uint32_t g_eq[kMaxGroups];
-    __shared__ uint32_t s_wave[kT / kWave];
+    __shared__ uint32_t s_wave[kWaves];
     __shared__ uint32_t s_out[3];
-    const int s = blockIdx.x;
+    __shared__ uint32_t s_red[2][kWaves];
+    __shared__ uint32_t s_eq[kBatch * kWaves];
+    __shared__ uint32_t s_sel[kBatch * kWaves];
+    const int s = blockIdx.y;
+    const uint32_t g = blockIdx.x;
     const uint32_t t = threadIdx.x;
     const bool dn = src.dense(s);
-    const uint32_t nphys = src.nphys(s, dn);
+    const uint32_t n = src.nphys(s, dn);
     const uint32_t L = src.group_slots(dn);
-    const uint32_t ng = (uint32_t)(((uint64_t)nphys + L - 1) / L);
+    const uint64_t first = (uint64_t)g * L;
+    if (first >= n) return;
+    const uint32_t end = (uint32_t)(first + L < n ? first + L : n);
+    const uint32_t wave = t / kWave;
+
+    // the block's first round of items is fetched up front: its latency overlaps the finish
+    uint32_t idx[kBatch], vb[kBatch];
+    bool ok[kBatch];
+    auto load_round = [&](uint32_t i0) {
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            const uint32_t p = i0 + j * kBlock + t;
+            idx[j] = 0; vb[j] = 0;
+            ok[j] = p < end && src.fetch_ord(s, dn, p, idx[j], vb[j]);
+        }
+    };
+    load_round((uint32_t)first);
+
+    // ---- finish -------------------------------------------------------------------------
     const Digit dg = src.digit(s, dn, st);
     const uint32_t d1 = st.d1[s];
     uint32_t krem = st.krem[s];
@@ -339,12 +378,12 @@ __global__ __launch_bounds__(1024) void k_finish(Src src, SelState st) {
     const bool overflow = nlist > st.list_cap;       // the list is incomplete: read the set itself
     const uint2* list = st.list + (size_t)s * st.list_cap;
     const uint32_t lo = dg.lo(d1), width = dg.width(d1);    // bin d1 = [lo, lo + width)
-    // per-group counts of keys above the bin (two groups per thread), loaded early
-    const uint32_t ggt0 = 2 * t < ng ? st.grp_gt[(size_t)s * st.maxgroups + 2 * t] : 0u;
-    const uint32_t ggt1 = 2 * t + 1 < ng ? st.grp_gt[(size_t)s * st.maxgroups + 2 * t + 1] : 0u;
+    // keys above the bin in the groups before this one
+    uint32_t before_gt = 0;
+    for (uint32_t gp = t; gp < g; gp += kT) before_gt += st.grp_gt[(size_t)s * st.maxgroups + gp];
 
     // a short list is read once and kept in registers
-    constexpr int kCache = 8;
+    constexpr int kCache = 4;
     constexpr uint32_t kNone = 0xFFFFFFFFu;            // no key has bit 31 set
     const bool cached = !overflow && nlist <= (uint32_t)(kCache * kT);
     uint2 ent[kCache];
@@ -353,7 +392,7 @@ __global__ __launch_bounds__(1024) void k_finish(Src src, SelState st) {
         const uint32_t i = t + (uint32_t)j * kT;
         ent[j] = (cached && i < nlist) ? list[i] : make_uint2(kNone, 0u);
     }
-    // f(key, group) is called by every thread the same number of times; key == kNone = nothing
+    // f(key, group): key == kNone = nothing
     auto for_each_entry = [&](auto&& f) {
         if (cached) {
 #pragma unroll
@@ -371,14 +410,14 @@ __global__ __launch_bounds__(1024) void k_finish(Src src, SelState st) {
             }
         } else {
             // every item of the set in logical order; items outside bin d1 are skipped
-            for (uint64_t p0 = 0; p0 < nphys; p0 += (uint64_t)kT * kBatch) {
+            for (uint64_t p0 = 0; p0 < n; p0 += (uint64_t)kT * kBatch) {
                 uint32_t key[kBatch], grp[kBatch];
 #pragma unroll
                 for (int j = 0; j < kBatch; ++j) {
                     const uint64_t p = p0 + (uint64_t)j * kT + t;
-                    uint32_t idx, bits = 0;
-                    const bool ok = p < nphys && src.fetch_ord(s, dn, (uint32_t)p, idx, bits);
-                    key[j] = (ok && dg.bin(bits & kAbs) == d1) ? (bits & kAbs) : kNone;
+                    uint32_t i2, b2 = 0;
+                    const bool live = p < n && src.fetch_ord(s, dn, (uint32_t)p, i2, b2);
+                    key[j] = (live && dg.bin(b2 & kAbs) == d1) ? (b2 & kAbs) : kNone;
                     grp[j] = (uint32_t)(p / L);
                 }
 #pragma unroll
@@ -394,8 +433,8 @@ __global__ __launch_bounds__(1024) void k_finish(Src src, SelState st) {
         const int shift = pass == 0 ? 20 : (pass == 1 ? 10 : 0);
         const int bits = pass == 0 ? 11 : 10;
         if (shift > 0 && width <= (1u << shift)) continue;       // uniform
-        h[t] = 0u;
-        h[t + kT] = 0u;
+#pragma unroll
+        for (int j = 0; j < 2048 / kT; ++j) h[t + j * kT] = 0u;
         __syncthreads();
         for_each_entry([&](uint32_t key, uint32_t) {
             if (key != kNone) {
@@ -405,92 +444,45 @@ __global__ __launch_bounds__(1024) void k_finish(Src src, SelState st) {
             }
         });
         __syncthreads();
-        const uint32_t loc[2] = {h[2 * t], h[2 * t + 1]};
-        suffix_pick<2>(loc, krem, s_wave, s_out);
+        constexpr int kPer = 2048 / kT;
+        uint32_t loc[kPer];
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) loc[j] = h[t * kPer + j];
+        suffix_pick<kPer>(loc, krem, s_wave, s_out);
         prefix = (prefix << bits) | s_out[0];
         krem -= s_out[1];
     }
     const uint32_t T = lo + prefix;
     const uint32_t need = krem;
 
-    // per-group counts of selected-for-sure (key > T) and tied (key == T) entries
-    g_gt[2 * t] = ggt0;
-    g_gt[2 * t + 1] = ggt1;
-    g_eq[2 * t] = 0u;
-    g_eq[2 * t + 1] = 0u;
-    __syncthreads();
-    for_each_entry([&](uint32_t key, uint32_t g) {
-        g &= (uint32_t)kMaxGroups - 1;
-        add_grouped(key != kNone && key > T, g, g_gt);
-        add_grouped(key != kNone && key == T, g, g_eq);
+    // list keys of the groups before this one: above T, equal to T
+    uint32_t c_gt = before_gt, c_eq = 0;
+    for_each_entry([&](uint32_t key, uint32_t grp) {
+        if (key != kNone && grp < g) {
+            c_gt += key > T ? 1u : 0u;
+            c_eq += key == T ? 1u : 0u;
+        }
     });
-    __syncthreads();
-
-    // exclusive scans over the groups (ng <= 2048: two per thread)
-    {
-        const uint32_t g0 = 2 * t, g1 = 2 * t + 1;
-        const uint32_t a0 = g0 < ng ? g_gt[g0] : 0u, a1 = g1 < ng ? g_gt[g1] : 0u;
-        const uint32_t e0 = g0 < ng ? g_eq[g0] : 0u, e1 = g1 < ng ? g_eq[g1] : 0u;
-        uint32_t tot;
-        const uint32_t ia = block_incl_scan(a0 + a1, s_wave, tot);
-        const uint32_t ie = block_incl_scan(e0 + e1, s_wave, tot);
-        uint32_t* og = st.off_gt + (size_t)s * st.maxgroups;
-        uint32_t* oe = st.off_eq + (size_t)s * st.maxgroups;
-        if (g0 < ng) { og[g0] = ia - a0 - a1; oe[g0] = ie - e0 - e1; }
-        if (g1 < ng) { og[g1] = ia - a1; oe[g1] = ie - e1; }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        c_gt += __shfl_xor(c_gt, d);
+        c_eq += __shfl_xor(c_eq, d);
     }
-    // leave the per-set scratch clear for the next select that uses it
-    uint32_t* hg = st.hist + (size_t)s * kHistBins;
-    for (uint32_t b = t; b < (uint32_t)kHistBins; b += kT) hg[b] = 0u;
-    for (uint32_t g = t; g < ng; g += kT) st.grp_gt[(size_t)s * st.maxgroups + g] = 0u;
-    if (t == 0) {
+    if (lane_id() == 0) { s_red[0][wave] = c_gt; s_red[1][wave] = c_eq; }
+    __syncthreads();
+    uint32_t off_gt = 0, eq_before = 0;
+#pragma unroll
+    for (int v = 0; v < kWaves; ++v) { off_gt += s_red[0][v]; eq_before += s_red[1][v]; }
+    if (g == 0 && t == 0) {
         st.T[s] = T;
         st.need[s] = need;
         if (st.T_out) st.T_out[s] = T;
-        st.list_cnt[s] = 0u;
     }
-}
 
-// ---------------------------------------------------------------------------------
-// kernel 4: ordered emit
-// ---------------------------------------------------------------------------------
-
-// One block per group of logical positions.  An entry is selected if key > T, or
-// key == T and fewer than `need` equal-key entries precede it in index order; its output
-// slot is the number of selected entries before it.  ZERO: also store +0.0 at its index
-// in the set's dense row (Algorithm 4 line 8).  DIVIDE: value / divisor (Eq. 3).
-// gbits != NULL: also set bit `index` of that bitmap (the dense gMask of Algorithm 3
-// lines 21-22, one bit per gradient element).  A block takes 1024 positions per round:
-// their order inside a round is (sub-step j, wave, lane).
-template <class Src, bool ZERO, bool DIVIDE>
-__global__ __launch_bounds__(kBlock) void k_emit(
-        Src src, SelState st, uint32_t k, uint32_t* __restrict__ out_idx,
-        float* __restrict__ out_val, int64_t out_stride, float* __restrict__ row,
-        int64_t row_stride, float divisor, uint32_t* __restrict__ gbits) {
-    constexpr int kWaves = kBlock / kWave;
-    __shared__ uint32_t s_eq[kBatch * kWaves];
-    __shared__ uint32_t s_sel[kBatch * kWaves];
-    const int s = blockIdx.y;
-    const uint32_t g = blockIdx.x;
-    const bool dn = src.dense(s);
-    const uint32_t n = src.nphys(s, dn);
-    const uint32_t L = src.group_slots(dn);
-    const uint64_t first = (uint64_t)g * L;
-    if (first >= n) return;
-    const uint32_t end = (uint32_t)(first + L < n ? first + L : n);
-    const uint32_t T = st.T[s], need = st.need[s];
-    uint32_t eq_before = st.off_eq[(size_t)s * st.maxgroups + g];
-    uint32_t outp = st.off_gt[(size_t)s * st.maxgroups + g] + (eq_before < need ? eq_before : need);
-    const uint32_t wave = threadIdx.x / kWave;
+    // ---- emit ---------------------------------------------------------------------------
+    uint32_t outp = off_gt + (eq_before < need ? eq_before : need);
     for (uint32_t i0 = (uint32_t)first; i0 < end; i0 += kBlock * kBatch) {
-        uint32_t idx[kBatch], vb[kBatch];
-        bool ok[kBatch];
-#pragma unroll
-        for (int j = 0; j < kBatch; ++j) {
-            const uint32_t p = i0 + j * kBlock + threadIdx.x;
-            idx[j] = 0; vb[j] = 0;
-            ok[j] = p < end && src.fetch_ord(s, dn, p, idx[j], vb[j]);
-        }
+        if (i0 != (uint32_t)first) load_round(i0);
         bool is_gt[kBatch], is_eq[kBatch];
         uint64_t eqm[kBatch];
         __syncthreads();                  // the previous round's s_eq / s_sel are no longer read
@@ -536,13 +528,22 @@ __global__ __launch_bounds__(kBlock) void k_emit(
                     if (DIVIDE) v = v / divisor;
                     out_val[(int64_t)s * out_stride + pos] = v;
                 }
-                if (ZERO) row[(int64_t)s * row_stride + idx[j]] = 0.0f;
                 if (gbits) atomicOr(&gbits[idx[j] >> 5], 1u << (idx[j] & 31));
             }
         }
         outp += sel_all;
         eq_before += eq_all;
     }
+}
+
+// Algorithm 4 line 8 for the stand-alone local selection: +0.0 at the k selected entries of
+// every worker's row.
+__global__ __launch_bounds__(kBlock) void k_zero_selected(
+        const uint32_t* __restrict__ sel_idx, uint32_t k, float* __restrict__ row,
+        int64_t row_stride) {
+    const uint32_t t = blockIdx.x * kBlock + threadIdx.x;
+    const int s = blockIdx.y;
+    if (t < k) row[(int64_t)s * row_stride + sel_idx[(size_t)s * k + t]] = 0.0f;
 }
 
 }  // namespace gtopk
