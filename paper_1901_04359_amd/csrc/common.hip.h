@@ -16,7 +16,7 @@ constexpr int kBlock = 256;                 // threads per block of the select k
 constexpr int kBatch = 4;                   // items a thread loads before it processes any
 constexpr int kMaxGroups = 2048;            // groups per set, at most
 constexpr int kHistBins = 4096;             // bins of the first digit
-constexpr int kFineShift = 10;              // bin width 2^10 keys when a lower bound of T is known
+constexpr int kFineShift = 10;              // narrowest bin: 2^10 keys, when a lower bound of T is known
 constexpr int kCoarseShift = 19;            // bin width 2^19 keys (exponent + 4 mantissa bits) otherwise
 constexpr int kSampleBits = 14;             // sample histogram: exponent + 6 mantissa bits
 constexpr int kSampleBins = 1 << kSampleBits;
@@ -110,28 +110,48 @@ __device__ __forceinline__ void add_grouped(bool pred, uint32_t g, uint32_t* arr
 }
 
 // ---- first digit of a key ----------------------------------------------------------
-// The 31-bit key space is cut into 4096 consecutive intervals.  With a known lower
-// bound `base` of the k-th key: bin 0 = [0, base + 2^shift), bin d = [base + d*2^shift,
-// base + (d+1)*2^shift), the last bin is open-ended.  base = 0, shift = 19 gives the
-// top 12 key bits.
+// The 31-bit key space is cut into 4096 consecutive intervals ("bins").
+//   coarse (base = 0, shift = 19): bin = the key's top 12 bits (exponent + 4 mantissa bits).
+//   fine (shift = 10), for a known lower bound `base` of the k-th key; rel = key - base
+//   (0 for keys below base):
+//     bins 0 .. 2047     rel < 2^21, 1024 keys each (bin 0 also takes every key below base);
+//     bins 2048 .. 4095  eight octaves [2^e, 2^(e+1)) of rel, e = 21 .. 28, 256 bins each:
+//                        the resolution falls off with the distance from the bound, the way
+//                        the keys themselves thin out; the last bin is open-ended.
+// lo() / width() give a bin's key interval; both layouts tile [0, 2^31) without gaps.
 struct Digit {
     uint32_t base, shift;
-    __device__ __forceinline__ uint32_t bin(uint32_t key) const {
-        const uint32_t d = key > base ? (key - base) >> shift : 0u;
-        return d < (uint32_t)kHistBins - 1 ? d : (uint32_t)kHistBins - 1;
+    static constexpr uint32_t kLinBins = 2048, kLinLog2 = 21, kSubLog2 = 8, kTopOctave = 28;
+    __host__ __device__ __forceinline__ uint32_t bin(uint32_t key) const {
+        const uint32_t rel = key > base ? key - base : 0u;
+        if (shift != (uint32_t)kFineShift || rel < (1u << kLinLog2)) {
+            const uint32_t d = rel >> shift;
+            return d < (uint32_t)kHistBins - 1 ? d : (uint32_t)kHistBins - 1;
+        }
+        const uint32_t e = 31u - (uint32_t)__builtin_clz(rel);
+        if (e > kTopOctave) return (uint32_t)kHistBins - 1;
+        return kLinBins + ((e - kLinLog2) << kSubLog2) + ((rel >> (e - kSubLog2)) & ((1u << kSubLog2) - 1u));
+    }
+    // distance from base to the smallest key of bin d
+    __host__ __device__ __forceinline__ unsigned long long edge(uint32_t d) const {
+        if (shift != (uint32_t)kFineShift || d <= kLinBins) return (unsigned long long)d << shift;
+        const uint32_t o = d - kLinBins, e = kLinLog2 + (o >> kSubLog2);
+        return (1ull << e) + ((unsigned long long)(o & ((1u << kSubLog2) - 1u)) << (e - kSubLog2));
     }
     // smallest key of bin d
-    __device__ __forceinline__ uint32_t lo(uint32_t d) const {
+    __host__ __device__ __forceinline__ uint32_t lo(uint32_t d) const {
         if (d == 0) return 0u;
-        const unsigned long long v = (unsigned long long)base + ((unsigned long long)d << shift);
+        const unsigned long long v = (unsigned long long)base + edge(d);
         return v > 0x80000000ull ? 0x80000000u : (uint32_t)v;      // bins past 2^31 hold no key
     }
     // number of keys of bin d (<= 2^31)
-    __device__ __forceinline__ uint32_t width(uint32_t d) const {
+    __host__ __device__ __forceinline__ uint32_t width(uint32_t d) const {
         if (d == (uint32_t)kHistBins - 1) return 0x80000000u - lo(d);
         return lo(d + 1) - lo(d);
     }
 };
+static_assert(Digit::kLinBins + ((Digit::kTopOctave - Digit::kLinLog2 + 1) << Digit::kSubLog2) == kHistBins,
+              "the fine layout has exactly kHistBins bins");
 
 // ---- clearing ----------------------------------------------------------------------
 

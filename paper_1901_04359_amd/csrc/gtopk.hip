@@ -91,12 +91,16 @@ uint32_t group_slots_for(uint64_t n, uint32_t max_groups) {
     return L < 1024u ? 1024u : L;
 }
 
+constexpr uint32_t kUnionPathMinK = 65536;      // sets above this size take k_union_path
+constexpr int kUnionPathEpt = 8;
+
 struct MergeWs {
     SelState sel;      // state of even rounds
     SelState sel_alt;  // state of odd rounds (own hist / list_cnt / grp_gt)
     size_t alt_clear_words;
-    uint32_t* m_idx;   // [pairs][2k]
+    uint32_t* m_idx;   // [pairs][m_stride]: the 2k slots of a pair, padded to a multiple of 8
     float* m_val;
+    uint32_t m_stride;
     uint32_t* tmin[2]; // [pairs] smallest key of each output set, alternating between rounds
     uint32_t L;
     size_t bytes;
@@ -107,8 +111,9 @@ MergeWs carve_merge(Carver& c, uint32_t k, size_t pairs) {
     w.L = group_slots_for(2ull * k, kMaxGroups);
     w.sel = carve_select(c, pairs, 2 * k, ceil_div(2ull * k, w.L));
     w.sel_alt = carve_select_alt(c, w.sel, pairs, &w.alt_clear_words);
-    w.m_idx = c.take<uint32_t>(pairs * 2 * k);
-    w.m_val = c.take<float>(pairs * 2 * k);
+    w.m_stride = (2 * k + 7u) & ~7u;
+    w.m_idx = c.take<uint32_t>(pairs * w.m_stride);
+    w.m_val = c.take<float>(pairs * w.m_stride);
     w.tmin[0] = c.take<uint32_t>(pairs);
     w.tmin[1] = c.take<uint32_t>(pairs);
     w.bytes = c.off;
@@ -312,15 +317,17 @@ void do_merge_batch(const uint32_t* a_idx, const float* a_val, const uint32_t* b
     const bool odd = (round & 1) != 0;
     uint32_t* zp = odd ? w.sel.hist : w.sel_alt.hist;
     const uint32_t zw = (uint32_t)(odd ? select_clear_words(w.sel) : w.alt_clear_words);
-    // one entry of either operand per thread measured best at k = 25,557 and k = 255,570; for
-    // very large sets the boundary searches' scattered probes dominate, so a block takes more
-    if (k <= (1u << 20))
+    // small sets: one entry of either operand per thread, many small blocks (latency);
+    // large sets: cut by output position, a few entries per thread (throughput)
+    if (k <= kUnionPathMinK)
         hipLaunchKernelGGL(k_union<1>, dim3(ceil_div(k, kBlock), batch), dim3(kBlock), 0, st, a_idx,
-                           a_val, b_idx, b_val, k, in_stride, w.m_idx, w.m_val, zp, zw);
+                           a_val, b_idx, b_val, k, in_stride, w.m_idx, w.m_val, w.m_stride, zp, zw);
     else
-        hipLaunchKernelGGL(k_union<8>, dim3(ceil_div(k, kBlock * 8), batch), dim3(kBlock), 0, st, a_idx,
-                           a_val, b_idx, b_val, k, in_stride, w.m_idx, w.m_val, zp, zw);
-    MergedSrc src{w.m_idx, w.m_val, 2 * k, w.L, in_min};
+        hipLaunchKernelGGL(k_union_path<kUnionPathEpt>,
+                           dim3(ceil_div(2 * k, kBlock * kUnionPathEpt), batch), dim3(kBlock), 0, st,
+                           a_idx, a_val, b_idx, b_val, k, in_stride, w.m_idx, w.m_val, w.m_stride, zp,
+                           zw);
+    MergedSrc src{w.m_idx, w.m_val, 2 * k, w.m_stride, w.L, in_min};
     SelState ss = odd ? w.sel_alt : w.sel;
     ss.T_out = out_min;
     run_select<MergedSrc, DIVIDE>(src, ss, batch, k, 2ull * k, out_idx, out_val, out_stride, divisor,

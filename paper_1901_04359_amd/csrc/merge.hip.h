@@ -54,7 +54,7 @@ __global__ __launch_bounds__(kBlock) void k_union(
         const uint32_t* __restrict__ a_idx, const float* __restrict__ a_val,
         const uint32_t* __restrict__ b_idx, const float* __restrict__ b_val, uint32_t k,
         int64_t in_stride, uint32_t* __restrict__ m_idx, float* __restrict__ m_val,
-        uint32_t* __restrict__ zero_ptr, uint32_t zero_words) {
+        uint32_t m_stride, uint32_t* __restrict__ zero_ptr, uint32_t zero_words) {
     __shared__ uint32_t s_bound[4];
     const int s = blockIdx.y;
     {
@@ -69,8 +69,8 @@ __global__ __launch_bounds__(kBlock) void k_union(
     const float* av = a_val + (int64_t)s * in_stride;
     const uint32_t* bi = b_idx + (int64_t)s * in_stride;
     const float* bv = b_val + (int64_t)s * in_stride;
-    uint32_t* mi = m_idx + (size_t)s * 2 * k;
-    float* mv = m_val + (size_t)s * 2 * k;
+    uint32_t* mi = m_idx + (size_t)s * m_stride;
+    float* mv = m_val + (size_t)s * m_stride;
     const uint32_t wave = threadIdx.x / kWave;
     // this thread's entries (loads overlap with the boundary searches)
     uint32_t ia[EPT], ib[EPT];
@@ -161,6 +161,159 @@ __global__ __launch_bounds__(kBlock) void k_union(
         const bool dup = pb[j] > 0 && A_idx(pb[j] - 1) == ib[j];
         mi[x + pb[j]] = dup ? kTomb : ib[j];
         mv[x + pb[j]] = fb[j];
+    }
+}
+
+// First position of [lo, hi) at which pred is false (hi if there is none); pred must be
+// true on a prefix of the range.  Wave-cooperative like wave_count_below: every lane
+// calls it with the same arguments and gets the same result after log64(hi - lo) rounds.
+template <class Pred>
+__device__ inline uint32_t wave_first_false(uint32_t lo, uint32_t hi, Pred pred) {
+    const uint32_t lane = lane_id();
+    while (lo < hi) {
+        const uint32_t len = hi - lo;
+        const uint32_t step = (len + kWave - 1) / kWave;
+        const uint32_t start = lo + lane * step;
+        const bool active = start < hi;
+        const uint32_t last = (start + step < hi ? start + step : hi) - 1;
+        const bool t = active && pred(last);
+        const uint32_t c = (uint32_t)__popcll(__ballot(t));
+        const uint32_t cstart = lo + c * step;
+        uint32_t nhi = hi;
+        if (c < (uint32_t)kWave && cstart < hi) nhi = (cstart + step < hi ? cstart + step : hi) - 1;
+        lo = cstart < hi ? cstart : hi;
+        hi = nhi;
+    }
+    return lo;
+}
+
+// The same union, cut by OUTPUT position ("merge path"): for large sets.
+// The 2k slots of a pair are the stable merge of A and B by index, A first among equals;
+// the slot of an A entry that has an equal B entry right after it carries the sum, and
+// that B entry's slot is a tombstone - exactly the layout k_union produces.
+// A block owns kBlock*EPT consecutive slots.  Two of its waves find, each with one 64-ary
+// search along a diagonal of the merge grid, how many A entries precede the block's
+// first and last slot; the A and B entries in between (kBlock*EPT in total) are staged in
+// LDS; every thread then finds the start of its own EPT slots with a binary search in LDS
+// and merges EPT steps sequentially.  Rows of m_idx / m_val are m_stride apart (a multiple
+// of EPT, 16-byte aligned), so every thread stores whole vectors; slots past 2k in the
+// row's padding become tombstones.
+template <int EPT>
+__global__ __launch_bounds__(kBlock) void k_union_path(
+        const uint32_t* __restrict__ a_idx, const float* __restrict__ a_val,
+        const uint32_t* __restrict__ b_idx, const float* __restrict__ b_val, uint32_t k,
+        int64_t in_stride, uint32_t* __restrict__ m_idx, float* __restrict__ m_val,
+        uint32_t m_stride, uint32_t* __restrict__ zero_ptr, uint32_t zero_words) {
+    static_assert(EPT % 4 == 0, "whole 16-byte vectors per thread");
+    constexpr uint32_t kTile = kBlock * EPT;
+    constexpr uint32_t kStage = kTile + 3;         // A: previous + entries + sentinel; B: entries + next
+    // EPT spare slots: with operands that are not sorted (unspecified results) a thread's
+    // merge may run up to EPT entries past either staged range; it must stay inside LDS
+    __shared__ uint32_t s_i[kStage + EPT];
+    __shared__ float s_v[kStage + EPT];
+    __shared__ uint32_t s_split[2];
+    const int s = blockIdx.y;
+    {
+        const uint32_t nthreads = gridDim.x * gridDim.y * kBlock;
+        for (uint32_t i = (blockIdx.y * gridDim.x + blockIdx.x) * kBlock + threadIdx.x; i < zero_words;
+             i += nthreads)
+            zero_ptr[i] = 0u;
+    }
+    const uint32_t n = 2 * k;
+    const uint32_t p0 = blockIdx.x * kTile;                    // < n by the launch grid
+    const uint32_t p1 = p0 + kTile < n ? p0 + kTile : n;
+    const uint32_t* ai = a_idx + (int64_t)s * in_stride;
+    const float* av = a_val + (int64_t)s * in_stride;
+    const uint32_t* bi = b_idx + (int64_t)s * in_stride;
+    const float* bv = b_val + (int64_t)s * in_stride;
+    const uint32_t wave = threadIdx.x / kWave;
+    if (wave < 2) {
+        // number of A entries among the first p slots: A[x] is one of them iff A[x] <= B[p-1-x]
+        const uint32_t p = wave == 0 ? p0 : p1;
+        const uint32_t lo = p > k ? p - k : 0u, hi = p < k ? p : k;
+        const uint32_t x = wave_first_false(lo, hi, [&](uint32_t x) { return ai[x] <= bi[p - 1 - x]; });
+        if (lane_id() == 0) s_split[wave] = x;
+    }
+    __syncthreads();
+    const uint32_t nout = p1 - p0;
+    const uint32_t xa0 = s_split[0];
+    uint32_t xa1 = s_split[1];
+    // always true for sorted operands; keeps every access in bounds for any others
+    if (xa1 < xa0) xa1 = xa0;
+    if (xa1 > xa0 + nout) xa1 = xa0 + nout;
+    const uint32_t yb0 = p0 - xa0, yb1 = p1 - xa1;
+    const uint32_t na = xa1 - xa0, nb = yb1 - yb0;             // na + nb = p1 - p0
+    // stage: s[0] = A[xa0-1] (or none), s[1 .. na] = A entries, s[na+1] = none (sentinel: above
+    // every index); s[na+2 .. na+1+nb] = B entries, s[na+2+nb] = B[yb1] (or none)
+    {
+        constexpr int kRounds = (int)((kStage + kBlock - 1) / kBlock);
+        uint32_t ti[kRounds];
+        float tv[kRounds];
+#pragma unroll
+        for (int r = 0; r < kRounds; ++r) {
+            const uint32_t c = r * kBlock + threadIdx.x;
+            ti[r] = kTomb;
+            tv[r] = 0.0f;
+            if (c < na + 1) {
+                if (xa0 + c > 0) { ti[r] = ai[xa0 + c - 1]; tv[r] = av[xa0 + c - 1]; }
+            } else if (c >= na + 2 && c < na + 3 + nb) {
+                const uint32_t y = yb0 + (c - na - 2);
+                if (y < k) { ti[r] = bi[y]; tv[r] = bv[y]; }
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < kRounds; ++r) {
+            const uint32_t c = r * kBlock + threadIdx.x;
+            if (c < kStage) { s_i[c] = ti[r]; s_v[c] = tv[r]; }
+        }
+    }
+    __syncthreads();
+    const uint32_t* sa = s_i + 1;                  // sa[x], x in [-1, na]
+    const uint32_t* sb = s_i + na + 2;             // sb[y], y in [0, nb]
+    const float* sav = s_v + 1;
+    const float* sbv = s_v + na + 2;
+    const uint32_t d = threadIdx.x * EPT;          // first slot of this thread, relative to p0
+    if (d >= nout) return;                         // nout is a multiple of EPT except in the last block
+    // A entries among the tile's first d slots
+    uint32_t x = d > nb ? d - nb : 0u;
+    {
+        uint32_t hi = d < na ? d : na;
+        while (x < hi) {
+            const uint32_t mid = (x + hi) >> 1;
+            if (sa[mid] <= sb[d - 1 - mid]) x = mid + 1; else hi = mid;
+        }
+    }
+    uint32_t y = d - x;
+    uint32_t oi[EPT];
+    float ov[EPT];
+    uint32_t a = sa[x], b = sb[y];
+    uint32_t aprev = sa[(int)x - 1];
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) {
+        if (d + j >= nout) {                       // padding of the row
+            oi[j] = kTomb;
+            ov[j] = 0.0f;
+        } else if (a <= b) {
+            float v = sav[x];
+            if (b == a) v = v + sbv[y];
+            oi[j] = a;
+            ov[j] = v;
+            aprev = a;
+            ++x;
+            a = sa[x];
+        } else {
+            oi[j] = b == aprev ? kTomb : b;
+            ov[j] = sbv[y];
+            ++y;
+            b = sb[y];
+        }
+    }
+    uint32_t* mi = m_idx + (size_t)s * m_stride + p0 + d;
+    float* mv = m_val + (size_t)s * m_stride + p0 + d;
+#pragma unroll
+    for (int j = 0; j < EPT; j += 4) {
+        *reinterpret_cast<uint4*>(mi + j) = make_uint4(oi[j], oi[j + 1], oi[j + 2], oi[j + 3]);
+        *reinterpret_cast<float4*>(mv + j) = make_float4(ov[j], ov[j + 1], ov[j + 2], ov[j + 3]);
     }
 }
 

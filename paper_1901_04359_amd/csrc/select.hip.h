@@ -119,7 +119,8 @@ struct CandSrc {
     }
 };
 
-// Merge: n = 2k slots per pair, index-ascending, a slot with index kTomb holds nothing.
+// Merge: n = 2k slots per pair (rows `stride` slots apart), index-ascending, a slot with
+// index kTomb holds nothing.
 // Every key of the union that is a plain copy of an operand's entry is at least that
 // operand's smallest key, so the larger of the two smallest keys bounds the k-th key of
 // the union from below (sums that cancel can fall under it; they land in bin 0).
@@ -130,7 +131,7 @@ struct MergedSrc {
     static constexpr bool kRunScan = false;
     const uint32_t* idx;
     const float* val;
-    uint32_t n, L;       // L slots per group
+    uint32_t n, stride, L;       // L slots per group
     const uint32_t* in_min;
     __device__ bool dense(int) const { return false; }
     __device__ uint32_t nphys(int, bool) const { return n; }
@@ -141,13 +142,13 @@ struct MergedSrc {
         return Digit{ma > mb ? ma : mb, (uint32_t)kFineShift};
     }
     __device__ bool fetch_phys(int s, bool, uint32_t p, uint32_t& i, uint32_t& bits) const {
-        i = idx[(size_t)s * n + p];
-        bits = __float_as_uint(val[(size_t)s * n + p]);
+        i = idx[(size_t)s * stride + p];
+        bits = __float_as_uint(val[(size_t)s * stride + p]);
         return i != kTomb;
     }
     __device__ bool fetch_key_phys(int s, bool, uint32_t p, uint32_t& key) const {
-        key = __float_as_uint(val[(size_t)s * n + p]) & kAbs;
-        return idx[(size_t)s * n + p] != kTomb;
+        key = __float_as_uint(val[(size_t)s * stride + p]) & kAbs;
+        return idx[(size_t)s * stride + p] != kTomb;
     }
     __device__ uint32_t logical(int, bool, uint32_t p, uint32_t) const { return p; }
     __device__ void store_ordered(int, bool, uint32_t, uint32_t, uint32_t) const {}

@@ -102,7 +102,8 @@ def run_merge(a_idx, a_val, b_idx, b_val, k):
 
 @pytest.mark.parametrize("kind", ["gauss", "ties", "cancel"])
 @pytest.mark.parametrize("k,m", [(1, 10), (2, 3), (64, 64), (255, 5000), (256, 5000), (257, 5000),
-                                 (5000, 200_000), (14_728, 1_000_000)])
+                                 (5000, 200_000), (14_728, 1_000_000), (65_536, 300_000),
+                                 (65_537, 300_000), (70_001, 70_001), (131_075, 5_000_000)])
 def test_merge_parity(kind, k, m):
     batch = 3
     idx, val = W.ksets(2 * batch, k, m, seed=k, overlap=0.4, value_kind=kind)
@@ -114,6 +115,40 @@ def test_merge_parity(kind, k, m):
         oi, ov = orc.merge(a_idx[b], a_val[b], b_idx[b], b_val[b], k)
         assert np.array_equal(gi[b], oi), f"b={b} idx: {first_diff(gi[b], oi)}"
         assert bits_equal(gv[b], ov), f"b={b} val: {first_diff(gv[b], ov)}"
+
+
+@pytest.mark.parametrize("layout", ["a_below_b", "b_below_a", "identical", "interleaved",
+                                    "blocks", "one_shared"])
+@pytest.mark.parametrize("k", [300, 66_000, 100_003])
+def test_merge_structured_index_sets(layout, k):
+    """Index layouts that put the cut points of the union at their extremes."""
+    rng = np.random.default_rng(k)
+    t = np.arange(k, dtype=np.uint32)
+    if layout == "a_below_b":
+        a_idx, b_idx = t, t + k
+    elif layout == "b_below_a":
+        a_idx, b_idx = t + k + 5, t
+    elif layout == "identical":
+        a_idx, b_idx = 3 * t, 3 * t
+    elif layout == "interleaved":
+        a_idx, b_idx = 2 * t, 2 * t + 1
+    elif layout == "blocks":          # long runs of A, then of B, some of them shared
+        blk, off = t // 5000, t % 5000
+        a_idx = blk * 20_000 + 10_000 + off
+        b_idx = blk * 20_000 + off + np.choose(blk % 3, [10_000, 0, 15_000])
+    else:
+        a_idx, b_idx = 2 * t, 2 * t + 1
+        b_idx = b_idx.copy()
+        b_idx[k // 2] = a_idx[k // 2]
+    a_idx = np.ascontiguousarray(a_idx, dtype=np.uint32)[None]
+    b_idx = np.ascontiguousarray(b_idx, dtype=np.uint32)[None]
+    a_val = rng.standard_normal((1, k)).astype(np.float32)
+    b_val = rng.standard_normal((1, k)).astype(np.float32)
+    say(f"merge layout={layout} k={k}")
+    gi, gv = run_merge(a_idx, a_val, b_idx, b_val, k)
+    oi, ov = orc.merge(a_idx[0], a_val[0], b_idx[0], b_val[0], k)
+    assert np.array_equal(gi[0], oi), first_diff(gi[0], oi)
+    assert bits_equal(gv[0], ov), first_diff(gv[0], ov)
 
 
 @pytest.mark.parametrize("P", [1, 2, 4, 8, 16, 32])
