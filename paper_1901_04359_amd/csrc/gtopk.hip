@@ -63,6 +63,8 @@ SelState carve_select(Carver& c, size_t sets, uint32_t list_cap, uint32_t maxgro
     s.need = c.take<uint32_t>(sets);
     s.T_out = nullptr;
     s.list = c.take<uint2>(sets * list_cap);
+    s.off_gt = c.take<uint32_t>(sets * maxgroups);
+    s.off_eq = c.take<uint32_t>(sets * maxgroups);
     s.list_cap = list_cap;
     s.maxgroups = maxgroups;
     return s;
@@ -91,6 +93,7 @@ uint32_t group_slots_for(uint64_t n, uint32_t max_groups) {
     return L < 1024u ? 1024u : L;
 }
 
+constexpr uint64_t kInlineFinishMax = 1u << 20;  // sets up to this many slots: no k_finish
 constexpr uint32_t kUnionPathMinK = 65536;      // sets above this size take k_union_path
 constexpr int kUnionPathEpt = 8;
 
@@ -226,8 +229,16 @@ void run_select(const Src& src, const SelState& ss, uint32_t sets, uint32_t k, u
     hipLaunchKernelGGL((k_hist<Src>), dim3(hb + (Src::kRunScan ? 1 : 0), sets), dim3(kHistBlock), 0,
                        st, src, ss, hb);
     hipLaunchKernelGGL((k_bucket<Src>), dim3(ss.maxgroups, sets), dim3(kBlock), 0, st, src, ss, k);
-    hipLaunchKernelGGL((k_emit<Src, DIVIDE>), dim3(ss.maxgroups, sets), dim3(kBlock), 0, st, src, ss,
-                       k, out_idx, out_val, out_stride, divisor, gbits);
+    // small sets: every block of the emit finishes the select itself (the list of keys it
+    // needs for that is short); large sets: once per set, in a kernel of its own
+    if (nphys_max <= kInlineFinishMax) {
+        hipLaunchKernelGGL((k_emit<Src, DIVIDE, true>), dim3(ss.maxgroups, sets), dim3(kBlock), 0, st,
+                           src, ss, k, out_idx, out_val, out_stride, divisor, gbits);
+    } else {
+        hipLaunchKernelGGL((k_finish<Src>), dim3(sets), dim3(1024), 0, st, src, ss);
+        hipLaunchKernelGGL((k_emit<Src, DIVIDE, false>), dim3(ss.maxgroups, sets), dim3(kBlock), 0, st,
+                           src, ss, k, out_idx, out_val, out_stride, divisor, gbits);
+    }
 }
 
 // Sample plan for the speculative threshold: tiles of 64 contiguous elements, evenly

@@ -12,6 +12,8 @@
 //   k_emit    every block: LDS radix passes over the list give the exact key T and the
 //             number of ties to take, and the block's output offsets; then, per group:
 //             ordered compaction of the selected entries
+// For large sets (long lists) the first half of k_emit runs once per set in a kernel of
+// its own, k_finish, instead of once per block.
 #pragma once
 #include "common.hip.h"
 
@@ -30,6 +32,8 @@ struct SelState {
     uint32_t* T_out;      // [sets] optional second copy of T that outlives the next select (or NULL)
     uint32_t* need;       // [sets] entries with key == T to take (>= 1)
     uint2* list;          // [sets][list_cap]  (key, group)
+    uint32_t* off_gt;     // [sets][maxgroups] written by k_finish only: selected entries with
+    uint32_t* off_eq;     //   key > T / entries with key == T in the groups before this one
     uint32_t list_cap, maxgroups;
 };
 
@@ -212,8 +216,12 @@ __global__ __launch_bounds__(kBlock) void k_bucket(Src src, SelState st, uint32_
     __shared__ uint32_t s_gt[kBlock / kWave];
     __shared__ uint32_t s_in[kBlock / kWave];
     __shared__ uint32_t s_base;
+    constexpr int kStash = 1024;
+    __shared__ uint2 s_stash[kStash];
+    __shared__ uint32_t s_nstash;
     const int s = blockIdx.y;
     const uint32_t g = blockIdx.x;
+    if (threadIdx.x == 0) s_nstash = 0u;       // visible after the barrier inside the pick
     const bool dn = src.dense(s);
     const uint32_t n = src.nphys(s, dn);
     const uint32_t L = src.group_slots(dn);
@@ -254,26 +262,32 @@ __global__ __launch_bounds__(kBlock) void k_bucket(Src src, SelState st, uint32_
         st.krem[s] = k - s_out[1];
     }
     const uint32_t wave = threadIdx.x / kWave;
-    const bool single = end - (uint32_t)first <= (uint32_t)(kBlock * kBatch);
     uint32_t* ggt = st.grp_gt + (size_t)s * st.maxgroups;
     uint32_t gt = 0, in = 0;     // wave-uniform
-    // kept from the (only) round when the group fits in one: no second fetch then
-    uint32_t key[kBatch], lg[kBatch];
-    bool inside[kBatch];
     for (uint32_t i0 = (uint32_t)first; i0 < end; i0 += kBlock * kBatch) {
         if (i0 != (uint32_t)first) load_round(i0);
 #pragma unroll
         for (int j = 0; j < kBatch; ++j) {
             const uint32_t p = i0 + j * kBlock + threadIdx.x;
             if (p < end) src.store_ordered(s, dn, lp[j], idx[j], bits[j]);
-            key[j] = bits[j] & kAbs;
-            const uint32_t d = dg.bin(key[j]);
+            const uint32_t key = bits[j] & kAbs;
+            const uint32_t d = dg.bin(key);
             const bool above = ok[j] && d > d1;
-            inside[j] = ok[j] && d == d1;
-            lg[j] = Src::kIdentity ? g : lp[j] / L;
+            const bool inside = ok[j] && d == d1;
+            const uint32_t lg = Src::kIdentity ? g : lp[j] / L;
             if (Src::kIdentity) gt += (uint32_t)__popcll(__ballot(above));
-            else add_grouped(above, lg[j], ggt);
-            in += (uint32_t)__popcll(__ballot(inside[j]));
+            else add_grouped(above, lg, ggt);
+            // in-bin entries are parked in LDS (in any order) as long as they fit
+            const uint64_t inm = __ballot(inside);
+            if (inm) {
+                const uint32_t cnt = (uint32_t)__popcll(inm);
+                uint32_t base = 0;
+                if (lane_id() == 0) base = atomicAdd(&s_nstash, cnt);
+                base = __shfl(base, 0);
+                const uint32_t pos = base + rank_in(inm);
+                if (inside && pos < (uint32_t)kStash) s_stash[pos] = make_uint2(key, lg);
+                in += cnt;
+            }
         }
     }
     if (lane_id() == 0) { s_gt[wave] = gt; s_in[wave] = in; }
@@ -285,27 +299,29 @@ __global__ __launch_bounds__(kBlock) void k_bucket(Src src, SelState st, uint32_
         s_base = ti ? atomicAdd(&st.list_cnt[s], ti) : 0u;     // one reservation per block
     }
     __syncthreads();
+    const uint32_t total = s_nstash;
+    if (total == 0) return;
+    uint2* list = st.list + (size_t)s * st.list_cap;
+    if (total <= (uint32_t)kStash) {
+        for (uint32_t i = threadIdx.x; i < total; i += kBlock)
+            if (s_base + i < st.list_cap) list[s_base + i] = s_stash[i];
+        return;
+    }
+    // more in-bin entries than the stash holds: walk the group again; this wave's entries
+    // go to its slice of the block's reservation
     if (in == 0) return;
-    // second walk: this wave's in-bin entries go to its slice of the block's reservation
     uint32_t off = s_base;
     for (uint32_t v = 0; v < wave; ++v) off += s_in[v];
-    uint2* list = st.list + (size_t)s * st.list_cap;
     for (uint32_t i0 = (uint32_t)first; i0 < end; i0 += kBlock * kBatch) {
-        if (!single) {
-            load_round(i0);
-#pragma unroll
-            for (int j = 0; j < kBatch; ++j) {
-                key[j] = bits[j] & kAbs;
-                inside[j] = ok[j] && dg.bin(key[j]) == d1;
-                lg[j] = Src::kIdentity ? g : lp[j] / L;
-            }
-        }
+        load_round(i0);
 #pragma unroll
         for (int j = 0; j < kBatch; ++j) {
-            const uint64_t inm = __ballot(inside[j]);
-            if (inside[j]) {
+            const uint32_t key = bits[j] & kAbs;
+            const bool inside = ok[j] && dg.bin(key) == d1;
+            const uint64_t inm = __ballot(inside);
+            if (inside) {
                 const uint32_t pos = off + rank_in(inm);
-                if (pos < st.list_cap) list[pos] = make_uint2(key[j], lg[j]);
+                if (pos < st.list_cap) list[pos] = make_uint2(key, Src::kIdentity ? g : lp[j] / L);
             }
             off += (uint32_t)__popcll(inm);
         }
@@ -313,7 +329,127 @@ __global__ __launch_bounds__(kBlock) void k_bucket(Src src, SelState st, uint32_
 }
 
 // ---------------------------------------------------------------------------------
-// kernel 3: finish the key, then ordered emit
+// kernel 3 (large sets only): one block per set finishes the key and scans the groups
+// ---------------------------------------------------------------------------------
+
+// What every block of k_emit<.., INLINE = true> does for itself, done once per set: the
+// exact key T, the number of ties to take, and for every group the counts of entries with
+// key > T and with key == T in the groups before it.
+template <class Src>
+__global__ __launch_bounds__(1024) void k_finish(Src src, SelState st) {
+    constexpr int kT = 1024;
+    __shared__ uint32_t h[2048];
+    __shared__ uint32_t g_gt[kMaxGroups];
+    __shared__ uint32_t g_eq[kMaxGroups];
+    __shared__ uint32_t s_wave[kT / kWave];
+    __shared__ uint32_t s_out[3];
+    const int s = blockIdx.x;
+    const uint32_t t = threadIdx.x;
+    const bool dn = src.dense(s);
+    const uint32_t nphys = src.nphys(s, dn);
+    const uint32_t L = src.group_slots(dn);
+    const uint32_t ng = (uint32_t)(((uint64_t)nphys + L - 1) / L);
+    const Digit dg = src.digit(s, dn, st);
+    const uint32_t d1 = st.d1[s];
+    uint32_t krem = st.krem[s];
+    const uint32_t nlist = st.list_cnt[s];
+    const bool overflow = nlist > st.list_cap;       // the list is incomplete: read the set itself
+    const uint2* list = st.list + (size_t)s * st.list_cap;
+    const uint32_t lo = dg.lo(d1), width = dg.width(d1);    // bin d1 = [lo, lo + width)
+    // per-group counts of keys above the bin (two groups per thread), loaded early
+    const uint32_t ggt0 = 2 * t < ng ? st.grp_gt[(size_t)s * st.maxgroups + 2 * t] : 0u;
+    const uint32_t ggt1 = 2 * t + 1 < ng ? st.grp_gt[(size_t)s * st.maxgroups + 2 * t + 1] : 0u;
+    constexpr uint32_t kNone = 0xFFFFFFFFu;            // no key has bit 31 set
+    // f(key, group) is called by every thread the same number of times; key == kNone = nothing
+    auto for_each_entry = [&](auto&& f) {
+        if (!overflow) {
+            for (uint32_t i0 = 0; i0 < nlist; i0 += kT * kBatch) {
+                uint2 e[kBatch];
+#pragma unroll
+                for (int j = 0; j < kBatch; ++j) {
+                    const uint32_t i = i0 + j * kT + t;
+                    e[j] = i < nlist ? list[i] : make_uint2(kNone, 0u);
+                }
+#pragma unroll
+                for (int j = 0; j < kBatch; ++j) f(e[j].x, e[j].y);
+            }
+        } else {
+            // every item of the set in logical order; items outside bin d1 are skipped
+            for (uint64_t p0 = 0; p0 < nphys; p0 += (uint64_t)kT * kBatch) {
+                uint32_t key[kBatch], grp[kBatch];
+#pragma unroll
+                for (int j = 0; j < kBatch; ++j) {
+                    const uint64_t p = p0 + (uint64_t)j * kT + t;
+                    uint32_t idx, bits = 0;
+                    const bool ok = p < nphys && src.fetch_ord(s, dn, (uint32_t)p, idx, bits);
+                    key[j] = (ok && dg.bin(bits & kAbs) == d1) ? (bits & kAbs) : kNone;
+                    grp[j] = (uint32_t)(p / L);
+                }
+#pragma unroll
+                for (int j = 0; j < kBatch; ++j) f(key[j], grp[j]);
+            }
+        }
+    };
+    // radix passes over rel = key - lo: bits 30..20, 19..10, 9..0; a pass whose bits are
+    // zero for the whole bin is skipped
+    uint32_t prefix = 0;          // value of the rel bits above the current pass
+    for (int pass = 0; pass < 3; ++pass) {
+        const int shift = pass == 0 ? 20 : (pass == 1 ? 10 : 0);
+        const int bits = pass == 0 ? 11 : 10;
+        if (shift > 0 && width <= (1u << shift)) continue;       // uniform
+        h[t] = 0u;
+        h[t + kT] = 0u;
+        __syncthreads();
+        for_each_entry([&](uint32_t key, uint32_t) {
+            if (key != kNone) {
+                const uint32_t rel = key - lo;
+                if ((rel >> (shift + bits)) == prefix)
+                    atomicAdd(&h[(rel >> shift) & ((1u << bits) - 1u)], 1u);
+            }
+        });
+        __syncthreads();
+        const uint32_t loc[2] = {h[2 * t], h[2 * t + 1]};
+        suffix_pick<2>(loc, krem, s_wave, s_out);
+        prefix = (prefix << bits) | s_out[0];
+        krem -= s_out[1];
+    }
+    const uint32_t T = lo + prefix;
+    const uint32_t need = krem;
+
+    // per-group counts of selected-for-sure (key > T) and tied (key == T) entries
+    g_gt[2 * t] = ggt0;
+    g_gt[2 * t + 1] = ggt1;
+    g_eq[2 * t] = 0u;
+    g_eq[2 * t + 1] = 0u;
+    __syncthreads();
+    for_each_entry([&](uint32_t key, uint32_t g) {
+        g &= (uint32_t)kMaxGroups - 1;
+        add_grouped(key != kNone && key > T, g, g_gt);
+        add_grouped(key != kNone && key == T, g, g_eq);
+    });
+    __syncthreads();
+    // exclusive scans over the groups (ng <= 2048: two per thread)
+    {
+        const uint32_t g0 = 2 * t, g1 = 2 * t + 1;
+        const uint32_t a0 = g0 < ng ? g_gt[g0] : 0u, a1 = g1 < ng ? g_gt[g1] : 0u;
+        const uint32_t e0 = g0 < ng ? g_eq[g0] : 0u, e1 = g1 < ng ? g_eq[g1] : 0u;
+        uint32_t tot;
+        const uint32_t ia = block_incl_scan(a0 + a1, s_wave, tot);
+        const uint32_t ie = block_incl_scan(e0 + e1, s_wave, tot);
+        uint32_t* og = st.off_gt + (size_t)s * st.maxgroups;
+        uint32_t* oe = st.off_eq + (size_t)s * st.maxgroups;
+        if (g0 < ng) { og[g0] = ia - a0 - a1; oe[g0] = ie - e0 - e1; }
+        if (g1 < ng) { og[g1] = ia - a1; oe[g1] = ie - e1; }
+    }
+    if (t == 0) {
+        st.T[s] = T;
+        st.need[s] = need;
+        if (st.T_out) st.T_out[s] = T;
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// kernel 4: finish the key (unless k_finish has), then ordered emit
 // ---------------------------------------------------------------------------------
 
 // One block per group of logical positions.
@@ -334,7 +470,7 @@ __global__ __launch_bounds__(kBlock) void k_bucket(Src src, SelState st, uint32_
 // (sub-step j, wave, lane).
 // The kernel writes nothing that a source reads: in the overflow case other blocks of the
 // set are still reading all of it.
-template <class Src, bool DIVIDE>
+template <class Src, bool DIVIDE, bool INLINE>
 __global__ __launch_bounds__(kBlock) void k_emit(
         Src src, SelState st, uint32_t k, uint32_t* __restrict__ out_idx,
         float* __restrict__ out_val, int64_t out_stride, float divisor,
@@ -372,112 +508,121 @@ __global__ __launch_bounds__(kBlock) void k_emit(
     load_round((uint32_t)first);
 
     // ---- finish -------------------------------------------------------------------------
-    const Digit dg = src.digit(s, dn, st);
-    const uint32_t d1 = st.d1[s];
-    uint32_t krem = st.krem[s];
-    const uint32_t nlist = st.list_cnt[s];
-    const bool overflow = nlist > st.list_cap;       // the list is incomplete: read the set itself
-    const uint2* list = st.list + (size_t)s * st.list_cap;
-    const uint32_t lo = dg.lo(d1), width = dg.width(d1);    // bin d1 = [lo, lo + width)
-    // keys above the bin in the groups before this one
-    uint32_t before_gt = 0;
-    for (uint32_t gp = t; gp < g; gp += kT) before_gt += st.grp_gt[(size_t)s * st.maxgroups + gp];
+    uint32_t T, need, off_gt, eq_before;
+    if (!INLINE) {
+        T = st.T[s];
+        need = st.need[s];
+        off_gt = st.off_gt[(size_t)s * st.maxgroups + g];
+        eq_before = st.off_eq[(size_t)s * st.maxgroups + g];
+    } else {
+        const Digit dg = src.digit(s, dn, st);
+        const uint32_t d1 = st.d1[s];
+        uint32_t krem = st.krem[s];
+        const uint32_t nlist = st.list_cnt[s];
+        const bool overflow = nlist > st.list_cap;       // the list is incomplete: read the set itself
+        const uint2* list = st.list + (size_t)s * st.list_cap;
+        const uint32_t lo = dg.lo(d1), width = dg.width(d1);    // bin d1 = [lo, lo + width)
+        // keys above the bin in the groups before this one
+        uint32_t before_gt = 0;
+        for (uint32_t gp = t; gp < g; gp += kT) before_gt += st.grp_gt[(size_t)s * st.maxgroups + gp];
 
-    // a short list is read once and kept in registers
-    constexpr int kCache = 4;
-    constexpr uint32_t kNone = 0xFFFFFFFFu;            // no key has bit 31 set
-    const bool cached = !overflow && nlist <= (uint32_t)(kCache * kT);
-    uint2 ent[kCache];
+        // a short list is read once and kept in registers
+        constexpr int kCache = 4;
+        constexpr uint32_t kNone = 0xFFFFFFFFu;            // no key has bit 31 set
+        const bool cached = !overflow && nlist <= (uint32_t)(kCache * kT);
+        uint2 ent[kCache];
 #pragma unroll
-    for (int j = 0; j < kCache; ++j) {
-        const uint32_t i = t + (uint32_t)j * kT;
-        ent[j] = (cached && i < nlist) ? list[i] : make_uint2(kNone, 0u);
-    }
-    // f(key, group): key == kNone = nothing
-    auto for_each_entry = [&](auto&& f) {
-        if (cached) {
-#pragma unroll
-            for (int j = 0; j < kCache; ++j) f(ent[j].x, ent[j].y);
-        } else if (!overflow) {
-            for (uint32_t i0 = 0; i0 < nlist; i0 += kT * kBatch) {
-                uint2 e[kBatch];
-#pragma unroll
-                for (int j = 0; j < kBatch; ++j) {
-                    const uint32_t i = i0 + j * kT + t;
-                    e[j] = i < nlist ? list[i] : make_uint2(kNone, 0u);
-                }
-#pragma unroll
-                for (int j = 0; j < kBatch; ++j) f(e[j].x, e[j].y);
-            }
-        } else {
-            // every item of the set in logical order; items outside bin d1 are skipped
-            for (uint64_t p0 = 0; p0 < n; p0 += (uint64_t)kT * kBatch) {
-                uint32_t key[kBatch], grp[kBatch];
-#pragma unroll
-                for (int j = 0; j < kBatch; ++j) {
-                    const uint64_t p = p0 + (uint64_t)j * kT + t;
-                    uint32_t i2, b2 = 0;
-                    const bool live = p < n && src.fetch_ord(s, dn, (uint32_t)p, i2, b2);
-                    key[j] = (live && dg.bin(b2 & kAbs) == d1) ? (b2 & kAbs) : kNone;
-                    grp[j] = (uint32_t)(p / L);
-                }
-#pragma unroll
-                for (int j = 0; j < kBatch; ++j) f(key[j], grp[j]);
-            }
+        for (int j = 0; j < kCache; ++j) {
+            const uint32_t i = t + (uint32_t)j * kT;
+            ent[j] = (cached && i < nlist) ? list[i] : make_uint2(kNone, 0u);
         }
-    };
-
-    // radix passes over rel = key - lo: bits 30..20, 19..10, 9..0; a pass whose bits are
-    // zero for the whole bin is skipped
-    uint32_t prefix = 0;          // value of the rel bits above the current pass
-    for (int pass = 0; pass < 3; ++pass) {
-        const int shift = pass == 0 ? 20 : (pass == 1 ? 10 : 0);
-        const int bits = pass == 0 ? 11 : 10;
-        if (shift > 0 && width <= (1u << shift)) continue;       // uniform
+        // f(key, group): key == kNone = nothing
+        auto for_each_entry = [&](auto&& f) {
+            if (cached) {
 #pragma unroll
-        for (int j = 0; j < 2048 / kT; ++j) h[t + j * kT] = 0u;
-        __syncthreads();
-        for_each_entry([&](uint32_t key, uint32_t) {
-            if (key != kNone) {
-                const uint32_t rel = key - lo;
-                if ((rel >> (shift + bits)) == prefix)
-                    atomicAdd(&h[(rel >> shift) & ((1u << bits) - 1u)], 1u);
+                for (int j = 0; j < kCache; ++j) f(ent[j].x, ent[j].y);
+            } else if (!overflow) {
+                for (uint32_t i0 = 0; i0 < nlist; i0 += kT * kBatch) {
+                    uint2 e[kBatch];
+#pragma unroll
+                    for (int j = 0; j < kBatch; ++j) {
+                        const uint32_t i = i0 + j * kT + t;
+                        e[j] = i < nlist ? list[i] : make_uint2(kNone, 0u);
+                    }
+#pragma unroll
+                    for (int j = 0; j < kBatch; ++j) f(e[j].x, e[j].y);
+                }
+            } else {
+                // every item of the set in logical order; items outside bin d1 are skipped
+                for (uint64_t p0 = 0; p0 < n; p0 += (uint64_t)kT * kBatch) {
+                    uint32_t key[kBatch], grp[kBatch];
+#pragma unroll
+                    for (int j = 0; j < kBatch; ++j) {
+                        const uint64_t p = p0 + (uint64_t)j * kT + t;
+                        uint32_t i2, b2 = 0;
+                        const bool live = p < n && src.fetch_ord(s, dn, (uint32_t)p, i2, b2);
+                        key[j] = (live && dg.bin(b2 & kAbs) == d1) ? (b2 & kAbs) : kNone;
+                        grp[j] = (uint32_t)(p / L);
+                    }
+#pragma unroll
+                    for (int j = 0; j < kBatch; ++j) f(key[j], grp[j]);
+                }
+            }
+        };
+
+        // radix passes over rel = key - lo: bits 30..20, 19..10, 9..0; a pass whose bits are
+        // zero for the whole bin is skipped
+        uint32_t prefix = 0;          // value of the rel bits above the current pass
+        for (int pass = 0; pass < 3; ++pass) {
+            const int shift = pass == 0 ? 20 : (pass == 1 ? 10 : 0);
+            const int bits = pass == 0 ? 11 : 10;
+            if (shift > 0 && width <= (1u << shift)) continue;       // uniform
+#pragma unroll
+            for (int j = 0; j < 2048 / kT; ++j) h[t + j * kT] = 0u;
+            __syncthreads();
+            for_each_entry([&](uint32_t key, uint32_t) {
+                if (key != kNone) {
+                    const uint32_t rel = key - lo;
+                    if ((rel >> (shift + bits)) == prefix)
+                        atomicAdd(&h[(rel >> shift) & ((1u << bits) - 1u)], 1u);
+                }
+            });
+            __syncthreads();
+            constexpr int kPer = 2048 / kT;
+            uint32_t loc[kPer];
+#pragma unroll
+            for (int j = 0; j < kPer; ++j) loc[j] = h[t * kPer + j];
+            suffix_pick<kPer>(loc, krem, s_wave, s_out);
+            prefix = (prefix << bits) | s_out[0];
+            krem -= s_out[1];
+        }
+        T = lo + prefix;
+        need = krem;
+
+        // list keys of the groups before this one: above T, equal to T
+        uint32_t c_gt = before_gt, c_eq = 0;
+        for_each_entry([&](uint32_t key, uint32_t grp) {
+            if (key != kNone && grp < g) {
+                c_gt += key > T ? 1u : 0u;
+                c_eq += key == T ? 1u : 0u;
             }
         });
-        __syncthreads();
-        constexpr int kPer = 2048 / kT;
-        uint32_t loc[kPer];
 #pragma unroll
-        for (int j = 0; j < kPer; ++j) loc[j] = h[t * kPer + j];
-        suffix_pick<kPer>(loc, krem, s_wave, s_out);
-        prefix = (prefix << bits) | s_out[0];
-        krem -= s_out[1];
-    }
-    const uint32_t T = lo + prefix;
-    const uint32_t need = krem;
-
-    // list keys of the groups before this one: above T, equal to T
-    uint32_t c_gt = before_gt, c_eq = 0;
-    for_each_entry([&](uint32_t key, uint32_t grp) {
-        if (key != kNone && grp < g) {
-            c_gt += key > T ? 1u : 0u;
-            c_eq += key == T ? 1u : 0u;
+        for (int d = 32; d >= 1; d >>= 1) {
+            c_gt += __shfl_xor(c_gt, d);
+            c_eq += __shfl_xor(c_eq, d);
         }
-    });
+        if (lane_id() == 0) { s_red[0][wave] = c_gt; s_red[1][wave] = c_eq; }
+        __syncthreads();
+        off_gt = 0;
+        eq_before = 0;
 #pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) {
-        c_gt += __shfl_xor(c_gt, d);
-        c_eq += __shfl_xor(c_eq, d);
-    }
-    if (lane_id() == 0) { s_red[0][wave] = c_gt; s_red[1][wave] = c_eq; }
-    __syncthreads();
-    uint32_t off_gt = 0, eq_before = 0;
-#pragma unroll
-    for (int v = 0; v < kWaves; ++v) { off_gt += s_red[0][v]; eq_before += s_red[1][v]; }
-    if (g == 0 && t == 0) {
-        st.T[s] = T;
-        st.need[s] = need;
-        if (st.T_out) st.T_out[s] = T;
+        for (int v = 0; v < kWaves; ++v) { off_gt += s_red[0][v]; eq_before += s_red[1][v]; }
+        if (g == 0 && t == 0) {
+            st.T[s] = T;
+            st.need[s] = need;
+            if (st.T_out) st.T_out[s] = T;
+        }
     }
 
     // ---- emit ---------------------------------------------------------------------------

@@ -103,7 +103,8 @@ def run_merge(a_idx, a_val, b_idx, b_val, k):
 @pytest.mark.parametrize("kind", ["gauss", "ties", "cancel"])
 @pytest.mark.parametrize("k,m", [(1, 10), (2, 3), (64, 64), (255, 5000), (256, 5000), (257, 5000),
                                  (5000, 200_000), (14_728, 1_000_000), (65_536, 300_000),
-                                 (65_537, 300_000), (70_001, 70_001), (131_075, 5_000_000)])
+                                 (65_537, 300_000), (70_001, 70_001), (131_075, 5_000_000),
+                                 (600_001, 5_000_000)])
 def test_merge_parity(kind, k, m):
     batch = 3
     idx, val = W.ksets(2 * batch, k, m, seed=k, overlap=0.4, value_kind=kind)
@@ -315,11 +316,13 @@ def test_apply_update_and_dense_mask(m, k, copies):
     assert np.array_equal(mask.cpu().numpy(), orc.dense_mask(g_idx, m))
 
 
-@pytest.mark.parametrize("rho", [0.25, 0.0725, 0.015, 0.005, 0.004, 0.0005])
-def test_step_density_schedule(rho):
+@pytest.mark.parametrize("rho,m", [(0.25, 1_000_003), (0.0725, 1_000_003), (0.015, 1_000_003),
+                                   (0.005, 1_000_003), (0.004, 1_000_003), (0.0005, 1_000_003),
+                                   (0.25, 3_000_017)])     # sets of more than 2^20 slots
+def test_step_density_schedule(rho, m):
     """The densities of the paper's warm-up schedule (Section IV-B: 0.25, 0.0725, 0.015,
     0.004), the LSTM density 0.005 and the smallest density of its sensitivity study."""
-    m, P = 1_000_003, 4
+    P = 4
     cfg = W.scaled(W.CONFIGS["C4a"], m, k=max(1, int(round(rho * m))), P=P, name=f"rho={rho}")
     check_steps(cfg, lambda it: W.gradients(cfg, it), 2, cfg.name)
     from paper_1901_04359_amd import binding as B
