@@ -15,6 +15,11 @@ order, so that it can be checked against the paper by eye:
   * Algorithm 3 lines 19-23 (broadcast, gMask) and Algorithm 4 line 10
     (extra residual)                                            -> `residual_restore`
   * Algorithm 4 line 11 (model update) and the dense gMask      -> `apply_update`, `dense_mask`
+  * The two aggregations the paper compares against, as comparison workloads:
+    Algorithm 1, procedure TopKAllReduce (gather, scatter-add, average)
+                                                                 -> `topk_allreduce`
+    Algorithm 2 (naive gTop-k), lines 11-13: top-k of that dense average
+                                                                 -> `dense_topk`
 
 Precision: the paper trains in 32-bit floating point (note under Table III), so
 every add here is ONE IEEE-754 binary32 round-to-nearest add, in a fixed order;
@@ -43,6 +48,12 @@ the design document as well):
       on its INDEX being absent from the global index set (gMask is an index
       mask).
   R11 k-sets are stored index-ascending, indices distinct, uint32.
+  R15 Algorithm 1's TopKAllReduce as printed starts its sum from the worker's
+      own sparse gradient and slices the gathered arrays with garbled bounds;
+      taken literally the own contribution would count twice.  Reading: start
+      from a zero vector and add worker g's k entries for g = 0 .. P-1 in that
+      order (the printed loop order), then divide by P - which is what the
+      comment on the call site states (the average of the P sparse vectors).
 
 Non-finite inputs are outside the method's domain and not supported.
 
@@ -53,7 +64,11 @@ P = 2 against the dense sum, shared-support closed form, exact conservation
 hand-worked 4-worker example.  For P > 2 with general inputs the tree is
 pinned by composition of pinned merges in the R5 order plus the structural
 closed forms (log2 P rounds, P - 1 merges, rank 0 in every round); the paper
-prints no numeric example (its worked figures are images).
+prints no numeric example (its worked figures are images).  `topk_allreduce`
+is pinned by a per-index Python loop, by exact integer-valued sums, by an
+input whose fp32 sum depends on the order, and through P = 2, where its top-k
+must equal the tree's result; `dense_topk` by the same brute force and library
+top-k as the local selection.
 """
 from __future__ import annotations
 
@@ -201,6 +216,27 @@ def dense_mask(g_idx: np.ndarray, m: int) -> np.ndarray:
     mask = np.zeros(m, dtype=np.uint8)
     mask[g_idx] = 1
     return mask
+
+
+def topk_allreduce(loc_idx: Sequence[np.ndarray], loc_val: Sequence[np.ndarray], m: int
+                   ) -> np.ndarray:
+    """Algorithm 1, procedure TopKAllReduce (reading R15): a dense m-vector that starts at
+    +0.0; worker g's k values are added at worker g's k indices, g = 0 .. P-1 in that
+    order, one fp32 add each; then every element is divided by P."""
+    P = len(loc_idx)
+    dense = np.zeros(m, dtype=np.float32)
+    for g in range(P):
+        at = loc_idx[g]                      # distinct within a worker
+        dense[at] = (dense[at] + loc_val[g]).astype(np.float32)
+    return (dense / np.float32(P)).astype(np.float32)
+
+
+def dense_topk(dense: np.ndarray, k: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Algorithm 2 lines 11-13: the k entries of a dense vector with the largest |v|
+    (same R1/R2 rule as the local selection), as an index-ascending sparse k-set."""
+    m = dense.shape[0]
+    idx = first_k_by_magnitude(magnitude_keys(dense), np.arange(m, dtype=np.uint32), k)
+    return idx, dense[idx].copy()
 
 
 def step(residual: np.ndarray, grad: np.ndarray, k: int):

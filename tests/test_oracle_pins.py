@@ -404,13 +404,108 @@ def pin_apply_update_and_mask():
     assert [i for i in range(m) if mask[i]] == g_idx.tolist()
 
 
+def pin_topk_allreduce():
+    """Algorithm 1's TopKAllReduce: per-index Python loop; integer-valued inputs (every fp32
+    sum exact, so a float64 scatter-add must agree); an order-sensitive input; -0.0."""
+    rng = np.random.default_rng(51)
+    m, k, P = 97, 13, 4
+    idx, val = [], []
+    for g in range(P):
+        idx.append(np.sort(rng.choice(m // 2, k, replace=False)).astype(np.uint32))   # many shared
+        val.append((rng.standard_normal(k) * 10.0 ** rng.integers(-3, 4, k)).astype(np.float32))
+    out = orc.topk_allreduce(idx, val, m)
+    exp = np.zeros(m, dtype=np.float32)
+    for i in range(m):
+        acc = f32(0.0)
+        for g in range(P):
+            for t in range(k):
+                if int(idx[g][t]) == i:
+                    acc = f32(acc + val[g][t])
+        exp[i] = f32(acc / f32(P))
+    assert out.dtype == np.float32 and same_bits(out, exp)
+    # integer-valued: exact in any precision
+    ival = [rng.integers(-1000, 1000, k).astype(np.float32) for _ in range(P)]
+    ref = np.zeros(m, dtype=np.float64)
+    for g in range(P):
+        np.add.at(ref, idx[g], ival[g].astype(np.float64))
+    assert np.array_equal(orc.topk_allreduce(idx, ival, m).astype(np.float64), ref / P)
+    # rank order of the adds: ((1 + 1e8) - 1e8) = 0 in fp32; adding the 1 last gives 1
+    one = [np.array([5], dtype=np.uint32)] * 3 + [np.array([6], dtype=np.uint32)]
+    v = [np.array([x], dtype=np.float32) for x in (1.0, 1e8, -1e8, 8.0)]
+    r = orc.topk_allreduce(one, v, 8)
+    assert r[5] == 0.0 and r[6] == 2.0 and not r[[0, 1, 2, 3, 4, 7]].any()
+    # literal += on a zero vector: a lone -0.0 becomes +0.0
+    z = orc.topk_allreduce([np.array([2], dtype=np.uint32)], [np.array([-0.0], dtype=np.float32)], 4)
+    assert bits(z).tolist() == [0, 0, 0, 0]
+    # P = 1: the scatter itself
+    s1 = orc.topk_allreduce(idx[:1], val[:1], m)
+    assert same_bits(s1[idx[0]], val[0]) and np.count_nonzero(s1) == np.count_nonzero(val[0])
+
+
+def pin_dense_topk_and_p2_equals_tree():
+    """Top-k of a dense vector: brute force, library top-k, fewer than k non-zeros; and for
+    P = 2 the naive aggregation (Algorithm 2) must equal the tree (Algorithm 3)."""
+    rng = np.random.default_rng(52)
+    for kind in ("gauss", "ties", "special"):
+        m, k = 60, 9
+        d = random_small(rng, m, kind)
+        oi, ov = orc.dense_topk(d, k)
+        bi, _ = brute_first_k([float(x) for x in d], list(range(m)), k)
+        assert oi.tolist() == bi and same_bits(ov, d[oi])
+    import torch
+    d = rng.standard_normal(5000).astype(np.float32)
+    oi, _ = orc.dense_topk(d, 50)
+    assert set(oi.tolist()) == set(torch.topk(torch.from_numpy(np.abs(d)), 50).indices.tolist())
+    oi, ov = orc.dense_topk(np.array([0, 5, 0, 0, -3], dtype=np.float32), 4)
+    assert oi.tolist() == [0, 1, 2, 4] and ov.tolist() == [0, 5, 0, -3]
+    for seed in range(5):
+        r2 = np.random.default_rng(seed)
+        m, k = 200, 17
+        idx = [np.sort(r2.choice(m, k, replace=False)).astype(np.uint32) for _ in range(2)]
+        val = [r2.standard_normal(k).astype(np.float32) for _ in range(2)]
+        ti, tv = orc.tree(idx, val, k)
+        ni, nv = orc.dense_topk(orc.topk_allreduce(idx, val, m), k)
+        # candidates of the dense top-k also include untouched zeros; with >= k non-zero
+        # sums they never win
+        assert ni.tolist() == ti.tolist() and same_bits(nv, tv)
+
+
+def _mut_allreduce_reverse_order(loc_idx, loc_val, m):
+    dense = np.zeros(m, dtype=np.float32)
+    for g in reversed(range(len(loc_idx))):
+        dense[loc_idx[g]] = (dense[loc_idx[g]] + loc_val[g]).astype(np.float32)
+    return (dense / np.float32(len(loc_idx))).astype(np.float32)
+
+
+def _mut_allreduce_no_average(loc_idx, loc_val, m):
+    dense = np.zeros(m, dtype=np.float32)
+    for g in range(len(loc_idx)):
+        dense[loc_idx[g]] = (dense[loc_idx[g]] + loc_val[g]).astype(np.float32)
+    return dense
+
+
+def _mut_allreduce_own_twice(loc_idx, loc_val, m):
+    dense = np.zeros(m, dtype=np.float32)
+    dense[loc_idx[0]] = loc_val[0]                       # the printed initialisation, literally
+    for g in range(len(loc_idx)):
+        dense[loc_idx[g]] = (dense[loc_idx[g]] + loc_val[g]).astype(np.float32)
+    return (dense / np.float32(len(loc_idx))).astype(np.float32)
+
+
+def _mut_dense_topk_signed(dense, k):
+    order = np.argsort(-dense, kind="stable")[:k]
+    idx = np.sort(order).astype(np.uint32)
+    return idx, dense[idx].copy()
+
+
 def _mut_apply_plus(weights, g_idx, g_val, lr):
     out = weights.copy()
     out[g_idx] = out[g_idx] + np.float32(lr) * g_val
     return out
 
 
-PINS = [pin_apply_update_and_mask, pin_local_select_bruteforce, pin_local_select_library_topk, pin_local_select_invariants,
+PINS = [pin_apply_update_and_mask, pin_topk_allreduce, pin_dense_topk_and_p2_equals_tree,
+        pin_local_select_bruteforce, pin_local_select_library_topk, pin_local_select_invariants,
         pin_local_select_special_k, pin_denormals_not_flushed, pin_merge_dense_definition,
         pin_merge_special_supports, pin_tree_p1_p2, pin_tree_shared_support,
         pin_tree_order_by_composition, pin_tree_not_the_dense_topk, pin_average_is_exact_scale,
@@ -498,6 +593,10 @@ MUTANTS = [
     ("residual_restore", _mut_restore_none),
     ("residual_restore", _mut_restore_store),
     ("apply_update", _mut_apply_plus),
+    ("topk_allreduce", _mut_allreduce_reverse_order),
+    ("topk_allreduce", _mut_allreduce_no_average),
+    ("topk_allreduce", _mut_allreduce_own_twice),
+    ("dense_topk", _mut_dense_topk_signed),
 ]
 
 
