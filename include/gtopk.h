@@ -48,9 +48,10 @@ extern "C" {
 
 typedef enum {
     GTOPK_OK = 0,
-    GTOPK_EINVAL = -1,     /* null pointer; m < 1 or m > 2^31; k < 1 or k > m; P < 1 or not a
-                              power of two (the paper assumes a power of two, Section III);
-                              stride < m; batch < 1; k-set stride < k                        */
+    GTOPK_EINVAL = -1,     /* null pointer; m < 1 or m > 2^31; k < 1 or k > m; k > 2^30 where
+                              sets are merged; P < 1 or not a power of two (the paper assumes
+                              a power of two, Section III); stride < m; batch < 1; k-set
+                              stride < k                                                      */
     GTOPK_EWORKSPACE = -2, /* ws_bytes smaller than the matching *_workspace_bytes query   */
     GTOPK_EALIGN = -3,     /* a pointer is not 16-byte aligned                              */
     GTOPK_EHIP = -4        /* a kernel launch failed (hipGetLastError)                      */
@@ -147,6 +148,38 @@ int gtopk_apply_update(float* weights, int64_t m, int64_t stride, int32_t copies
  * every i in g_idx, 0 elsewhere; mask has m bytes (16-byte aligned).  Needs no workspace.
  */
 int gtopk_dense_mask(const uint32_t* g_idx, int32_t k, int64_t m, uint8_t* mask, void* stream);
+
+/*
+ * The aggregation of Top-k S-SGD, Algorithm 1 procedure TopKAllReduce, with all P workers'
+ * k-sets on this GPU (the procedure's AllGather is then a no-op): dense[i] = s_i / P, where
+ * s_i starts at +0.0 and receives worker g's value at index i (if worker g holds i) for
+ * g = 0 .. P-1 IN THAT ORDER, one fp32 add each; the division is one fp32 divide.  (As
+ * printed the procedure starts the sum from the caller's own sparse gradient and would
+ * count it twice; the zero start gives the average that the call site's comment states.)
+ * An index held by nobody gets +0.0.  This is the comparison workload for gtopk_tree: it
+ * moves P*k entries in and a dense m-vector out.
+ *
+ *   loc_idx, loc_val [P][k] in : the workers' k-sets (index-ascending, indices < m)
+ *   P                          : 1 .. 1024, any value (not only powers of two)
+ *   dense            [m]   out : the averaged dense gradient G_i
+ *   ws                         : gtopk_allreduce_workspace_bytes(m, P) bytes
+ */
+size_t gtopk_allreduce_workspace_bytes(int64_t m, int32_t P);
+int gtopk_topk_allreduce(const uint32_t* loc_idx, const float* loc_val, int32_t P, int32_t k,
+                         int64_t m, float* dense, void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Second sparsification of the naive gTop-k, Algorithm 2 lines 11-13: the k entries of a
+ * dense m-vector with the largest |v| (same rule as everywhere: exactly k, lower index
+ * first among equal magnitudes), as an index-ascending k-set with the values copied bit
+ * for bit.  Algorithm 2's remaining lines are gtopk_topk_allreduce before it (line 9),
+ * gtopk_residual_restore (line 14) and gtopk_apply_update (line 15) after it.
+ *
+ *   dense [m] in : not modified
+ *   ws           : gtopk_workspace_bytes(m, k, 1) bytes
+ */
+int gtopk_dense_topk(const float* dense, int64_t m, int32_t k, uint32_t* g_idx, float* g_val,
+                     void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Instrumentation for benchmarks (not part of the method): arm the NEXT

@@ -20,6 +20,7 @@ EXPORTS = (
     "gtopk_status_string", "gtopk_workspace_bytes", "gtopk_merge_workspace_bytes",
     "gtopk_local_select", "gtopk_merge", "gtopk_tree", "gtopk_residual_restore", "gtopk_step",
     "gtopk_apply_update", "gtopk_dense_mask",
+    "gtopk_allreduce_workspace_bytes", "gtopk_topk_allreduce", "gtopk_dense_topk",
     "gtopk_arm_stage_events", "gtopk_debug_candidate_counts",
 )
 
@@ -68,6 +69,12 @@ def load() -> ctypes.CDLL:
     lib.gtopk_apply_update.argtypes = [vp, i64, i64, i32, i32, vp, vp, c.c_float, vp]
     lib.gtopk_dense_mask.restype = c.c_int
     lib.gtopk_dense_mask.argtypes = [vp, i32, i64, vp, vp]
+    lib.gtopk_allreduce_workspace_bytes.restype = sz
+    lib.gtopk_allreduce_workspace_bytes.argtypes = [i64, i32]
+    lib.gtopk_topk_allreduce.restype = c.c_int
+    lib.gtopk_topk_allreduce.argtypes = [vp, vp, i32, i32, i64, vp, vp, sz, vp]
+    lib.gtopk_dense_topk.restype = c.c_int
+    lib.gtopk_dense_topk.argtypes = [vp, i64, i32, vp, vp, vp, sz, vp]
     lib.gtopk_arm_stage_events.restype = c.c_int
     lib.gtopk_arm_stage_events.argtypes = [c.POINTER(c.c_void_p)]
     lib.gtopk_debug_candidate_counts.restype = c.c_int
@@ -224,6 +231,38 @@ def gtopk_dense_mask(g_idx, k: int, mask) -> None:
     rc = load().gtopk_dense_mask(_ptr(g_idx, torch.int32, "g_idx"), k, mask.numel(),
                                  _ptr(mask, torch.uint8, "mask"), _stream())
     _check(rc, "gtopk_dense_mask")
+
+
+def gtopk_allreduce_workspace_bytes(m: int, P: int) -> int:
+    return int(load().gtopk_allreduce_workspace_bytes(m, P))
+
+
+def alloc_allreduce_workspace(m: int, P: int, device="cuda"):
+    torch = _torch()
+    n = gtopk_allreduce_workspace_bytes(m, P)
+    if n == 0:
+        raise GtopkError(GTOPK_EINVAL, "gtopk_allreduce_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def gtopk_topk_allreduce(loc_idx, loc_val, P: int, k: int, dense, ws) -> None:
+    """loc_idx / loc_val: [P][k] contiguous; dense: [m] float32 (output)."""
+    torch = _torch()
+    rc = load().gtopk_topk_allreduce(
+        _ptr(loc_idx, torch.int32, "loc_idx"), _ptr(loc_val, torch.float32, "loc_val"), P, k,
+        dense.numel(), _ptr(dense, torch.float32, "dense"), _ptr(ws, torch.uint8, "ws"),
+        ws.numel(), _stream())
+    _check(rc, "gtopk_topk_allreduce")
+
+
+def gtopk_dense_topk(dense, k: int, g_idx, g_val, ws) -> None:
+    """dense: [m] float32; ws from alloc_workspace(m, k, 1)."""
+    torch = _torch()
+    rc = load().gtopk_dense_topk(
+        _ptr(dense, torch.float32, "dense"), dense.numel(), k,
+        _ptr(g_idx, torch.int32, "g_idx"), _ptr(g_val, torch.float32, "g_val"),
+        _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream())
+    _check(rc, "gtopk_dense_topk")
 
 
 def gtopk_arm_stage_events(events) -> None:

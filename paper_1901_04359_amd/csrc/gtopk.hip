@@ -27,6 +27,7 @@
 #include "select.hip.h"
 #include "merge.hip.h"
 #include "apply.hip.h"
+#include "aggregate.hip.h"
 
 using namespace gtopk;
 
@@ -190,8 +191,11 @@ StepWs carve_step(void* ws, int64_t m, uint32_t k, uint32_t P) {
     return s;
 }
 
+constexpr int64_t kMaxMergeK = (int64_t)1 << 30;     // a merged pair has 2k slots, a uint32
+
 bool sizes_ok(int64_t m, int64_t k, int64_t P) {
-    return m >= 1 && m <= ((int64_t)1 << 31) && k >= 1 && k <= m && is_pow2(P) && P <= 65535;
+    return m >= 1 && m <= ((int64_t)1 << 31) && k >= 1 && k <= m && is_pow2(P) && P <= 65535 &&
+           (P == 1 || k <= kMaxMergeK);
 }
 
 int launch_status() { return hipGetLastError() == hipSuccess ? GTOPK_OK : GTOPK_EHIP; }
@@ -408,7 +412,7 @@ size_t gtopk_workspace_bytes(int64_t m, int32_t k, int32_t P) {
 }
 
 size_t gtopk_merge_workspace_bytes(int32_t k, int32_t batch) {
-    if (k < 1 || batch < 1 || batch > 65535) return 0;
+    if (k < 1 || k > kMaxMergeK || batch < 1 || batch > 65535) return 0;
     Carver c{nullptr};
     return carve_merge(c, (uint32_t)k, (size_t)batch).bytes;
 }
@@ -431,7 +435,8 @@ int gtopk_merge(const uint32_t* a_idx, const float* a_val, const uint32_t* b_idx
                 int32_t k, int32_t batch, int64_t in_stride, uint32_t* out_idx, float* out_val,
                 int64_t out_stride, void* ws, size_t ws_bytes, void* stream) {
     if (!a_idx || !a_val || !b_idx || !b_val || !out_idx || !out_val || !ws) return GTOPK_EINVAL;
-    if (k < 1 || batch < 1 || batch > 65535 || in_stride < k || out_stride < k) return GTOPK_EINVAL;
+    if (k < 1 || k > kMaxMergeK || batch < 1 || batch > 65535 || in_stride < k || out_stride < k)
+        return GTOPK_EINVAL;
     if (!aligned16(a_idx) || !aligned16(a_val) || !aligned16(b_idx) || !aligned16(b_val) ||
         !aligned16(out_idx) || !aligned16(out_val) || !aligned16(ws))
         return GTOPK_EALIGN;
@@ -448,7 +453,7 @@ int gtopk_merge(const uint32_t* a_idx, const float* a_val, const uint32_t* b_idx
 int gtopk_tree(const uint32_t* loc_idx, const float* loc_val, int32_t P, int32_t k, uint32_t* g_idx,
                float* g_val, void* ws, size_t ws_bytes, void* stream) {
     if (!loc_idx || !loc_val || !g_idx || !g_val || !ws) return GTOPK_EINVAL;
-    if (k < 1 || !is_pow2(P) || P > 65535) return GTOPK_EINVAL;
+    if (k < 1 || k > kMaxMergeK || !is_pow2(P) || P > 65535) return GTOPK_EINVAL;
     if (!aligned16(loc_idx) || !aligned16(loc_val) || !aligned16(g_idx) || !aligned16(g_val) ||
         !aligned16(ws))
         return GTOPK_EALIGN;
@@ -530,6 +535,50 @@ int gtopk_dense_mask(const uint32_t* g_idx, int32_t k, int64_t m, uint8_t* mask,
     hipLaunchKernelGGL(k_mask_clear, dim3(blocks), dim3(256), 0, st, mask, (uint64_t)m);
     hipLaunchKernelGGL(k_mask_set, dim3(ceil_div((uint32_t)k, kBlock)), dim3(kBlock), 0, st, mask,
                        (uint32_t)k, g_idx);
+    return launch_status();
+}
+
+size_t gtopk_allreduce_workspace_bytes(int64_t m, int32_t P) {
+    if (m < 1 || m > ((int64_t)1 << 31) || P < 1 || P > kAggMaxP) return 0;
+    const uint64_t nranges = ceil_div((uint64_t)m, kAggRange);
+    return (size_t)(((uint64_t)P * (nranges + 1) * sizeof(uint32_t) + 255) & ~(uint64_t)255);
+}
+
+int gtopk_topk_allreduce(const uint32_t* loc_idx, const float* loc_val, int32_t P, int32_t k,
+                         int64_t m, float* dense, void* ws, size_t ws_bytes, void* stream) {
+    if (!loc_idx || !loc_val || !dense || !ws) return GTOPK_EINVAL;
+    if (m < 1 || m > ((int64_t)1 << 31) || k < 1 || k > m || P < 1 || P > kAggMaxP)
+        return GTOPK_EINVAL;
+    if (!aligned16(loc_idx) || !aligned16(loc_val) || !aligned16(dense) || !aligned16(ws))
+        return GTOPK_EALIGN;
+    if (ws_bytes < gtopk_allreduce_workspace_bytes(m, P)) return GTOPK_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    const uint32_t nranges = ceil_div((uint64_t)m, kAggRange);
+    uint32_t* bounds = reinterpret_cast<uint32_t*>(ws);
+    hipLaunchKernelGGL(k_slice_bounds, dim3(ceil_div((uint32_t)k, kBlock), (uint32_t)P), dim3(kBlock),
+                       0, st, loc_idx, (uint32_t)k, nranges, bounds);
+    hipLaunchKernelGGL(k_scatter_mean, dim3(nranges), dim3(kBlock), 0, st, loc_idx, loc_val,
+                       (uint32_t)P, (uint32_t)k, (uint32_t)m, bounds, nranges, (float)P, dense);
+    return launch_status();
+}
+
+int gtopk_dense_topk(const float* dense, int64_t m, int32_t k, uint32_t* g_idx, float* g_val,
+                     void* ws, size_t ws_bytes, void* stream) {
+    if (!dense || !g_idx || !g_val || !ws) return GTOPK_EINVAL;
+    if (!sizes_ok(m, k, 1)) return GTOPK_EINVAL;
+    if (!aligned16(dense) || !aligned16(g_idx) || !aligned16(g_val) || !aligned16(ws))
+        return GTOPK_EALIGN;
+    const StepWs w = carve_step(ws, m, (uint32_t)k, 1);
+    if (ws_bytes < w.bytes) return GTOPK_EWORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    // a candidate count of zero makes the select read the dense row itself
+    zero_async(st, w.samp_hist, (size_t)(w.tspec - w.samp_hist), w.sel.hist,
+               select_clear_words(w.sel));
+    CandSrc src{dense, m, (uint32_t)m, (uint32_t)k, w.cap, w.nchunks, w.Lc, w.Ld,
+                w.cand_idx, w.cand_val, w.cand_count, w.tspec, w.run_table, w.run_off,
+                w.ord_idx, w.ord_val};
+    run_select<CandSrc, false>(src, w.sel, 1, (uint32_t)k, (uint64_t)m, g_idx, g_val, (int64_t)k,
+                               1.0f, nullptr, st);
     return launch_status();
 }
 

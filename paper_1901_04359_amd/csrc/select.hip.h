@@ -193,8 +193,18 @@ __global__ __launch_bounds__(kHistBlock) void k_hist(Src src, SelState st, uint3
             ok[j] = p < n && src.fetch_key_phys(s, dn, (uint32_t)p, key[j]);
         }
 #pragma unroll
-        for (int j = 0; j < kBatch; ++j)
-            if (ok[j]) atomicAdd(&h[dg.bin(key[j])], 1u);
+        for (int j = 0; j < kBatch; ++j) {
+            // a wave whose keys all fall into one bin (rows of zeros, equal values) adds once
+            const uint32_t b = dg.bin(key[j]);
+            const uint64_t act = __ballot(ok[j]);
+            if (act == 0) continue;
+            const uint32_t b0 = __shfl(b, __builtin_ctzll(act));
+            if (__ballot(ok[j] && b == b0) == act) {
+                if (lane_id() == (uint32_t)__builtin_ctzll(act)) atomicAdd(&h[b0], (uint32_t)__popcll(act));
+            } else if (ok[j]) {
+                atomicAdd(&h[b], 1u);
+            }
+        }
     }
     __syncthreads();
     uint32_t* out = st.hist + (size_t)s * kHistBins;

@@ -129,3 +129,33 @@ def test_argument_errors_apply_and_mask():
     assert mk(k=0) == B.GTOPK_EINVAL
     assert mk(m=5) == B.GTOPK_EINVAL
     assert mk(mask=ODD) == B.GTOPK_EALIGN
+
+
+def test_argument_errors_allreduce_and_dense_topk():
+    lib = B.load()
+    assert B.gtopk_allreduce_workspace_bytes(25_557_032, 32) >= 32 * (25_557_032 // 8192 + 2) * 4
+    assert B.gtopk_allreduce_workspace_bytes(100, 3) > 0          # any P up to 1024
+    assert B.gtopk_allreduce_workspace_bytes(100, 1025) == 0
+    assert B.gtopk_allreduce_workspace_bytes(0, 2) == 0
+    ok_ws = B.gtopk_allreduce_workspace_bytes(1000, 3)
+    ar = lambda **kw: lib.gtopk_topk_allreduce(
+        kw.get("li", FAKE), FAKE, kw.get("P", 3), kw.get("k", 10), kw.get("m", 1000),
+        kw.get("dense", FAKE), kw.get("ws", FAKE), kw.get("wsb", ok_ws), None)
+    assert ar(li=None) == B.GTOPK_EINVAL
+    assert ar(P=0) == B.GTOPK_EINVAL
+    assert ar(P=1025) == B.GTOPK_EINVAL
+    assert ar(k=1001) == B.GTOPK_EINVAL
+    assert ar(dense=ODD) == B.GTOPK_EALIGN
+    assert ar(wsb=ok_ws - 1) == B.GTOPK_EWORKSPACE
+    ok_ws = B.gtopk_workspace_bytes(1000, 10, 1)
+    dt = lambda **kw: lib.gtopk_dense_topk(
+        kw.get("dense", FAKE), kw.get("m", 1000), kw.get("k", 10), kw.get("gi", FAKE), FAKE,
+        kw.get("ws", FAKE), kw.get("wsb", ok_ws), None)
+    assert dt(dense=None) == B.GTOPK_EINVAL
+    assert dt(k=0) == B.GTOPK_EINVAL
+    assert dt(k=1001) == B.GTOPK_EINVAL
+    assert dt(gi=ODD) == B.GTOPK_EALIGN
+    assert dt(wsb=ok_ws - 1) == B.GTOPK_EWORKSPACE
+    # merged pairs have 2k slots in a uint32
+    assert B.gtopk_merge_workspace_bytes(2**30 + 1, 1) == 0
+    assert B.gtopk_workspace_bytes(2**31, 2**30 + 1, 2) == 0

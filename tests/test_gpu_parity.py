@@ -387,3 +387,116 @@ def test_step_matches_the_three_calls():
     assert bits_equal(a.residual(), b.residual()), first_diff(a.residual(), b.residual())
     exp = orc.step(np.zeros((P, m), dtype=np.float32), g, k)
     assert bits_equal(a.residual(), exp["residual"])
+
+
+# --------------------------------------------------------------------------
+# the two comparison aggregations: Algorithm 1's TopKAllReduce, Algorithm 2's second top-k
+# --------------------------------------------------------------------------
+
+def run_allreduce(idx, val, m):
+    import torch
+    from paper_1901_04359_amd import binding as B
+    P, k = idx.shape
+    dense = torch.full((m,), float("nan"), dtype=torch.float32, device="cuda")   # every element must be written
+    ws = B.alloc_allreduce_workspace(m, P)
+    ws.fill_(0xA5)
+    B.gtopk_topk_allreduce(to_dev(idx), to_dev(val), P, k, dense, ws)
+    return dense
+
+
+@pytest.mark.parametrize("P,k,m,kind,overlap", [
+    (1, 10, 100, "gauss", 0.0), (2, 17, 200, "cancel", 0.9), (3, 300, 2000, "ties", 0.5),
+    (4, 66, 65_536, "gauss", 0.3), (8, 5000, 8192, "gauss", 0.9),       # one range, long slices
+    (5, 8193, 8193, "gauss", 1.0),                                      # k = m: everything everywhere
+    (32, 1000, 1_000_003, "cancel", 0.5), (16, 20_000, 300_001, "gauss", 0.7),
+    (100, 50, 40_000, "gauss", 0.2),
+])
+def test_topk_allreduce_parity(P, k, m, kind, overlap):
+    idx, val = W.ksets(P, k, m, seed=P * 1000 + k, overlap=overlap, value_kind=kind)
+    say(f"topk_allreduce P={P} k={k} m={m} kind={kind}")
+    dense = run_allreduce(idx, val, m).cpu().numpy()
+    exp = orc.topk_allreduce(list(idx), list(val), m)
+    assert bits_equal(dense, exp), first_diff(dense, exp)
+
+
+def test_topk_allreduce_order_and_signed_zero():
+    """Adds at one index happen in rank order; a lone -0.0 comes out as +0.0."""
+    m = 20_000
+    idx = np.array([[5, 9000], [5, 9001], [5, 9002], [6, 19_999]], dtype=np.uint32)
+    val = np.array([[1.0, -0.0], [1e8, 2.0], [-1e8, 3.0], [8.0, -0.0]], dtype=np.float32)
+    say("topk_allreduce order")
+    dense = run_allreduce(idx, val, m).cpu().numpy()
+    exp = orc.topk_allreduce(list(idx), list(val), m)
+    assert bits_equal(dense, exp), first_diff(dense, exp)
+    assert dense[5] == 0.0 and dense[6] == 2.0
+    assert dense[[9000, 19_999]].view(np.uint32).tolist() == [0, 0]
+
+
+@pytest.mark.parametrize("m,k,kind", [
+    (100, 10, "gauss"), (5000, 5000, "gauss"), (70_000, 1, "gauss"), (300_001, 3000, "ties"),
+    (1_000_003, 1000, "sparse"), (1_000_003, 50_000, "sparse"), (2_500_000, 2500, "gauss"),
+])
+def test_dense_topk_parity(m, k, kind):
+    import torch
+    from paper_1901_04359_amd import binding as B
+    rng = np.random.default_rng(m + k)
+    if kind == "gauss":
+        d = rng.standard_normal(m).astype(np.float32)
+    elif kind == "ties":
+        d = (rng.integers(-3, 4, m)).astype(np.float32) * np.float32(0.5)
+    else:                      # what an allreduce of sparse sets leaves: mostly +0.0
+        d = np.zeros(m, dtype=np.float32)
+        at = rng.choice(m, min(m, 3 * k // 2), replace=False)
+        d[at] = rng.standard_normal(at.shape[0]).astype(np.float32)
+    dd = to_dev(d)
+    g_idx = torch.zeros(k, dtype=torch.int32, device="cuda")
+    g_val = torch.zeros(k, dtype=torch.float32, device="cuda")
+    ws = B.alloc_workspace(m, k, 1)
+    ws.fill_(0xA5)
+    say(f"dense_topk m={m} k={k} kind={kind}")
+    B.gtopk_dense_topk(dd, k, g_idx, g_val, ws)
+    oi, ov = orc.dense_topk(d, k)
+    gi, gv = idx_np(g_idx), val_np(g_val)
+    assert np.array_equal(gi, oi), first_diff(gi, oi)
+    assert bits_equal(gv, ov), first_diff(gv, ov)
+    assert bits_equal(dd.cpu().numpy(), d)          # the input is not modified
+
+
+def test_naive_gtopk_iteration_matches_oracle():
+    """Algorithm 2 lines 4-15 chained through the entry points: local selection, sparse
+    all-reduce, second top-k, extra residual, model update."""
+    import torch
+    from paper_1901_04359_amd import binding as B
+    cfg = W.scaled(W.CONFIGS["C2"], 200_003, k=400, P=8, name="naive")
+    P, m, k = cfg.P, cfg.m, cfg.k
+    dev = Device(P, m, k)
+    res = np.zeros((P, m), dtype=np.float32)
+    wts = np.linspace(-1, 1, m, dtype=np.float32)
+    d_w = to_dev(wts)
+    dense = torch.empty(m, dtype=torch.float32, device="cuda")
+    ws_ar = B.alloc_allreduce_workspace(m, P)
+    ws_1 = B.alloc_workspace(m, k, 1)
+    for it in range(2):
+        g = W.gradients(cfg, it)
+        dev.set_res(res)
+        dev.set_grad(g)
+        say(f"naive gtopk iteration {it}")
+        li, lv = dev.local_select()
+        B.gtopk_topk_allreduce(dev.loc_idx, dev.loc_val, P, k, dense, ws_ar)
+        B.gtopk_dense_topk(dense, k, dev.g_idx, dev.g_val, ws_1)
+        B.gtopk_residual_restore(dev.res, k, dev.loc_idx, dev.loc_val, dev.g_idx)
+        B.gtopk_apply_update(d_w, k, dev.g_idx, dev.g_val, 0.05)
+        # oracle
+        o_li, o_lv, o_res = [], [], []
+        for w in range(P):
+            a, b, c = orc.local_select(res[w], g[w], k)
+            o_li.append(a); o_lv.append(b); o_res.append(c)
+        o_dense = orc.topk_allreduce(o_li, o_lv, m)
+        o_gi, o_gv = orc.dense_topk(o_dense, k)
+        res = np.stack([orc.residual_restore(o_res[w], o_li[w], o_lv[w], o_gi) for w in range(P)])
+        wts = orc.apply_update(wts, o_gi, o_gv, 0.05)
+        assert np.array_equal(idx_np(dev.g_idx), o_gi)
+        assert bits_equal(val_np(dev.g_val), o_gv)
+        assert bits_equal(dense.cpu().numpy(), o_dense)
+        assert bits_equal(dev.residual(), res)
+        assert bits_equal(d_w.cpu().numpy(), wts)
