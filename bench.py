@@ -76,6 +76,53 @@ def cpu_baseline(cfg, n_workers: int, budget_s: float = 15.0):
     }
 
 
+def time_aggregations(B, torch, cfg, grads, reps: int = 20):
+    """The three ways of aggregating the P local k-sets that the paper compares, timed on the
+    local sets of one step of this workload (HIP events, `reps` repetitions each):
+    the gTop-k tree (Algorithm 3), Top-k S-SGD's TopKAllReduce (Algorithm 1: dense average),
+    and the naive gTop-k (Algorithm 2: that average, then its top-k).  Also how many of the
+    tree's k indices are in the naive version's exact global top-k."""
+    P, m, k = cfg.P, cfg.m, cfg.k
+    res = torch.zeros((P, m), dtype=torch.float32, device="cuda")
+    loc_idx = torch.zeros((P, k), dtype=torch.int32, device="cuda")
+    loc_val = torch.zeros((P, k), dtype=torch.float32, device="cuda")
+    g_idx = torch.zeros(k, dtype=torch.int32, device="cuda")
+    g_val = torch.zeros(k, dtype=torch.float32, device="cuda")
+    n_idx = torch.zeros(k, dtype=torch.int32, device="cuda")
+    n_val = torch.zeros(k, dtype=torch.float32, device="cuda")
+    dense = torch.empty(m, dtype=torch.float32, device="cuda")
+    ws = B.alloc_workspace(m, k, P)
+    ws1 = B.alloc_workspace(m, k, 1)
+    ws_ar = B.alloc_allreduce_workspace(m, P)
+    B.gtopk_local_select(grads[0], res, k, loc_idx, loc_val, ws)
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    t_tree = timed(lambda: B.gtopk_tree(loc_idx, loc_val, P, k, g_idx, g_val, ws))
+    t_ar = timed(lambda: B.gtopk_topk_allreduce(loc_idx, loc_val, P, k, dense, ws_ar))
+    t_top = timed(lambda: B.gtopk_dense_topk(dense, k, n_idx, n_val, ws1))
+    shared = int(torch.isin(g_idx, n_idx).sum().item())
+    ar_bytes = 4.0 * m + 8.0 * P * k
+    return {
+        "gtopk_tree_ms": round(t_tree, 4),
+        "alg1_topk_allreduce_ms": round(t_ar, 4),
+        "alg1_algorithmic_GBs": round(ar_bytes / (t_ar * 1e-3) / 1e9, 1),
+        "alg2_dense_topk_ms": round(t_top, 4),
+        "alg2_total_ms": round(t_ar + t_top, 4),
+        "tree_indices_in_exact_global_topk": shared / k,
+        "note": "alg1 bytes = 4*m (dense out) + 8*P*k (sets in); alg2 total = alg1 + its top-k",
+    }
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -86,6 +133,9 @@ def main() -> int:
     ap.add_argument("--k", type=int, default=0, help="override the workload's k (density studies)")
     ap.add_argument("--cpu-workers", type=int, default=-1,
                     help="workers in the oracle sample (0 = skip, -1 = as many as fit in ~15 s)")
+    ap.add_argument("--aggregations", action="store_true",
+                    help="also time the paper's comparison aggregations (Algorithms 1 and 2) "
+                         "against the tree on this workload's local sets")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy a few times (reference "
                          "reading for the rocprofv3 FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -180,6 +230,9 @@ def main() -> int:
                      "algorithmic_bytes_per_launch": alg_bytes},
         "input_generation_s": round(t_gen, 1),
     }
+    if args.aggregations:
+        del res, ws
+        out["aggregations"] = time_aggregations(B, torch, cfg, grads)
     if args.cpu_workers != 0:
         out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_workers)
     print(json.dumps(out))

@@ -50,8 +50,8 @@ typedef enum {
     GTOPK_OK = 0,
     GTOPK_EINVAL = -1,     /* null pointer; m < 1 or m > 2^31; k < 1 or k > m; k > 2^30 where
                               sets are merged; P < 1 or not a power of two (the paper assumes
-                              a power of two, Section III); stride < m; batch < 1; k-set
-                              stride < k                                                      */
+                              a power of two, Section III); stride < m; batch < 1 or
+                              batch > 32767; k-set stride < k                                 */
     GTOPK_EWORKSPACE = -2, /* ws_bytes smaller than the matching *_workspace_bytes query   */
     GTOPK_EALIGN = -3,     /* a pointer is not 16-byte aligned                              */
     GTOPK_EHIP = -4        /* a kernel launch failed (hipGetLastError)                      */

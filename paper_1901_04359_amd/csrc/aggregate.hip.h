@@ -8,49 +8,50 @@
 namespace gtopk {
 
 constexpr int kAggRange = 8192;        // dense elements per block (held in LDS)
-constexpr int kAggStage = 2048;        // k-set entries staged in LDS at a time
 constexpr int kAggMaxP = 1024;         // workers, at most
 
 constexpr int kAggRangeLog2 = 13;
 static_assert((1 << kAggRangeLog2) == kAggRange, "range size");
 
 // bounds[g][b] = number of entries of worker g's (index-ascending) k-set with index below
-// b * 8192, for b = 0 .. nranges: the slices that k_scatter_mean's blocks take.  Entry j
-// writes the bounds that fall between its predecessor's range and its own; the last
-// entry also writes those behind it.
+// b * kAggRange, for b = 0 .. nranges: the slices that k_scatter_mean's blocks take.  One
+// binary search per bound; the searches of neighbouring bounds share their first probes.
 __global__ __launch_bounds__(kBlock) void k_slice_bounds(
         const uint32_t* __restrict__ loc_idx, uint32_t k, uint32_t nranges,
         uint32_t* __restrict__ bounds) {
-    const uint32_t j = blockIdx.x * kBlock + threadIdx.x;
+    const uint32_t b = blockIdx.x * kBlock + threadIdx.x;
     const int g = blockIdx.y;
-    if (j >= k) return;
+    if (b > nranges) return;
     const uint32_t* ig = loc_idx + (size_t)g * k;
-    uint32_t* bg = bounds + (size_t)g * (nranges + 1);
-    uint32_t cur = ig[j] >> kAggRangeLog2;
-    if (cur > nranges) cur = nranges;                 // only for an index >= m (not a valid set)
-    uint32_t b = 0;
-    if (j > 0) {
-        const uint32_t prev = ig[j - 1] >> kAggRangeLog2;
-        b = prev + 1;                                 // bounds up to prev are the predecessors'
+    const uint64_t target = (uint64_t)b << kAggRangeLog2;
+    uint32_t lo = 0, hi = k;
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if ((uint64_t)ig[mid] < target) lo = mid + 1; else hi = mid;
     }
-    for (; b <= cur; ++b) bg[b] = j;
-    if (j == k - 1)
-        for (b = cur + 1; b <= nranges; ++b) bg[b] = k;
+    bounds[(size_t)g * (nranges + 1) + b] = lo;
 }
 
-// Block b owns the dense elements [b*8192, (b+1)*8192).  It reads, for every worker, the
-// slice of that worker's k-set that falls into its range, stages the slices' entries in
-// LDS, all workers' loads in flight together, and adds them into an LDS copy of its range
-// worker by worker: at one index the adds happen in the order g = 0 .. P-1, each one fp32
-// add, the first onto +0.0.  Indices are distinct inside a worker's set, so the threads
-// that apply one worker's slice never meet.  The range is written out once, divided by P.
+// Block b owns the dense elements [b*R, (b+1)*R), R = kAggRange, and keeps them in LDS.
+// It reads, for every worker, the slice of that worker's k-set that falls into its range
+// and lays the slices end to end ("flat" order: by worker, then by index).  Threads take
+// the flat entries 1024 at a time, four each, in registers.  At one index the adds must
+// happen in worker order, each one fp32 add, the first onto +0.0; entries at different
+// indices are independent.  So the entries of a batch are applied in rounds: every
+// pending entry bids for its index with its flat position (LDS atomic minimum), the
+// winners add their value and retire, until nothing is pending.  A round retires, for
+// every index, the pending entry of the lowest worker; the number of rounds is the largest
+// number of workers that share one index within the batch (1 to 3 for sparse sets).
+// Batches follow each other in flat order, so the order holds across batches as well.
+// The range is written out once, divided by P.
 __global__ __launch_bounds__(kBlock) void k_scatter_mean(
         const uint32_t* __restrict__ loc_idx, const float* __restrict__ loc_val, uint32_t P,
         uint32_t k, uint32_t m, const uint32_t* __restrict__ bounds, uint32_t nranges,
         float divisor, float* __restrict__ dense) {
-    __shared__ float acc[kAggRange];
-    __shared__ uint32_t st_i[kAggStage];
-    __shared__ float st_v[kAggStage];
+    constexpr int kEpt = 4;
+    constexpr uint32_t kNoBid = 0xFFFFFFFFu;
+    __shared__ __align__(16) float acc[kAggRange];
+    __shared__ uint32_t bid[kAggRange];
     __shared__ uint32_t s_lo[kAggMaxP];            // first entry of worker g inside the range
     __shared__ uint32_t s_off[kAggMaxP + 1];       // entries of workers < g inside the range
     __shared__ uint32_t s_wave[kBlock / kWave];
@@ -66,7 +67,7 @@ __global__ __launch_bounds__(kBlock) void k_scatter_mean(
         s_lo[g] = lo;
         s_off[g + 1] = hi;                         // holds the end for now
     }
-    for (uint32_t i = t; i < (uint32_t)kAggRange; i += kBlock) acc[i] = 0.0f;
+    for (uint32_t i = t; i < (uint32_t)kAggRange; i += kBlock) { acc[i] = 0.0f; bid[i] = kNoBid; }
     __syncthreads();
     // counts -> exclusive offsets (up to 4 workers per thread)
     {
@@ -100,30 +101,59 @@ __global__ __launch_bounds__(kBlock) void k_scatter_mean(
         }
         return lo;
     };
-    for (uint32_t c0 = 0; c0 < total; c0 += (uint32_t)kAggStage) {
-        const uint32_t c1 = c0 + (uint32_t)kAggStage < total ? c0 + (uint32_t)kAggStage : total;
-        for (uint32_t e = c0 + t; e < c1; e += kBlock) {
-            const uint32_t g = worker_of(e);
-            const size_t j = (size_t)g * k + s_lo[g] + (e - s_off[g]);
-            st_i[e - c0] = loc_idx[j] - base;
-            st_v[e - c0] = loc_val[j];
-        }
-        __syncthreads();
-        const uint32_t g_first = worker_of(c0), g_last = worker_of(c1 - 1);
-        for (uint32_t g = g_first; g <= g_last; ++g) {
-            const uint32_t b0 = s_off[g] > c0 ? s_off[g] : c0;
-            const uint32_t b1 = s_off[g + 1] < c1 ? s_off[g + 1] : c1;
-            if (b0 >= b1) continue;       // block-uniform
-            for (uint32_t e = b0 + t; e < b1; e += kBlock) {
-                const uint32_t i = st_i[e - c0];
-                if (i < (uint32_t)kAggRange) acc[i] = acc[i] + st_v[e - c0];   // always true for sorted sets
+    for (uint32_t c0 = 0; c0 < total; c0 += kBlock * kEpt) {
+        // thread t takes the flat entries c0 + 4t .. c0 + 4t + 3: its bids order them
+        uint32_t ei[kEpt];
+        float ev[kEpt];
+        bool pending[kEpt];
+#pragma unroll
+        for (int u = 0; u < kEpt; ++u) {
+            const uint32_t e = c0 + t * kEpt + u;
+            pending[u] = e < total;
+            ei[u] = 0;
+            ev[u] = 0.0f;
+            if (pending[u]) {
+                const uint32_t g = worker_of(e);
+                const size_t j = (size_t)g * k + s_lo[g] + (e - s_off[g]);
+                ei[u] = loc_idx[j] - base;
+                ev[u] = loc_val[j];
+                pending[u] = ei[u] < (uint32_t)kAggRange;      // always true for sorted sets
             }
+        }
+        bool any = true;
+        while (any) {                     // block-uniform: `any` comes from a block-wide vote
+#pragma unroll
+            for (int u = 0; u < kEpt; ++u)
+                if (pending[u]) atomicMin(&bid[ei[u]], t * kEpt + u);
             __syncthreads();
+            bool win[kEpt];
+#pragma unroll
+            for (int u = 0; u < kEpt; ++u) win[u] = pending[u] && bid[ei[u]] == t * kEpt + u;
+            __syncthreads();
+            bool left = false;
+#pragma unroll
+            for (int u = 0; u < kEpt; ++u) {
+                if (win[u]) {
+                    acc[ei[u]] = acc[ei[u]] + ev[u];
+                    bid[ei[u]] = kNoBid;
+                    pending[u] = false;
+                }
+                left = left || pending[u];
+            }
+            any = __syncthreads_or(left) != 0;
         }
     }
     __syncthreads();
-    float* out = dense + base;
-    for (uint32_t i = t; i < span; i += kBlock) out[i] = acc[i] / divisor;
+    float* out = dense + base;                      // 16-byte aligned: base is a multiple of kAggRange
+    if (span == (uint32_t)kAggRange) {
+        for (uint32_t i = 4 * t; i < (uint32_t)kAggRange; i += 4 * kBlock) {
+            const float4 a = *reinterpret_cast<const float4*>(&acc[i]);
+            *reinterpret_cast<float4*>(out + i) =
+                make_float4(a.x / divisor, a.y / divisor, a.z / divisor, a.w / divisor);
+        }
+    } else {
+        for (uint32_t i = t; i < span; i += kBlock) out[i] = acc[i] / divisor;
+    }
 }
 
 }  // namespace gtopk

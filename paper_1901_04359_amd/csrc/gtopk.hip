@@ -106,6 +106,7 @@ struct MergeWs {
     float* m_val;
     uint32_t m_stride;
     uint32_t* tmin[2]; // [pairs] smallest key of each output set, alternating between rounds
+    uint32_t* inv_min; // [2*pairs] 0x7fffffff - smallest key of each caller-supplied operand
     uint32_t L;
     size_t bytes;
 };
@@ -120,6 +121,7 @@ MergeWs carve_merge(Carver& c, uint32_t k, size_t pairs) {
     w.m_val = c.take<float>(pairs * w.m_stride);
     w.tmin[0] = c.take<uint32_t>(pairs);
     w.tmin[1] = c.take<uint32_t>(pairs);
+    w.inv_min = c.take<uint32_t>(2 * pairs);
     w.bytes = c.off;
     return w;
 }
@@ -164,7 +166,10 @@ StepWs carve_step(void* ws, int64_t m, uint32_t k, uint32_t P) {
     s.nchunks = ceil_div((uint64_t)m + 3, kChunk);      // a row may start up to 3 elements into a chunk
     s.Lc = group_slots_for(s.cap, kMaxGroups);
     const uint32_t gcand = ceil_div(s.cap, s.Lc);
-    s.Ld = group_slots_for((uint64_t)m, gcand > 256 ? gcand : 256);   // a fallback: coarse groups
+    // dense rows are a fallback when there are several workers: coarse groups keep the
+    // grids small; with one set (also the dense top-k) they get as many groups as any set
+    const uint32_t gdense = P == 1 ? (uint32_t)kMaxGroups : 256u;
+    s.Ld = group_slots_for((uint64_t)m, gcand > gdense ? gcand : gdense);
     s.samp_hist = c.take<uint32_t>((size_t)P * kSampleBins);
     s.cand_count = c.take<uint32_t>(P);
     s.tspec = c.take<uint32_t>(P);
@@ -320,6 +325,11 @@ int do_local_select(const float* grad, float* residual, int64_t m, int64_t strid
     return launch_status();
 }
 
+inline uint32_t min_key_blocks(uint32_t k) {
+    const uint32_t b = ceil_div(k, 8192);
+    return b < 1 ? 1 : (b > 64 ? 64 : b);
+}
+
 // one batch of merges: union + exact select + ordered emit.  `round` picks which of the
 // two select states is used (it must be clear on entry); the other one is cleared on the
 // side for the next round.
@@ -327,8 +337,8 @@ template <bool DIVIDE>
 void do_merge_batch(const uint32_t* a_idx, const float* a_val, const uint32_t* b_idx,
                     const float* b_val, uint32_t k, uint32_t batch, int64_t in_stride,
                     uint32_t* out_idx, float* out_val, int64_t out_stride, const MergeWs& w,
-                    int round, const uint32_t* in_min, uint32_t* out_min, float divisor,
-                    uint32_t* gbits, hipStream_t st) {
+                    int round, const uint32_t* in_min, bool in_min_inverted, uint32_t* out_min,
+                    float divisor, uint32_t* gbits, hipStream_t st) {
     const bool odd = (round & 1) != 0;
     uint32_t* zp = odd ? w.sel.hist : w.sel_alt.hist;
     const uint32_t zw = (uint32_t)(odd ? select_clear_words(w.sel) : w.alt_clear_words);
@@ -342,7 +352,7 @@ void do_merge_batch(const uint32_t* a_idx, const float* a_val, const uint32_t* b
                            dim3(ceil_div(2 * k, kBlock * kUnionPathEpt), batch), dim3(kBlock), 0, st,
                            a_idx, a_val, b_idx, b_val, k, in_stride, w.m_idx, w.m_val, w.m_stride, zp,
                            zw);
-    MergedSrc src{w.m_idx, w.m_val, 2 * k, w.m_stride, w.L, in_min};
+    MergedSrc src{w.m_idx, w.m_val, 2 * k, w.m_stride, w.L, in_min, in_min_inverted};
     SelState ss = odd ? w.sel_alt : w.sel;
     ss.T_out = out_min;
     run_select<MergedSrc, DIVIDE>(src, ss, batch, k, 2ull * k, out_idx, out_val, out_stride, divisor,
@@ -362,7 +372,15 @@ int do_tree(const uint32_t* loc_idx, const float* loc_val, const uint32_t* loc_m
     }
     if (!pre_cleared)
         zero_async(st, w.mrg.sel.hist, select_clear_words(w.mrg.sel), w.mrg.sel_alt.hist,
-                   w.mrg.alt_clear_words);
+                   w.mrg.alt_clear_words, w.mrg.inv_min, P);
+    bool inverted = false;
+    if (!loc_min) {
+        // sets from the caller: find their smallest keys, the first round's lower bounds
+        hipLaunchKernelGGL(k_set_min_key, dim3(min_key_blocks(k), P), dim3(kBlock), 0, st, loc_val,
+                           (const float*)nullptr, (int64_t)k, k, w.mrg.inv_min);
+        loc_min = w.mrg.inv_min;
+        inverted = true;
+    }
     // After every round the surviving sets are stored compactly, so round j always
     // merges set 2p with set 2p+1 of its input: exactly worker p*2^(j+1) with worker
     // p*2^(j+1) + 2^j of the original numbering.
@@ -377,12 +395,14 @@ int do_tree(const uint32_t* loc_idx, const float* loc_val, const uint32_t* loc_m
         uint32_t* out_min = w.mrg.tmin[round & 1];
         if (last) {
             do_merge_batch<true>(in_idx, in_val, in_idx + k, in_val + k, k, 1, 2 * (int64_t)k, g_idx,
-                                 g_val, k, w.mrg, round, in_min, out_min, divisor, gbits, st);
+                                 g_val, k, w.mrg, round, in_min, inverted, out_min, divisor, gbits,
+                                 st);
         } else {
             do_merge_batch<false>(in_idx, in_val, in_idx + k, in_val + k, k, pairs, 2 * (int64_t)k,
-                                  ping_i, ping_v, k, w.mrg, round, in_min, out_min, 1.0f, nullptr,
-                                  st);
+                                  ping_i, ping_v, k, w.mrg, round, in_min, inverted, out_min, 1.0f,
+                                  nullptr, st);
             in_min = out_min;
+            inverted = false;
             in_idx = ping_i; in_val = ping_v;
             uint32_t* ti = ping_i; ping_i = pong_i; pong_i = ti;
             float* tv = ping_v; ping_v = pong_v; pong_v = tv;
@@ -412,7 +432,7 @@ size_t gtopk_workspace_bytes(int64_t m, int32_t k, int32_t P) {
 }
 
 size_t gtopk_merge_workspace_bytes(int32_t k, int32_t batch) {
-    if (k < 1 || k > kMaxMergeK || batch < 1 || batch > 65535) return 0;
+    if (k < 1 || k > kMaxMergeK || batch < 1 || batch > 32767) return 0;
     Carver c{nullptr};
     return carve_merge(c, (uint32_t)k, (size_t)batch).bytes;
 }
@@ -435,7 +455,7 @@ int gtopk_merge(const uint32_t* a_idx, const float* a_val, const uint32_t* b_idx
                 int32_t k, int32_t batch, int64_t in_stride, uint32_t* out_idx, float* out_val,
                 int64_t out_stride, void* ws, size_t ws_bytes, void* stream) {
     if (!a_idx || !a_val || !b_idx || !b_val || !out_idx || !out_val || !ws) return GTOPK_EINVAL;
-    if (k < 1 || k > kMaxMergeK || batch < 1 || batch > 65535 || in_stride < k || out_stride < k)
+    if (k < 1 || k > kMaxMergeK || batch < 1 || batch > 32767 || in_stride < k || out_stride < k)
         return GTOPK_EINVAL;
     if (!aligned16(a_idx) || !aligned16(a_val) || !aligned16(b_idx) || !aligned16(b_val) ||
         !aligned16(out_idx) || !aligned16(out_val) || !aligned16(ws))
@@ -444,9 +464,12 @@ int gtopk_merge(const uint32_t* a_idx, const float* a_val, const uint32_t* b_idx
     const MergeWs w = carve_merge(c, (uint32_t)k, (size_t)batch);
     if (ws_bytes < w.bytes) return GTOPK_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    zero_async(st, w.sel.hist, select_clear_words(w.sel));
+    zero_async(st, w.sel.hist, select_clear_words(w.sel), w.inv_min, 2 * (size_t)batch);
+    hipLaunchKernelGGL(k_set_min_key, dim3(min_key_blocks((uint32_t)k), 2 * (uint32_t)batch),
+                       dim3(kBlock), 0, st, a_val, b_val, in_stride, (uint32_t)k, w.inv_min);
     do_merge_batch<false>(a_idx, a_val, b_idx, b_val, (uint32_t)k, (uint32_t)batch, in_stride,
-                          out_idx, out_val, out_stride, w, 0, nullptr, nullptr, 1.0f, nullptr, st);
+                          out_idx, out_val, out_stride, w, 0, w.inv_min, true, nullptr, 1.0f, nullptr,
+                          st);
     return launch_status();
 }
 
@@ -555,7 +578,7 @@ int gtopk_topk_allreduce(const uint32_t* loc_idx, const float* loc_val, int32_t 
     hipStream_t st = (hipStream_t)stream;
     const uint32_t nranges = ceil_div((uint64_t)m, kAggRange);
     uint32_t* bounds = reinterpret_cast<uint32_t*>(ws);
-    hipLaunchKernelGGL(k_slice_bounds, dim3(ceil_div((uint32_t)k, kBlock), (uint32_t)P), dim3(kBlock),
+    hipLaunchKernelGGL(k_slice_bounds, dim3(ceil_div(nranges + 1, kBlock), (uint32_t)P), dim3(kBlock),
                        0, st, loc_idx, (uint32_t)k, nranges, bounds);
     hipLaunchKernelGGL(k_scatter_mean, dim3(nranges), dim3(kBlock), 0, st, loc_idx, loc_val,
                        (uint32_t)P, (uint32_t)k, (uint32_t)m, bounds, nranges, (float)P, dense);

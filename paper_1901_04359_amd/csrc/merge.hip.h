@@ -317,6 +317,33 @@ __global__ __launch_bounds__(kBlock) void k_union_path(
     }
 }
 
+// Smallest key of each k-set, for sets that did not come out of a select of this library:
+// out[s] = max over the set of (0x7fffffff - key), by atomic maximum onto a zeroed word.
+// Set s is row s of v0 (v1 == NULL), or row s/2 of v0 (s even) / v1 (s odd).
+__global__ __launch_bounds__(kBlock) void k_set_min_key(
+        const float* __restrict__ v0, const float* __restrict__ v1, int64_t stride, uint32_t k,
+        uint32_t* __restrict__ out) {
+    __shared__ uint32_t s_wave[kBlock / kWave];
+    const uint32_t s = blockIdx.y;
+    const float* v = v1 ? ((s & 1) ? v1 : v0) + (int64_t)(s >> 1) * stride : v0 + (int64_t)s * stride;
+    uint32_t best = 0;
+    for (uint32_t i = blockIdx.x * kBlock + threadIdx.x; i < k; i += gridDim.x * kBlock) {
+        const uint32_t inv = kAbs - (__float_as_uint(v[i]) & kAbs);
+        best = inv > best ? inv : best;
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const uint32_t o = __shfl_xor(best, d);
+        best = o > best ? o : best;
+    }
+    if (lane_id() == 0) s_wave[threadIdx.x / kWave] = best;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < kBlock / kWave; ++w) best = s_wave[w] > best ? s_wave[w] : best;
+        atomicMax(&out[s], best);
+    }
+}
+
 // P == 1: the tree has no round; the global set is worker 0's set divided by 1.
 __global__ void k_copy_set(const uint32_t* __restrict__ in_idx, const float* __restrict__ in_val,
                            uint32_t k, uint32_t* __restrict__ out_idx, float* __restrict__ out_val,

@@ -128,8 +128,8 @@ struct CandSrc {
 // Every key of the union that is a plain copy of an operand's entry is at least that
 // operand's smallest key, so the larger of the two smallest keys bounds the k-th key of
 // the union from below (sums that cancel can fall under it; they land in bin 0).
-// in_min[2s], in_min[2s+1] are those smallest keys when the operands came out of a
-// select of this library (its T); NULL when the caller supplied the sets.
+// in_min[2s], in_min[2s+1] are those smallest keys (NULL: not known; inverted: stored as
+// 0x7fffffff - key, the form in which k_set_min_key's atomic maximum leaves them).
 struct MergedSrc {
     static constexpr bool kIdentity = true;
     static constexpr bool kRunScan = false;
@@ -137,12 +137,14 @@ struct MergedSrc {
     const float* val;
     uint32_t n, stride, L;       // L slots per group
     const uint32_t* in_min;
+    bool inverted;
     __device__ bool dense(int) const { return false; }
     __device__ uint32_t nphys(int, bool) const { return n; }
     __device__ uint32_t group_slots(bool) const { return L; }
     __device__ Digit digit(int s, bool, const SelState&) const {
         if (!in_min) return Digit{0u, (uint32_t)kCoarseShift};
-        const uint32_t ma = in_min[2 * s], mb = in_min[2 * s + 1];
+        uint32_t ma = in_min[2 * s], mb = in_min[2 * s + 1];
+        if (inverted) { ma = kAbs - ma; mb = kAbs - mb; }
         return Digit{ma > mb ? ma : mb, (uint32_t)kFineShift};
     }
     __device__ bool fetch_phys(int s, bool, uint32_t p, uint32_t& i, uint32_t& bits) const {
