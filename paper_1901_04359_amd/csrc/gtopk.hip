@@ -94,6 +94,15 @@ uint32_t group_slots_for(uint64_t n, uint32_t max_groups) {
     return L < 1024u ? 1024u : L;
 }
 
+// Groups per set when `sets` sets are selected from side by side.  Every block of k_bucket
+// and k_emit pays a fixed price (it reads the set's 4096-bin histogram, or the list of
+// in-bin keys), so a batch gets about kTargetBlocks blocks in total and no more.
+constexpr uint32_t kTargetBlocks = 4096;
+uint32_t groups_for(uint32_t sets) {
+    const uint32_t g = kTargetBlocks / (sets ? sets : 1);
+    return g < 32 ? 32 : (g > (uint32_t)kMaxGroups ? (uint32_t)kMaxGroups : g);
+}
+
 constexpr uint64_t kInlineFinishMax = 1u << 20;  // sets up to this many slots: no k_finish
 constexpr uint32_t kUnionPathMinK = 65536;      // sets above this size take k_union_path
 constexpr int kUnionPathEpt = 8;
@@ -225,9 +234,9 @@ void zero_async(hipStream_t st, uint32_t* p0, size_t n0, uint32_t* p1 = nullptr,
 
 // histogram + bucket + emit over `sets` sets of at most nphys_max slots each
 template <class Src, bool DIVIDE>
-void run_select(const Src& src, const SelState& ss, uint32_t sets, uint32_t k, uint64_t nphys_max,
-                uint32_t* out_idx, float* out_val, int64_t out_stride, float divisor,
-                uint32_t* gbits, hipStream_t st) {
+void run_select(const Src& src, const SelState& ss, uint32_t sets, uint32_t groups, uint32_t k,
+                uint64_t nphys_max, uint32_t* out_idx, float* out_val, int64_t out_stride,
+                float divisor, uint32_t* gbits, hipStream_t st) {
     // few blocks per set (a popular bin takes one same-address atomic per block): one batch
     // of 4 slots per thread up to 32 blocks, then more slots per thread, then up to 256 blocks
     uint32_t hb = ceil_div(nphys_max, 4 * kHistBlock);
@@ -237,15 +246,15 @@ void run_select(const Src& src, const SelState& ss, uint32_t sets, uint32_t k, u
     }
     hipLaunchKernelGGL((k_hist<Src>), dim3(hb + (Src::kRunScan ? 1 : 0), sets), dim3(kHistBlock), 0,
                        st, src, ss, hb);
-    hipLaunchKernelGGL((k_bucket<Src>), dim3(ss.maxgroups, sets), dim3(kBlock), 0, st, src, ss, k);
+    hipLaunchKernelGGL((k_bucket<Src>), dim3(groups, sets), dim3(kBlock), 0, st, src, ss, k);
     // small sets: every block of the emit finishes the select itself (the list of keys it
     // needs for that is short); large sets: once per set, in a kernel of its own
     if (nphys_max <= kInlineFinishMax) {
-        hipLaunchKernelGGL((k_emit<Src, DIVIDE, true>), dim3(ss.maxgroups, sets), dim3(kBlock), 0, st,
+        hipLaunchKernelGGL((k_emit<Src, DIVIDE, true>), dim3(groups, sets), dim3(kBlock), 0, st,
                            src, ss, k, out_idx, out_val, out_stride, divisor, gbits);
     } else {
         hipLaunchKernelGGL((k_finish<Src>), dim3(sets), dim3(1024), 0, st, src, ss);
-        hipLaunchKernelGGL((k_emit<Src, DIVIDE, false>), dim3(ss.maxgroups, sets), dim3(kBlock), 0, st,
+        hipLaunchKernelGGL((k_emit<Src, DIVIDE, false>), dim3(groups, sets), dim3(kBlock), 0, st,
                            src, ss, k, out_idx, out_val, out_stride, divisor, gbits);
     }
 }
@@ -316,8 +325,8 @@ int do_local_select(const float* grad, float* residual, int64_t m, int64_t strid
     CandSrc src{residual, stride, (uint32_t)m, k, w.cap, w.nchunks, w.Lc, w.Ld,
                 w.cand_idx, w.cand_val, w.cand_count, w.tspec, w.run_table, w.run_off,
                 w.ord_idx, w.ord_val};
-    run_select<CandSrc, false>(src, w.sel, P, k, w.cap, out_idx, out_val, (int64_t)k, 1.0f, nullptr,
-                               st);
+    run_select<CandSrc, false>(src, w.sel, P, w.sel.maxgroups, k, w.cap, out_idx, out_val, (int64_t)k,
+                               1.0f, nullptr, st);
     // a kernel of its own: while the select runs, a dense row may still be read as a whole
     if (zero_rows)
         hipLaunchKernelGGL(k_zero_selected, dim3(ceil_div(k, kBlock), P), dim3(kBlock), 0, st, out_idx,
@@ -352,11 +361,16 @@ void do_merge_batch(const uint32_t* a_idx, const float* a_val, const uint32_t* b
                            dim3(ceil_div(2 * k, kBlock * kUnionPathEpt), batch), dim3(kBlock), 0, st,
                            a_idx, a_val, b_idx, b_val, k, in_stride, w.m_idx, w.m_val, w.m_stride, zp,
                            zw);
-    MergedSrc src{w.m_idx, w.m_val, 2 * k, w.m_stride, w.L, in_min, in_min_inverted};
+    // w.L is the smallest group the workspace was sized for; a batch of many pairs takes larger ones
+    uint32_t L = group_slots_for(2ull * k, groups_for(batch));
+    if (L > 4096u) L = 4096u;
+    if (L < w.L) L = w.L;
+    const uint32_t groups = ceil_div(2ull * k, L);
+    MergedSrc src{w.m_idx, w.m_val, 2 * k, w.m_stride, L, in_min, in_min_inverted};
     SelState ss = odd ? w.sel_alt : w.sel;
     ss.T_out = out_min;
-    run_select<MergedSrc, DIVIDE>(src, ss, batch, k, 2ull * k, out_idx, out_val, out_stride, divisor,
-                                  gbits, st);
+    run_select<MergedSrc, DIVIDE>(src, ss, batch, groups, k, 2ull * k, out_idx, out_val, out_stride,
+                                  divisor, gbits, st);
 }
 
 // loc_min: the smallest key of each of the P input sets (the local selection's T), or NULL
@@ -600,8 +614,8 @@ int gtopk_dense_topk(const float* dense, int64_t m, int32_t k, uint32_t* g_idx, 
     CandSrc src{dense, m, (uint32_t)m, (uint32_t)k, w.cap, w.nchunks, w.Lc, w.Ld,
                 w.cand_idx, w.cand_val, w.cand_count, w.tspec, w.run_table, w.run_off,
                 w.ord_idx, w.ord_val};
-    run_select<CandSrc, false>(src, w.sel, 1, (uint32_t)k, (uint64_t)m, g_idx, g_val, (int64_t)k,
-                               1.0f, nullptr, st);
+    run_select<CandSrc, false>(src, w.sel, 1, w.sel.maxgroups, (uint32_t)k, (uint64_t)m, g_idx, g_val,
+                               (int64_t)k, 1.0f, nullptr, st);
     return launch_status();
 }
 
