@@ -34,14 +34,14 @@ N_STAGES = 6
 STAGE_NAMES = ["sample", "accumulate_filter", "exact_select", "tree", "restore"]
 
 
-def read_traffic_note(workload: str):
-    """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc
-    summary (a line `traffic_bytes_per_launch <workload> <bytes>`), or None."""
+def read_traffic_note(workload: str, what: str = "traffic_bytes_per_launch"):
+    """HBM bytes per launch of the dominant kernel (or per step), from the committed
+    rocprofv3 --pmc summary (a line `<what> <workload> <bytes>`), or None."""
     path = os.path.join(ROOT, "profiles", "k_accum_filter_traffic.txt")
     try:
         for line in open(path):
             f = line.split()
-            if len(f) == 3 and f[0] == "traffic_bytes_per_launch" and f[1] == workload:
+            if len(f) == 3 and f[0] == what and f[1] == workload:
                 return float(f[2])
     except OSError:
         pass
@@ -123,6 +123,32 @@ def time_aggregations(B, torch, cfg, grads, reps: int = 20):
     }
 
 
+def time_three_calls(B, torch, cfg, grads, res, g_idx, g_val, ws, reps: int = 10):
+    """gtopk_local_select, gtopk_tree and gtopk_residual_restore timed one by one (HIP events,
+    `reps` repetitions each; the residual keeps evolving, as in training)."""
+    P, k = cfg.P, cfg.k
+    loc_idx = torch.zeros((P, k), dtype=torch.int32, device="cuda")
+    loc_val = torch.zeros((P, k), dtype=torch.float32, device="cuda")
+
+    def timed(fn):
+        fn(0)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(reps):
+            fn(i + 1)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    t_sel = timed(lambda i: B.gtopk_local_select(grads[i % len(grads)], res, k, loc_idx, loc_val, ws))
+    t_tree = timed(lambda i: B.gtopk_tree(loc_idx, loc_val, P, k, g_idx, g_val, ws))
+    t_res = timed(lambda i: B.gtopk_residual_restore(res, k, loc_idx, loc_val, g_idx))
+    return {"gtopk_local_select_ms": round(t_sel, 4), "gtopk_tree_ms": round(t_tree, 4),
+            "gtopk_residual_restore_ms": round(t_res, 4),
+            "sum_ms": round(t_sel + t_tree + t_res, 4)}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -133,6 +159,9 @@ def main() -> int:
     ap.add_argument("--k", type=int, default=0, help="override the workload's k (density studies)")
     ap.add_argument("--cpu-workers", type=int, default=-1,
                     help="workers in the oracle sample (0 = skip, -1 = as many as fit in ~15 s)")
+    ap.add_argument("--three-calls", action="store_true",
+                    help="also time gtopk_local_select, gtopk_tree and gtopk_residual_restore "
+                         "one by one")
     ap.add_argument("--aggregations", action="store_true",
                     help="also time the paper's comparison aggregations (Algorithms 1 and 2) "
                          "against the tree on this workload's local sets")
@@ -204,12 +233,14 @@ def main() -> int:
         for s in range(N_STAGES - 1):
             stage_ms[s] += row[s].elapsed_time(row[s + 1])
     stage_ms /= K
+    step_gpu_ms = sorted(row[0].elapsed_time(row[N_STAGES - 1]) for row in events)
     value = P * m / (ms_per_step * 1e-3)
 
     kern_ms = float(stage_ms[1])
     alg_bytes = 12.0 * P * m
     achieved = alg_bytes / (kern_ms * 1e-3) / 1e9
     traffic = read_traffic_note(cfg.name)
+    step_traffic = read_traffic_note(cfg.name, "traffic_bytes_per_step")
     label = {"C1": "tiny", "C2": "ResNet-20-sized", "C3": "VGG-16-sized", "C4a": "ResNet-50-sized",
              "C4b": "ResNet-50-sized", "C5": "AlexNet-sized"}.get(args.workload, "")
     out = {
@@ -222,14 +253,21 @@ def main() -> int:
                                f"batches cycled, residual carried across steps",
                    "m": m, "P": P, "k": k},
         "step_hbm": {"algorithmic_GBs": alg_bytes / (ms_per_step * 1e-3) / 1e9,
-                     "frac_of_peak": alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS},
+                     "frac_of_peak": alg_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                     "counter_GBs": (step_traffic / (ms_per_step * 1e-3) / 1e9
+                                     if step_traffic else None)},
         "stages_ms": {n: round(float(v), 4) for n, v in zip(STAGE_NAMES, stage_ms)},
+        "step_gpu_ms": {"median": round(step_gpu_ms[len(step_gpu_ms) // 2], 4),
+                        "min": round(step_gpu_ms[0], 4), "max": round(step_gpu_ms[-1], 4),
+                        "note": "per step, first to last HIP event of the step"},
         "roofline": {"kernel": "k_accum_filter", "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic, "launch_ms": kern_ms,
                      "algorithmic_bytes_per_launch": alg_bytes},
         "input_generation_s": round(t_gen, 1),
     }
+    if args.three_calls:
+        out["three_calls"] = time_three_calls(B, torch, cfg, grads, res, g_idx, g_val, ws)
     if args.aggregations:
         del res, ws
         out["aggregations"] = time_aggregations(B, torch, cfg, grads)

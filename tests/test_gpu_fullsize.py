@@ -58,3 +58,37 @@ def test_full_size_step(name, iters):
         # every worker must have been served from its candidate list (the timed path)
         counts, cap = dev.B.gtopk_debug_candidate_counts(dev.ws, m, k, P)
         assert all(k <= c <= cap for c in counts), (name, it, min(counts), max(counts), cap)
+
+
+@pytest.mark.parametrize("name", ["C4a", "C4b"])
+def test_full_size_comparison_aggregations_and_update(name):
+    """Algorithm 1's all-reduce, Algorithm 2's second top-k, the model update and the dense
+    gMask at a config's full size, on the local sets of its first iteration."""
+    import torch
+    from paper_1901_04359_amd import binding as B
+    cfg = W.CONFIGS[name]
+    P, m, k = cfg.P, cfg.m, cfg.k
+    dev = Device(P, m, k)
+    say(f"full size {name}: generating P={P} m={m}")
+    dev.set_grad(W.gradients(cfg, 0, threads=THREADS))
+    say(f"full size {name}: local select k={k}")
+    li, lv = dev.local_select()
+    dense = torch.empty(m, dtype=torch.float32, device="cuda")
+    say(f"full size {name}: topk_allreduce")
+    B.gtopk_topk_allreduce(dev.loc_idx, dev.loc_val, P, k, dense, B.alloc_allreduce_workspace(m, P))
+    o_dense = orc.topk_allreduce(list(li), list(lv), m)
+    got = dense.cpu().numpy()
+    assert bits_equal(got, o_dense), first_diff(got, o_dense)
+    say(f"full size {name}: dense_topk")
+    B.gtopk_dense_topk(dense, k, dev.g_idx, dev.g_val, B.alloc_workspace(m, k, 1))
+    o_gi, o_gv = orc.dense_topk(o_dense, k)
+    assert np.array_equal(idx_np(dev.g_idx), o_gi)
+    assert bits_equal(val_np(dev.g_val), o_gv)
+    say(f"full size {name}: apply_update, dense_mask")
+    wts = np.linspace(-1.0, 1.0, m, dtype=np.float32)
+    d_w = torch.from_numpy(wts).cuda()
+    B.gtopk_apply_update(d_w, k, dev.g_idx, dev.g_val, 0.01)
+    assert bits_equal(d_w.cpu().numpy(), orc.apply_update(wts, o_gi, o_gv, 0.01))
+    mask = torch.empty(m, dtype=torch.uint8, device="cuda")
+    B.gtopk_dense_mask(dev.g_idx, k, mask)
+    assert np.array_equal(mask.cpu().numpy(), orc.dense_mask(o_gi, m))
