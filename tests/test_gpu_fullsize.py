@@ -92,3 +92,50 @@ def test_full_size_comparison_aggregations_and_update(name):
     mask = torch.empty(m, dtype=torch.uint8, device="cuda")
     B.gtopk_dense_mask(dev.g_idx, k, mask)
     assert np.array_equal(mask.cpu().numpy(), orc.dense_mask(o_gi, m))
+
+
+def test_maximum_row_length():
+    """m = 2^31, the largest row the library accepts (P = 1, k = m/1000).  No CPU oracle can
+    sort a row of this length in test time, so the result is checked through the properties
+    that define it, evaluated with plain torch operations on the GPU: the selected values are
+    the accumulated ones at ascending indices, every unselected key is at most the smallest
+    selected key T, ties at T are taken lowest index first, and the residual is the
+    accumulated row with the selected entries at +0.0."""
+    import torch
+    from paper_1901_04359_amd import binding as B
+    m, k = 1 << 31, (1 << 31) // 1000
+    say(f"maximum row: generating m={m} on the device")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(190104359)
+    grad = torch.randn(m, dtype=torch.float32, device="cuda", generator=gen).mul_(1e-3)
+    res = torch.randn(m, dtype=torch.float32, device="cuda", generator=gen).mul_(1e-3)
+    acc = res + grad
+    g_idx = torch.zeros(k, dtype=torch.int32, device="cuda")
+    g_val = torch.zeros(k, dtype=torch.float32, device="cuda")
+    loc_idx = torch.zeros((1, k), dtype=torch.int32, device="cuda")
+    loc_val = torch.zeros((1, k), dtype=torch.float32, device="cuda")
+    ws = B.alloc_workspace(m, k, 1)
+    say(f"maximum row: gtopk_step m={m} k={k} P=1")
+    B.gtopk_step(grad.view(1, m), res.view(1, m), k, g_idx, g_val, loc_idx, loc_val, ws)
+    torch.cuda.synchronize()
+    del grad
+    li = loc_idx[0].long()                       # indices < 2^31 are non-negative as int32
+    assert bool((li >= 0).all()) and bool((li[1:] > li[:-1]).all())
+    assert torch.equal(loc_val[0].view(torch.int32), acc[li].view(torch.int32))
+    assert torch.equal(g_idx, loc_idx[0]) and torch.equal(g_val.view(torch.int32),
+                                                          loc_val[0].view(torch.int32))
+    keys = acc.view(torch.int32) & 0x7FFFFFFF
+    T = int(keys[li].min())
+    selected = torch.zeros(m, dtype=torch.bool, device="cuda")
+    selected[li] = True
+    assert int(selected.sum()) == k
+    assert not bool(((keys > T) & ~selected).any())
+    step = 1 << 28                # torch.nonzero cannot take 2^31 elements at once
+    ties = torch.cat([torch.nonzero(keys[a:a + step] == T).flatten() + a for a in range(0, m, step)])
+    n_taken = int(selected[ties].sum())
+    assert n_taken >= 1 and bool(selected[ties[:n_taken]].all())
+    del keys
+    expect = torch.where(selected, torch.zeros((), dtype=torch.float32, device="cuda"), acc)
+    assert torch.equal(res.view(torch.int32), expect.view(torch.int32))
+    counts, cap = B.gtopk_debug_candidate_counts(ws, m, k, 1)
+    assert k <= counts[0] <= cap
