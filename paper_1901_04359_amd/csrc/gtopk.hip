@@ -106,6 +106,7 @@ uint32_t groups_for(uint32_t sets) {
 constexpr uint64_t kInlineFinishMax = 1u << 20;  // sets up to this many slots: no k_finish
 constexpr uint32_t kUnionPathMinK = 65536;      // sets above this size take k_union_path
 constexpr int kUnionPathEpt = 8;
+constexpr uint32_t kUnionCutsMinK = 1u << 19;   // sets above this size: cut points in a kernel of their own
 
 struct MergeWs {
     SelState sel;      // state of even rounds
@@ -116,6 +117,7 @@ struct MergeWs {
     uint32_t m_stride;
     uint32_t* tmin[2]; // [pairs] smallest key of each output set, alternating between rounds
     uint32_t* inv_min; // [2*pairs] 0x7fffffff - smallest key of each caller-supplied operand
+    uint32_t* cuts;    // [pairs][tiles + 1] cut points of k_union_path's blocks (large sets)
     uint32_t L;
     size_t bytes;
 };
@@ -131,6 +133,9 @@ MergeWs carve_merge(Carver& c, uint32_t k, size_t pairs) {
     w.tmin[0] = c.take<uint32_t>(pairs);
     w.tmin[1] = c.take<uint32_t>(pairs);
     w.inv_min = c.take<uint32_t>(2 * pairs);
+    w.cuts = c.take<uint32_t>(k > kUnionCutsMinK
+                                  ? pairs * ((size_t)ceil_div(2ull * k, kBlock * kUnionPathEpt) + 1)
+                                  : 0);
     w.bytes = c.off;
     return w;
 }
@@ -356,11 +361,19 @@ void do_merge_batch(const uint32_t* a_idx, const float* a_val, const uint32_t* b
     if (k <= kUnionPathMinK)
         hipLaunchKernelGGL(k_union<1>, dim3(ceil_div(k, kBlock), batch), dim3(kBlock), 0, st, a_idx,
                            a_val, b_idx, b_val, k, in_stride, w.m_idx, w.m_val, w.m_stride, zp, zw);
-    else
-        hipLaunchKernelGGL(k_union_path<kUnionPathEpt>,
+    else if (k <= kUnionCutsMinK)
+        hipLaunchKernelGGL((k_union_path<kUnionPathEpt, false>),
                            dim3(ceil_div(2 * k, kBlock * kUnionPathEpt), batch), dim3(kBlock), 0, st,
-                           a_idx, a_val, b_idx, b_val, k, in_stride, w.m_idx, w.m_val, w.m_stride, zp,
-                           zw);
+                           a_idx, a_val, b_idx, b_val, k, in_stride, w.m_idx, w.m_val, w.m_stride,
+                           (const uint32_t*)nullptr, zp, zw);
+    else {
+        const uint32_t tile = kBlock * kUnionPathEpt, ntiles = ceil_div(2 * k, tile);
+        hipLaunchKernelGGL(k_union_cuts, dim3(ceil_div(ntiles + 1, kBlock), batch), dim3(kBlock), 0, st,
+                           a_idx, b_idx, k, in_stride, tile, ntiles, w.cuts);
+        hipLaunchKernelGGL((k_union_path<kUnionPathEpt, true>), dim3(ntiles, batch), dim3(kBlock), 0, st,
+                           a_idx, a_val, b_idx, b_val, k, in_stride, w.m_idx, w.m_val, w.m_stride,
+                           (const uint32_t*)w.cuts, zp, zw);
+    }
     // w.L is the smallest group the workspace was sized for; a batch of many pairs takes larger ones
     uint32_t L = group_slots_for(2ull * k, groups_for(batch));
     if (L > 4096u) L = 4096u;

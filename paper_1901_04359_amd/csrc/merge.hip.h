@@ -193,17 +193,41 @@ __device__ inline uint32_t wave_first_false(uint32_t lo, uint32_t hi, Pred pred)
 // that B entry's slot is a tombstone - exactly the layout k_union produces.
 // A block owns kBlock*EPT consecutive slots.  Two of its waves find, each with one 64-ary
 // search along a diagonal of the merge grid, how many A entries precede the block's
-// first and last slot; the A and B entries in between (kBlock*EPT in total) are staged in
+// first and last slot (CUTS: k_union_cuts has done that for all blocks beforehand, which
+// pays for very large sets); the A and B entries in between (kBlock*EPT in total) are staged in
 // LDS; every thread then finds the start of its own EPT slots with a binary search in LDS
 // and merges EPT steps sequentially.  Rows of m_idx / m_val are m_stride apart (a multiple
 // of EPT, 16-byte aligned), so every thread stores whole vectors; slots past 2k in the
 // row's padding become tombstones.
-template <int EPT>
+// cuts[s][c] = number of A entries among the first c * tile slots of pair s (c = 0 .. ntiles;
+// the last one is clamped to 2k slots): what k_union_path's blocks need, one binary
+// search along a diagonal each, all side by side instead of one after the other in
+// front of every block's work.
+__global__ __launch_bounds__(kBlock) void k_union_cuts(
+        const uint32_t* __restrict__ a_idx, const uint32_t* __restrict__ b_idx, uint32_t k,
+        int64_t in_stride, uint32_t tile, uint32_t ntiles, uint32_t* __restrict__ cuts) {
+    const uint32_t c = blockIdx.x * kBlock + threadIdx.x;
+    const int s = blockIdx.y;
+    if (c > ntiles) return;
+    const uint32_t* ai = a_idx + (int64_t)s * in_stride;
+    const uint32_t* bi = b_idx + (int64_t)s * in_stride;
+    const uint64_t pp = (uint64_t)c * tile;
+    const uint32_t p = pp < 2ull * k ? (uint32_t)pp : 2 * k;
+    uint32_t lo = p > k ? p - k : 0u, hi = p < k ? p : k;
+    while (lo < hi) {                 // A[x] is among the first p slots iff A[x] <= B[p-1-x]
+        const uint32_t mid = (lo + hi) >> 1;
+        if (ai[mid] <= bi[p - 1 - mid]) lo = mid + 1; else hi = mid;
+    }
+    cuts[(size_t)s * (ntiles + 1) + c] = lo;
+}
+
+template <int EPT, bool CUTS>
 __global__ __launch_bounds__(kBlock) void k_union_path(
         const uint32_t* __restrict__ a_idx, const float* __restrict__ a_val,
         const uint32_t* __restrict__ b_idx, const float* __restrict__ b_val, uint32_t k,
         int64_t in_stride, uint32_t* __restrict__ m_idx, float* __restrict__ m_val,
-        uint32_t m_stride, uint32_t* __restrict__ zero_ptr, uint32_t zero_words) {
+        uint32_t m_stride, const uint32_t* __restrict__ cuts, uint32_t* __restrict__ zero_ptr,
+        uint32_t zero_words) {
     static_assert(EPT % 4 == 0, "whole 16-byte vectors per thread");
     constexpr uint32_t kTile = kBlock * EPT;
     constexpr uint32_t kStage = kTile + 3;         // A: previous + entries + sentinel; B: entries + next
@@ -227,7 +251,13 @@ __global__ __launch_bounds__(kBlock) void k_union_path(
     const uint32_t* bi = b_idx + (int64_t)s * in_stride;
     const float* bv = b_val + (int64_t)s * in_stride;
     const uint32_t wave = threadIdx.x / kWave;
-    if (wave < 2) {
+    if (CUTS) {
+        if (threadIdx.x < 2) {
+            uint32_t x = cuts[(size_t)s * (gridDim.x + 1) + blockIdx.x + threadIdx.x];
+            if (x > k) x = k;             // only for operands that are not sorted
+            s_split[threadIdx.x] = x;
+        }
+    } else if (wave < 2) {
         // number of A entries among the first p slots: A[x] is one of them iff A[x] <= B[p-1-x]
         const uint32_t p = wave == 0 ? p0 : p1;
         const uint32_t lo = p > k ? p - k : 0u, hi = p < k ? p : k;
