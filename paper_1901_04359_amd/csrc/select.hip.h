@@ -495,6 +495,7 @@ __global__ __launch_bounds__(kBlock) void k_emit(
     __shared__ uint32_t s_red[2][kWaves];
     __shared__ uint32_t s_eq[kBatch * kWaves];
     __shared__ uint32_t s_sel[kBatch * kWaves];
+    __shared__ uint32_t s_cmp[kBlock];
     const int s = blockIdx.y;
     const uint32_t g = blockIdx.x;
     const uint32_t t = threadIdx.x;
@@ -686,11 +687,32 @@ __global__ __launch_bounds__(kBlock) void k_emit(
                     if (DIVIDE) v = v / divisor;
                     out_val[(int64_t)s * out_stride + pos] = v;
                 }
-                if (gbits) atomicOr(&gbits[idx[j] >> 5], 1u << (idx[j] & 31));
             }
         }
         outp += sel_all;
         eq_before += eq_all;
+        if (gbits) {                      // block-uniform
+            // a wave's selected indices, compacted, are ascending: the first of each run that
+            // shares a bitmap word sets the bits of the whole run with one atomic
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+                const uint32_t nsel = (uint32_t)__popcll(selm[j]);
+                if (sel[j]) s_cmp[wave * kWave + rank_in(selm[j])] = idx[j];
+                __syncthreads();
+                const uint32_t lane = lane_id();
+                if (lane < nsel) {
+                    const uint32_t* c = s_cmp + wave * kWave;
+                    const uint32_t word = c[lane] >> 5;
+                    if (lane == 0 || (c[lane - 1] >> 5) != word) {
+                        uint32_t bits = 1u << (c[lane] & 31);
+                        for (uint32_t q = lane + 1; q < nsel && (c[q] >> 5) == word; ++q)
+                            bits |= 1u << (c[q] & 31);
+                        atomicOr(&gbits[word], bits);
+                    }
+                }
+                __syncthreads();
+            }
+        }
     }
 }
 
