@@ -352,6 +352,15 @@ def pin_hand_worked_example():
     assert out["g_idx"].tolist() == ex["g_idx"]
     assert out["g_val"].tolist() == ex["g_val"]
     assert np.array_equal(out["residual"], np.array(ex["residual"], dtype=np.float32))
+    # the same local sets through Algorithm 1's all-reduce and Algorithm 2's second top-k
+    dense = orc.topk_allreduce(list(out["loc_idx"]), list(out["loc_val"]), m)
+    assert dense.tolist() == ex["alg1_dense"]
+    n_idx, n_val = orc.dense_topk(dense, k)
+    assert n_idx.tolist() == ex["alg2_g_idx"] and n_val.tolist() == ex["alg2_g_val"]
+    for w in range(P):
+        r = orc.residual_restore(out["residual_after_select"][w], out["loc_idx"][w],
+                                 out["loc_val"][w], n_idx)
+        assert r.tolist() == ex["alg2_residual"][w]
 
 
 def pin_step_feedback_and_bounds():
