@@ -529,3 +529,77 @@ def test_hand_worked_example_on_the_gpu():
     dev.set_res(np.array(ex["residual_after_select"], dtype=np.float32))
     dev.restore()
     assert dev.residual().tolist() == ex["alg2_residual"]
+
+
+def _random_shape_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        P = int(rng.choice([1, 2, 4, 8, 16]))
+        m = int(rng.choice([rng.integers(1, 40), rng.integers(40, 3000), rng.integers(3000, 120_000)]))
+        k = int(rng.choice([1, m, max(1, m // 1000), rng.integers(1, m + 1)]))
+        kind = str(rng.choice(["gauss", "ties", "special", "zeros_mostly"]))
+        pad = int(rng.choice([0, 0, 1, 3, 5]))
+        cases.append((P, m, k, kind, pad))
+    return cases
+
+
+@pytest.mark.parametrize("P,m,k,kind,pad", _random_shape_cases(48, 20260427))
+def test_step_random_shapes(P, m, k, kind, pad):
+    """Seeded random problem shapes (tiny rows, k = m, k = 1, odd strides) and value kinds,
+    two iterations each with the residual carried."""
+    rng = np.random.default_rng(P * 1_000_003 + m * 31 + k)
+    dev = Device(P, m, k, stride=m + pad if pad else None)
+    res = np.zeros((P, m), dtype=np.float32)
+    dev.set_res(res)
+    for it in range(2):
+        if kind == "gauss":
+            g = rng.standard_normal((P, m)).astype(np.float32)
+        elif kind == "ties":
+            g = rng.integers(-3, 4, (P, m)).astype(np.float32) * np.float32(0.5)
+        elif kind == "special":
+            g = np.stack([W.special_values(m, seed=int(rng.integers(0, 10_000))) for _ in range(P)])
+        else:
+            g = np.where(rng.random((P, m)) < 0.02, rng.standard_normal((P, m)), 0.0).astype(np.float32)
+        dev.set_grad(g)
+        say(f"random shape P={P} m={m} k={k} kind={kind} pad={pad} it={it}")
+        gi, gv = dev.step()
+        exp = orc.step(res, g, k)
+        assert np.array_equal(idx_np(dev.loc_idx), exp["loc_idx"])
+        assert bits_equal(val_np(dev.loc_val), exp["loc_val"])
+        assert np.array_equal(gi, exp["g_idx"]) and bits_equal(gv, exp["g_val"])
+        assert bits_equal(dev.residual(), exp["residual"])
+        res = exp["residual"]
+
+
+def _random_aggregation_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        P = int(rng.integers(1, 41))
+        m = int(rng.choice([rng.integers(1, 60), rng.integers(60, 9000), rng.integers(9000, 200_000)]))
+        k = int(rng.choice([1, m, max(1, m // 500), rng.integers(1, m + 1)]))
+        k = min(k, 30_000)
+        cases.append((P, m, k, float(rng.choice([0.0, 0.3, 0.9, 1.0])),
+                      str(rng.choice(["gauss", "ties", "cancel"]))))
+    return cases
+
+
+@pytest.mark.parametrize("P,m,k,overlap,kind", _random_aggregation_cases(24, 20260428))
+def test_aggregations_random_shapes(P, m, k, overlap, kind):
+    """Algorithm 1's all-reduce for any worker count, then Algorithm 2's top-k of its result."""
+    import torch
+    from paper_1901_04359_amd import binding as B
+    idx, val = W.ksets(P, k, m, seed=P * 7919 + k, overlap=overlap, value_kind=kind)
+    say(f"random aggregation P={P} m={m} k={k} overlap={overlap} kind={kind}")
+    dense = run_allreduce(idx, val, m)
+    exp = orc.topk_allreduce(list(idx), list(val), m)
+    got = dense.cpu().numpy()
+    assert bits_equal(got, exp), first_diff(got, exp)
+    g_idx = torch.zeros(k, dtype=torch.int32, device="cuda")
+    g_val = torch.zeros(k, dtype=torch.float32, device="cuda")
+    ws = B.alloc_workspace(m, k, 1)
+    ws.fill_(0x5A)
+    B.gtopk_dense_topk(dense, k, g_idx, g_val, ws)
+    oi, ov = orc.dense_topk(exp, k)
+    assert np.array_equal(idx_np(g_idx), oi) and bits_equal(val_np(g_val), ov)
