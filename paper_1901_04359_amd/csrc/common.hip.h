@@ -13,7 +13,8 @@ constexpr int kChunkLog2 = 15;
 constexpr int kChunk = 1 << kChunkLog2;                  // 32768 elements per block = one run
 static_assert(kChunk == kWaveSpan * (kSBlock / kWave), "a block covers exactly one chunk");
 constexpr int kBlock = 256;                 // threads per block of the select kernels
-constexpr int kBatch = 4;                   // items a thread loads before it processes any
+constexpr int kBatch = 2;                   // items a thread loads before it processes any (swept: 1, 2, 4, 8)
+constexpr int kHistBatch = 2;               // the same in the histogram kernel
 constexpr int kMaxGroups = 2048;            // groups per set, at most
 constexpr int kHistBins = 4096;             // bins of the first digit
 constexpr int kFineShift = 10;              // narrowest bin: 2^10 keys, when a lower bound of T is known

@@ -185,17 +185,17 @@ __global__ __launch_bounds__(kHistBlock) void k_hist(Src src, SelState st, uint3
     const uint32_t n = src.nphys(s, dn);
     const Digit dg = src.digit(s, dn, st);
     const uint64_t step = (uint64_t)hist_blocks * kHistBlock;
-    for (uint64_t p0 = (uint64_t)blockIdx.x * kHistBlock + threadIdx.x; p0 < n; p0 += step * kBatch) {
-        uint32_t key[kBatch];
-        bool ok[kBatch];
+    for (uint64_t p0 = (uint64_t)blockIdx.x * kHistBlock + threadIdx.x; p0 < n; p0 += step * kHistBatch) {
+        uint32_t key[kHistBatch];
+        bool ok[kHistBatch];
 #pragma unroll
-        for (int j = 0; j < kBatch; ++j) {
+        for (int j = 0; j < kHistBatch; ++j) {
             const uint64_t p = p0 + j * step;
             key[j] = 0;
             ok[j] = p < n && src.fetch_key_phys(s, dn, (uint32_t)p, key[j]);
         }
 #pragma unroll
-        for (int j = 0; j < kBatch; ++j) {
+        for (int j = 0; j < kHistBatch; ++j) {
             // a wave whose keys all fall into one bin (rows of zeros, equal values) adds once
             const uint32_t b = dg.bin(key[j]);
             const uint64_t act = __ballot(ok[j]);
@@ -241,7 +241,7 @@ __global__ __launch_bounds__(kBlock) void k_bucket(Src src, SelState st, uint32_
     if (first >= n) return;
     const uint32_t end = (uint32_t)(first + L < n ? first + L : n);
     const Digit dg = src.digit(s, dn, st);
-    // one round of the walk: the block's next 1024 slots, their items and logical positions
+    // one round of the walk: the block's next kBlock * kBatch slots, their items and logical positions
     uint32_t idx[kBatch], bits[kBatch], lp[kBatch];
     bool ok[kBatch];
     auto load_round = [&](uint32_t i0) {
@@ -478,7 +478,7 @@ __global__ __launch_bounds__(1024) void k_finish(Src src, SelState st) {
 // equal-key entries precede it in index order; its output slot is the number of selected
 // entries before it.  DIVIDE: value / divisor (Eq. 3).  gbits != NULL: also set bit
 // `index` of that bitmap (the dense gMask of Algorithm 3 lines 21-22, one bit per gradient
-// element).  A block takes 1024 positions per round: their order inside a round is
+// element).  A block takes kBlock * kBatch positions per round: their order inside a round is
 // (sub-step j, wave, lane).
 // The kernel writes nothing that a source reads: in the overflow case other blocks of the
 // set are still reading all of it.
