@@ -314,7 +314,9 @@ int do_local_select(const float* grad, float* residual, int64_t m, int64_t strid
 
     const SamplePlan sp = plan_sample(m, k);
     uint32_t sblocks = ceil_div(sp.n_tiles, (kSampleBlock / kSampleTile) * 8);
-    if (sblocks > 16) sblocks = 16;
+    // about 256 blocks in all: every block flushes its own 16384-bin histogram with atomics
+    const uint32_t sb_max = P >= 64 ? 4u : (P <= 16 ? 16u : 256u / P);
+    if (sblocks > sb_max) sblocks = sb_max;
     if (sblocks < 1) sblocks = 1;
     hipLaunchKernelGGL(k_sample, dim3(sblocks, P), dim3(kSampleBlock), 0, st, grad, residual,
                        (uint32_t)m, stride, sp.tile_stride, sp.n_tiles, w.samp_hist);
