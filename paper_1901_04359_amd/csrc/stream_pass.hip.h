@@ -19,7 +19,7 @@ __global__ __launch_bounds__(kSampleBlock) void k_sample(
     const float* g = grad + (int64_t)w * stride;
     const float* r = res + (int64_t)w * stride;
     const uint32_t sub = threadIdx.x / kSampleTile, el = threadIdx.x % kSampleTile;
-    constexpr int kUnroll = 8;
+    constexpr int kUnroll = 4;
     const uint64_t tiles_per_round = (uint64_t)(kSampleBlock / kSampleTile) * gridDim.x;
     for (uint64_t t0 = (uint64_t)blockIdx.x * (kSampleBlock / kSampleTile) + sub; t0 < n_tiles;
          t0 += tiles_per_round * kUnroll) {
