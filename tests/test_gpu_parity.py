@@ -603,3 +603,41 @@ def test_aggregations_random_shapes(P, m, k, overlap, kind):
     B.gtopk_dense_topk(dense, k, g_idx, g_val, ws)
     oi, ov = orc.dense_topk(exp, k)
     assert np.array_equal(idx_np(g_idx), oi) and bits_equal(val_np(g_val), ov)
+
+
+def test_step_under_graph_capture():
+    """gtopk_step allocates nothing, never synchronises and clears its workspace with a kernel
+    of its own, so a caller may capture it in a HIP graph.  Three replays with eager work and
+    synchronisations in between, each compared with the oracle (residual carried)."""
+    import torch
+    cfg = W.scaled(W.CONFIGS["C2"], 150_001, k=300, P=8, name="graph")
+    P, m, k = cfg.P, cfg.m, cfg.k
+    dev = Device(P, m, k)
+    grads = [W.gradients(cfg, it) for it in range(3)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):            # warm-up outside capture, as torch asks
+        dev.set_grad(grads[0])
+        dev.step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    say("graph capture of gtopk_step")
+    with torch.cuda.graph(graph):
+        dev.B.gtopk_step(dev.grad, dev.res, k, dev.g_idx, dev.g_val, dev.loc_idx, dev.loc_val, dev.ws)
+    res = np.zeros((P, m), dtype=np.float32)
+    dev.set_res(res)
+    for it in range(3):
+        dev.set_grad(grads[it])
+        scratch = torch.rand(1000, device="cuda").sum()      # eager work between the replays
+        torch.cuda.synchronize()
+        say(f"graph replay {it}")
+        graph.replay()
+        torch.cuda.synchronize()
+        exp = orc.step(res, grads[it], k)
+        assert np.array_equal(idx_np(dev.g_idx), exp["g_idx"]), it
+        assert bits_equal(val_np(dev.g_val), exp["g_val"]), it
+        assert np.array_equal(idx_np(dev.loc_idx), exp["loc_idx"]), it
+        assert bits_equal(dev.residual(), exp["residual"]), it
+        res = exp["residual"]
+        assert float(scratch) > 0
