@@ -106,6 +106,7 @@ uint32_t groups_for(uint32_t sets) {
 constexpr uint64_t kInlineFinishMax = 1u << 20;  // sets up to this many slots: no k_finish
 constexpr uint32_t kUnionPathMinK = 65536;      // sets above this size take k_union_path
 constexpr int kUnionPathEpt = 8;
+constexpr int kUnionHistBlock = 1024;           // threads per block of the union that also histograms
 constexpr uint32_t kUnionCutsMinK = 1u << 19;   // sets above this size: cut points in a kernel of their own
 
 struct MergeWs {
@@ -241,7 +242,7 @@ void zero_async(hipStream_t st, uint32_t* p0, size_t n0, uint32_t* p1 = nullptr,
 template <class Src, bool DIVIDE>
 void run_select(const Src& src, const SelState& ss, uint32_t sets, uint32_t groups, uint32_t k,
                 uint64_t nphys_max, uint32_t* out_idx, float* out_val, int64_t out_stride,
-                float divisor, uint32_t* gbits, hipStream_t st) {
+                float divisor, uint32_t* gbits, hipStream_t st, bool with_hist = true) {
     // few blocks per set (a popular bin takes one same-address atomic per block): one batch
     // of 4 slots per thread up to 32 blocks, then more slots per thread, then up to 256 blocks
     uint32_t hb = ceil_div(nphys_max, 4 * kHistBlock);
@@ -249,8 +250,9 @@ void run_select(const Src& src, const SelState& ss, uint32_t sets, uint32_t grou
         hb = ceil_div(nphys_max, 16 * kHistBlock);
         hb = hb < 32 ? 32 : (hb > 256 ? 256 : hb);
     }
-    hipLaunchKernelGGL((k_hist<Src>), dim3(hb + (Src::kRunScan ? 1 : 0), sets), dim3(kHistBlock), 0,
-                       st, src, ss, hb);
+    if (with_hist)
+        hipLaunchKernelGGL((k_hist<Src>), dim3(hb + (Src::kRunScan ? 1 : 0), sets), dim3(kHistBlock), 0,
+                           st, src, ss, hb);
     hipLaunchKernelGGL((k_bucket<Src>), dim3(groups, sets), dim3(kBlock), 0, st, src, ss, k);
     // small sets: every block of the emit finishes the select itself (the list of keys it
     // needs for that is short); large sets: once per set, in a kernel of its own
@@ -358,11 +360,22 @@ void do_merge_batch(const uint32_t* a_idx, const float* a_val, const uint32_t* b
     const bool odd = (round & 1) != 0;
     uint32_t* zp = odd ? w.sel.hist : w.sel_alt.hist;
     const uint32_t zw = (uint32_t)(odd ? select_clear_words(w.sel) : w.alt_clear_words);
-    // small sets: one entry of either operand per thread, many small blocks (latency);
+    // w.L is the smallest group the workspace was sized for; a batch of many pairs takes larger ones
+    uint32_t L = group_slots_for(2ull * k, groups_for(batch));
+    if (L > 4096u) L = 4096u;
+    if (L < w.L) L = w.L;
+    const uint32_t groups = ceil_div(2ull * k, L);
+    MergedSrc src{w.m_idx, w.m_val, 2 * k, w.m_stride, L, in_min, in_min_inverted};
+    SelState ss = odd ? w.sel_alt : w.sel;
+    ss.T_out = out_min;
+    // small sets: one entry of either operand per thread, in blocks as large as the histogram
+    // kernel's, which this kernel then replaces (latency: one launch fewer per round);
     // large sets: cut by output position, a few entries per thread (throughput)
-    if (k <= kUnionPathMinK)
-        hipLaunchKernelGGL(k_union<1>, dim3(ceil_div(k, kBlock), batch), dim3(kBlock), 0, st, a_idx,
-                           a_val, b_idx, b_val, k, in_stride, w.m_idx, w.m_val, w.m_stride, zp, zw);
+    const bool fused_hist = k <= kUnionPathMinK;
+    if (fused_hist)
+        hipLaunchKernelGGL((k_union<1, kUnionHistBlock, true>), dim3(ceil_div(k, kUnionHistBlock), batch),
+                           dim3(kUnionHistBlock), 0, st, a_idx, a_val, b_idx, b_val, k, in_stride, w.m_idx,
+                           w.m_val, w.m_stride, zp, zw, src, ss);
     else if (k <= kUnionCutsMinK)
         hipLaunchKernelGGL((k_union_path<kUnionPathEpt, false>),
                            dim3(ceil_div(2 * k, kBlock * kUnionPathEpt), batch), dim3(kBlock), 0, st,
@@ -376,16 +389,8 @@ void do_merge_batch(const uint32_t* a_idx, const float* a_val, const uint32_t* b
                            a_idx, a_val, b_idx, b_val, k, in_stride, w.m_idx, w.m_val, w.m_stride,
                            (const uint32_t*)w.cuts, zp, zw);
     }
-    // w.L is the smallest group the workspace was sized for; a batch of many pairs takes larger ones
-    uint32_t L = group_slots_for(2ull * k, groups_for(batch));
-    if (L > 4096u) L = 4096u;
-    if (L < w.L) L = w.L;
-    const uint32_t groups = ceil_div(2ull * k, L);
-    MergedSrc src{w.m_idx, w.m_val, 2 * k, w.m_stride, L, in_min, in_min_inverted};
-    SelState ss = odd ? w.sel_alt : w.sel;
-    ss.T_out = out_min;
     run_select<MergedSrc, DIVIDE>(src, ss, batch, groups, k, 2ull * k, out_idx, out_val, out_stride,
-                                  divisor, gbits, st);
+                                  divisor, gbits, st, !fused_hist);
 }
 
 // loc_min: the smallest key of each of the P input sets (the local selection's T), or NULL

@@ -49,22 +49,26 @@ __device__ inline uint32_t wave_count_below(const uint32_t* __restrict__ a, uint
 // searches over more entries (large k).
 // On the side, the grid clears zero_words words at zero_ptr: the select state that the
 // NEXT round of the tree will use (this round's is in use, the other one is free).
-template <int EPT>
-__global__ __launch_bounds__(kBlock) void k_union(
+template <int EPT, int BLOCK, bool HIST>
+__global__ __launch_bounds__(BLOCK) void k_union(
         const uint32_t* __restrict__ a_idx, const float* __restrict__ a_val,
         const uint32_t* __restrict__ b_idx, const float* __restrict__ b_val, uint32_t k,
         int64_t in_stride, uint32_t* __restrict__ m_idx, float* __restrict__ m_val,
-        uint32_t m_stride, uint32_t* __restrict__ zero_ptr, uint32_t zero_words) {
+        uint32_t m_stride, uint32_t* __restrict__ zero_ptr, uint32_t zero_words, MergedSrc hsrc,
+        SelState hst) {
     __shared__ uint32_t s_bound[4];
+    __shared__ uint32_t s_hist[HIST ? kHistBins : 1];
     const int s = blockIdx.y;
+    if (HIST)
+        for (int b = threadIdx.x; b < kHistBins; b += BLOCK) s_hist[b] = 0u;   // barriers follow
     {
-        const uint32_t nthreads = gridDim.x * gridDim.y * kBlock;
-        for (uint32_t i = (blockIdx.y * gridDim.x + blockIdx.x) * kBlock + threadIdx.x; i < zero_words;
+        const uint32_t nthreads = gridDim.x * gridDim.y * BLOCK;
+        for (uint32_t i = (blockIdx.y * gridDim.x + blockIdx.x) * BLOCK + threadIdx.x; i < zero_words;
              i += nthreads)
             zero_ptr[i] = 0u;
     }
-    const uint32_t x0 = blockIdx.x * (kBlock * EPT);            // < k by the launch grid
-    const uint32_t x1 = x0 + kBlock * EPT - 1 < k ? x0 + kBlock * EPT - 1 : k - 1;
+    const uint32_t x0 = blockIdx.x * (BLOCK * EPT);            // < k by the launch grid
+    const uint32_t x1 = x0 + BLOCK * EPT - 1 < k ? x0 + BLOCK * EPT - 1 : k - 1;
     const uint32_t* ai = a_idx + (int64_t)s * in_stride;
     const float* av = a_val + (int64_t)s * in_stride;
     const uint32_t* bi = b_idx + (int64_t)s * in_stride;
@@ -77,26 +81,26 @@ __global__ __launch_bounds__(kBlock) void k_union(
     float fa[EPT], fb[EPT];
 #pragma unroll
     for (int j = 0; j < EPT; ++j) {
-        const uint32_t x = x0 + j * kBlock + threadIdx.x;
+        const uint32_t x = x0 + j * BLOCK + threadIdx.x;
         const bool live = x < k;
         ia[j] = live ? ai[x] : 0u;
         ib[j] = live ? bi[x] : 0u;
         fa[j] = live ? av[x] : 0.0f;
         fb[j] = live ? bv[x] : 0.0f;
     }
-    uint32_t bound;
+    uint32_t bound = 0;
     if (wave == 0) bound = wave_count_below<false>(bi, k, ai[x0]);
     else if (wave == 1) bound = wave_count_below<false>(bi, k, ai[x1]);
     else if (wave == 2) bound = wave_count_below<true>(ai, k, bi[x0]);
-    else bound = wave_count_below<true>(ai, k, bi[x1]);
-    if (lane_id() == 0) s_bound[wave] = bound;
+    else if (wave == 3) bound = wave_count_below<true>(ai, k, bi[x1]);
+    if (lane_id() == 0 && wave < 4) s_bound[wave] = bound;
     __syncthreads();
     // pa = #{B < ia} lies in [b_lo, b_hi], pb = #{A <= ib} in [a_lo, a_hi].  The searches
     // read bi[b_lo .. b_hi-1]; the match test reads bi/bv[pa] (pa <= b_hi) and the duplicate
     // test ai[pb-1] (pb-1 >= a_lo-1).  When those ranges fit, they are staged in LDS with
     // coalesced loads and searched there; otherwise the same code reads global memory.
     const uint32_t b_lo = s_bound[0], b_hi = s_bound[1], a_lo = s_bound[2], a_hi = s_bound[3];
-    constexpr uint32_t kCap = 2u * kBlock * EPT + 2u;
+    constexpr uint32_t kCap = 2u * BLOCK * EPT + 2u;
     __shared__ uint32_t s_bi[kCap];
     __shared__ float s_bv[kCap];
     __shared__ uint32_t s_ai[kCap];
@@ -106,19 +110,19 @@ __global__ __launch_bounds__(kBlock) void k_union(
     const bool staged = b_n <= kCap && a_n <= kCap;               // block-uniform
     if (staged) {
         // all loads first, then the LDS stores: one memory round trip for the whole stage
-        constexpr int kRounds = (int)((kCap + kBlock - 1) / kBlock);
+        constexpr int kRounds = (int)((kCap + BLOCK - 1) / BLOCK);
         uint32_t tb[kRounds], ta[kRounds];
         float tv[kRounds];
 #pragma unroll
         for (int r = 0; r < kRounds; ++r) {
-            const uint32_t i = r * kBlock + threadIdx.x;
+            const uint32_t i = r * BLOCK + threadIdx.x;
             tb[r] = i < b_n ? bi[b_lo + i] : 0u;
             tv[r] = i < b_n ? bv[b_lo + i] : 0.0f;
             ta[r] = i < a_n ? ai[a_first + i] : 0u;
         }
 #pragma unroll
         for (int r = 0; r < kRounds; ++r) {
-            const uint32_t i = r * kBlock + threadIdx.x;
+            const uint32_t i = r * BLOCK + threadIdx.x;
             if (i < b_n) { s_bi[i] = tb[r]; s_bv[i] = tv[r]; }
             if (i < a_n) s_ai[i] = ta[r];
         }
@@ -152,7 +156,7 @@ __global__ __launch_bounds__(kBlock) void k_union(
     }
 #pragma unroll
     for (int j = 0; j < EPT; ++j) {
-        const uint32_t x = x0 + j * kBlock + threadIdx.x;
+        const uint32_t x = x0 + j * BLOCK + threadIdx.x;
         if (x >= k) continue;
         float sum = fa[j];
         if (pa[j] < k && B_idx(pa[j]) == ia[j]) sum = sum + B_val(pa[j]);
@@ -161,6 +165,21 @@ __global__ __launch_bounds__(kBlock) void k_union(
         const bool dup = pb[j] > 0 && A_idx(pb[j] - 1) == ib[j];
         mi[x + pb[j]] = dup ? kTomb : ib[j];
         mv[x + pb[j]] = fb[j];
+        if (HIST) {
+            // the first digit of the keys this block has just produced (what k_hist would
+            // read back): LDS counts now, one global add per bin and block below
+            const Digit dg = hsrc.digit(s, false, hst);
+            atomicAdd(&s_hist[dg.bin(__float_as_uint(sum) & kAbs)], 1u);
+            if (!dup) atomicAdd(&s_hist[dg.bin(__float_as_uint(fb[j]) & kAbs)], 1u);
+        }
+    }
+    if (HIST) {
+        __syncthreads();
+        uint32_t* out = hst.hist + (size_t)s * kHistBins;
+        for (int b = threadIdx.x; b < kHistBins; b += BLOCK) {
+            const uint32_t c = s_hist[b];
+            if (c) atomicAdd(&out[b], c);
+        }
     }
 }
 
