@@ -42,11 +42,10 @@ __device__ inline uint32_t wave_count_below(const uint32_t* __restrict__ a, uint
 // a bijection onto [0, 2k) that lists the union in index order, A's copy first
 // where both hold an index.  A's copy then carries the sum (one fp32 add) and B's
 // slot becomes a tombstone.
-// A block takes 256*EPT consecutive entries of A and of B.  Its four waves first find,
-// each with one 64-ary search, the counts for the block's first and last entry of
+// A block takes BLOCK*EPT consecutive entries of A and of B.  Four of its waves first
+// find, each with one 64-ary search, the counts for the block's first and last entry of
 // either side; every thread then searches only between those two counts, a short range
-// that the block's threads share in cache.  EPT > 1 spreads the cost of the boundary
-// searches over more entries (large k).
+// that is staged in LDS.
 // On the side, the grid clears zero_words words at zero_ptr: the select state that the
 // NEXT round of the tree will use (this round's is in use, the other one is free).
 template <int EPT, int BLOCK, bool HIST>
