@@ -48,6 +48,9 @@ __device__ inline uint32_t wave_count_below(const uint32_t* __restrict__ a, uint
 // that is staged in LDS.
 // On the side, the grid clears zero_words words at zero_ptr: the select state that the
 // NEXT round of the tree will use (this round's is in use, the other one is free).
+// HIST: the block also counts the first digits of the keys it produces, which saves the
+// select's histogram kernel; blocks are large then (BLOCK = 1024), as k_hist's are, so that
+// a popular bin costs few global atomics.
 template <int EPT, int BLOCK, bool HIST>
 __global__ __launch_bounds__(BLOCK) void k_union(
         const uint32_t* __restrict__ a_idx, const float* __restrict__ a_val,
