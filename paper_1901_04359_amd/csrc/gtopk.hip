@@ -96,8 +96,8 @@ uint32_t group_slots_for(uint64_t n, uint32_t max_groups) {
 
 // Groups per set when `sets` sets are selected from side by side.  Every block of k_bucket
 // and k_emit pays a fixed price (it reads the set's 4096-bin histogram, or the list of
-// in-bin keys), so a batch gets about kTargetBlocks blocks in total and no more.
-constexpr uint32_t kTargetBlocks = 4096;
+// in-bin keys), so a batch gets about kTargetBlocks blocks in total and no more (swept: 512 .. 4096).
+constexpr uint32_t kTargetBlocks = 1024;
 uint32_t groups_for(uint32_t sets) {
     const uint32_t g = kTargetBlocks / (sets ? sets : 1);
     return g < 32 ? 32 : (g > (uint32_t)kMaxGroups ? (uint32_t)kMaxGroups : g);
@@ -362,7 +362,7 @@ void do_merge_batch(const uint32_t* a_idx, const float* a_val, const uint32_t* b
     const uint32_t zw = (uint32_t)(odd ? select_clear_words(w.sel) : w.alt_clear_words);
     // w.L is the smallest group the workspace was sized for; a batch of many pairs takes larger ones
     uint32_t L = group_slots_for(2ull * k, groups_for(batch));
-    if (L > 4096u) L = 4096u;
+    if (L > 8192u) L = 8192u;
     if (L < w.L) L = w.L;
     const uint32_t groups = ceil_div(2ull * k, L);
     MergedSrc src{w.m_idx, w.m_val, 2 * k, w.m_stride, L, in_min, in_min_inverted};
