@@ -98,6 +98,7 @@ uint32_t group_slots_for(uint64_t n, uint32_t max_groups) {
 // and k_emit pays a fixed price (it reads the set's 4096-bin histogram, or the list of
 // in-bin keys), so a batch gets about kTargetBlocks blocks in total and no more (swept: 512 .. 4096).
 constexpr uint32_t kTargetBlocks = 1024;
+constexpr uint32_t kLocalTargetBlocks = 8192;   // the same for the local selection's P sets
 uint32_t groups_for(uint32_t sets) {
     const uint32_t g = kTargetBlocks / (sets ? sets : 1);
     return g < 32 ? 32 : (g > (uint32_t)kMaxGroups ? (uint32_t)kMaxGroups : g);
@@ -179,7 +180,13 @@ StepWs carve_step(void* ws, int64_t m, uint32_t k, uint32_t P) {
     StepWs s;
     s.cap = cand_capacity(m, k);
     s.nchunks = ceil_div((uint64_t)m + 3, kChunk);      // a row may start up to 3 elements into a chunk
-    s.Lc = group_slots_for(s.cap, kMaxGroups);
+    {
+        uint32_t g = kLocalTargetBlocks / P;
+        g = g < 32 ? 32 : (g > (uint32_t)kMaxGroups ? (uint32_t)kMaxGroups : g);
+        s.Lc = group_slots_for(s.cap, g);
+        const uint32_t lmin = group_slots_for(s.cap, kMaxGroups);
+        if (s.Lc > 8192u) s.Lc = lmin > 8192u ? lmin : 8192u;
+    }
     const uint32_t gcand = ceil_div(s.cap, s.Lc);
     // dense rows are a fallback when there are several workers: coarse groups keep the
     // grids small; with one set (also the dense top-k) they get as many groups as any set
