@@ -250,11 +250,12 @@ template <class Src, bool DIVIDE>
 void run_select(const Src& src, const SelState& ss, uint32_t sets, uint32_t groups, uint32_t k,
                 uint64_t nphys_max, uint32_t* out_idx, float* out_val, int64_t out_stride,
                 float divisor, uint32_t* gbits, hipStream_t st, bool with_hist = true) {
-    // few blocks per set (a popular bin takes one same-address atomic per block): one batch
-    // of 4 slots per thread up to 32 blocks, then more slots per thread, then up to 256 blocks
+    // few blocks per set (a popular bin takes one same-address atomic per block): 4 slots per
+    // thread up to 32 blocks, then 32 blocks with more slots per thread, then 32 slots per
+    // thread up to 256 blocks (swept at k = 255,570 .. 6.4 M)
     uint32_t hb = ceil_div(nphys_max, 4 * kHistBlock);
     if (hb > 32) {
-        hb = ceil_div(nphys_max, 16 * kHistBlock);
+        hb = ceil_div(nphys_max, 32 * kHistBlock);
         hb = hb < 32 ? 32 : (hb > 256 ? 256 : hb);
     }
     if (with_hist)
