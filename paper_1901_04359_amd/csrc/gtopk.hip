@@ -105,7 +105,7 @@ uint32_t groups_for(uint32_t sets) {
 }
 
 constexpr uint64_t kInlineFinishMax = 1u << 20;  // sets up to this many slots: no k_finish
-constexpr uint32_t kUnionPathMinK = 65536;      // sets above this size take k_union_path
+constexpr uint32_t kUnionPathMinK = 131072;      // sets above this size take k_union_path
 constexpr int kUnionPathEpt = 8;
 constexpr int kUnionHistBlock = 1024;           // threads per block of the union that also histograms
 constexpr uint32_t kUnionCutsMinK = 1u << 19;   // sets above this size: cut points in a kernel of their own
