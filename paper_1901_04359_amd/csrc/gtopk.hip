@@ -136,7 +136,7 @@ MergeWs carve_merge(Carver& c, uint32_t k, size_t pairs) {
     w.tmin[1] = c.take<uint32_t>(pairs);
     w.inv_min = c.take<uint32_t>(2 * pairs);
     w.cuts = c.take<uint32_t>(k > kUnionCutsMinK
-                                  ? pairs * ((size_t)ceil_div(2ull * k, kBlock * kUnionPathEpt) + 1)
+                                  ? pairs * ((size_t)ceil_div(2ull * k, kUnionHistBlock * kUnionPathEpt) + 1)
                                   : 0);
     w.bytes = c.off;
     return w;
@@ -376,29 +376,30 @@ void do_merge_batch(const uint32_t* a_idx, const float* a_val, const uint32_t* b
     MergedSrc src{w.m_idx, w.m_val, 2 * k, w.m_stride, L, in_min, in_min_inverted};
     SelState ss = odd ? w.sel_alt : w.sel;
     ss.T_out = out_min;
-    // small sets: one entry of either operand per thread, in blocks as large as the histogram
-    // kernel's, which this kernel then replaces (latency: one launch fewer per round);
-    // large sets: cut by output position, a few entries per thread (throughput)
-    const bool fused_hist = k <= kUnionPathMinK;
-    if (fused_hist)
+    // The union runs in blocks as large as the histogram kernel's and counts the first digits
+    // of the keys it produces, so the select below starts at its second kernel.
+    // small sets: one entry of either operand per thread (latency);
+    // large sets: cut by output position, eight slots per thread (throughput); for the
+    // largest the blocks' cut points come from a kernel of their own
+    if (k <= kUnionPathMinK)
         hipLaunchKernelGGL((k_union<1, kUnionHistBlock, true>), dim3(ceil_div(k, kUnionHistBlock), batch),
                            dim3(kUnionHistBlock), 0, st, a_idx, a_val, b_idx, b_val, k, in_stride, w.m_idx,
                            w.m_val, w.m_stride, zp, zw, src, ss);
     else if (k <= kUnionCutsMinK)
-        hipLaunchKernelGGL((k_union_path<kUnionPathEpt, false>),
-                           dim3(ceil_div(2 * k, kBlock * kUnionPathEpt), batch), dim3(kBlock), 0, st,
-                           a_idx, a_val, b_idx, b_val, k, in_stride, w.m_idx, w.m_val, w.m_stride,
-                           (const uint32_t*)nullptr, zp, zw);
+        hipLaunchKernelGGL((k_union_path<kUnionPathEpt, false, kUnionHistBlock, true>),
+                           dim3(ceil_div(2 * k, kUnionHistBlock * kUnionPathEpt), batch),
+                           dim3(kUnionHistBlock), 0, st, a_idx, a_val, b_idx, b_val, k, in_stride, w.m_idx,
+                           w.m_val, w.m_stride, (const uint32_t*)nullptr, zp, zw, src, ss);
     else {
-        const uint32_t tile = kBlock * kUnionPathEpt, ntiles = ceil_div(2 * k, tile);
+        const uint32_t tile = kUnionHistBlock * kUnionPathEpt, ntiles = ceil_div(2 * k, tile);
         hipLaunchKernelGGL(k_union_cuts, dim3(ceil_div(ntiles + 1, kBlock), batch), dim3(kBlock), 0, st,
                            a_idx, b_idx, k, in_stride, tile, ntiles, w.cuts);
-        hipLaunchKernelGGL((k_union_path<kUnionPathEpt, true>), dim3(ntiles, batch), dim3(kBlock), 0, st,
-                           a_idx, a_val, b_idx, b_val, k, in_stride, w.m_idx, w.m_val, w.m_stride,
-                           (const uint32_t*)w.cuts, zp, zw);
+        hipLaunchKernelGGL((k_union_path<kUnionPathEpt, true, kUnionHistBlock, true>), dim3(ntiles, batch),
+                           dim3(kUnionHistBlock), 0, st, a_idx, a_val, b_idx, b_val, k, in_stride, w.m_idx,
+                           w.m_val, w.m_stride, (const uint32_t*)w.cuts, zp, zw, src, ss);
     }
     run_select<MergedSrc, DIVIDE>(src, ss, batch, groups, k, 2ull * k, out_idx, out_val, out_stride,
-                                  divisor, gbits, st, !fused_hist);
+                                  divisor, gbits, st, /*with_hist=*/false);
 }
 
 // loc_min: the smallest key of each of the P input sets (the local selection's T), or NULL

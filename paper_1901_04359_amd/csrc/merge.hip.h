@@ -219,7 +219,7 @@ __device__ inline uint32_t wave_first_false(uint32_t lo, uint32_t hi, Pred pred)
 // LDS; every thread then finds the start of its own EPT slots with a binary search in LDS
 // and merges EPT steps sequentially.  Rows of m_idx / m_val are m_stride apart (a multiple
 // of EPT, 16-byte aligned), so every thread stores whole vectors; slots past 2k in the
-// row's padding become tombstones.
+// row's padding become tombstones.  HIST: as in k_union, with blocks as large as LDS allows.
 // cuts[s][c] = number of A entries among the first c * tile slots of pair s (c = 0 .. ntiles;
 // the last one is clamped to 2k slots): what k_union_path's blocks need, one binary
 // search along a diagonal each, all side by side instead of one after the other in
@@ -242,25 +242,28 @@ __global__ __launch_bounds__(kBlock) void k_union_cuts(
     cuts[(size_t)s * (ntiles + 1) + c] = lo;
 }
 
-template <int EPT, bool CUTS>
-__global__ __launch_bounds__(kBlock) void k_union_path(
+template <int EPT, bool CUTS, int BLOCK, bool HIST>
+__global__ __launch_bounds__(BLOCK) void k_union_path(
         const uint32_t* __restrict__ a_idx, const float* __restrict__ a_val,
         const uint32_t* __restrict__ b_idx, const float* __restrict__ b_val, uint32_t k,
         int64_t in_stride, uint32_t* __restrict__ m_idx, float* __restrict__ m_val,
         uint32_t m_stride, const uint32_t* __restrict__ cuts, uint32_t* __restrict__ zero_ptr,
-        uint32_t zero_words) {
+        uint32_t zero_words, MergedSrc hsrc, SelState hst) {
     static_assert(EPT % 4 == 0, "whole 16-byte vectors per thread");
-    constexpr uint32_t kTile = kBlock * EPT;
+    constexpr uint32_t kTile = BLOCK * EPT;
     constexpr uint32_t kStage = kTile + 3;         // A: previous + entries + sentinel; B: entries + next
     // EPT spare slots: with operands that are not sorted (unspecified results) a thread's
     // merge may run up to EPT entries past either staged range; it must stay inside LDS
     __shared__ uint32_t s_i[kStage + EPT];
     __shared__ float s_v[kStage + EPT];
     __shared__ uint32_t s_split[2];
+    __shared__ uint32_t s_hist[HIST ? kHistBins : 1];
     const int s = blockIdx.y;
+    if (HIST)
+        for (int b = threadIdx.x; b < kHistBins; b += BLOCK) s_hist[b] = 0u;   // barriers follow
     {
-        const uint32_t nthreads = gridDim.x * gridDim.y * kBlock;
-        for (uint32_t i = (blockIdx.y * gridDim.x + blockIdx.x) * kBlock + threadIdx.x; i < zero_words;
+        const uint32_t nthreads = gridDim.x * gridDim.y * BLOCK;
+        for (uint32_t i = (blockIdx.y * gridDim.x + blockIdx.x) * BLOCK + threadIdx.x; i < zero_words;
              i += nthreads)
             zero_ptr[i] = 0u;
     }
@@ -297,12 +300,12 @@ __global__ __launch_bounds__(kBlock) void k_union_path(
     // stage: s[0] = A[xa0-1] (or none), s[1 .. na] = A entries, s[na+1] = none (sentinel: above
     // every index); s[na+2 .. na+1+nb] = B entries, s[na+2+nb] = B[yb1] (or none)
     {
-        constexpr int kRounds = (int)((kStage + kBlock - 1) / kBlock);
+        constexpr int kRounds = (int)((kStage + BLOCK - 1) / BLOCK);
         uint32_t ti[kRounds];
         float tv[kRounds];
 #pragma unroll
         for (int r = 0; r < kRounds; ++r) {
-            const uint32_t c = r * kBlock + threadIdx.x;
+            const uint32_t c = r * BLOCK + threadIdx.x;
             ti[r] = kTomb;
             tv[r] = 0.0f;
             if (c < na + 1) {
@@ -314,7 +317,7 @@ __global__ __launch_bounds__(kBlock) void k_union_path(
         }
 #pragma unroll
         for (int r = 0; r < kRounds; ++r) {
-            const uint32_t c = r * kBlock + threadIdx.x;
+            const uint32_t c = r * BLOCK + threadIdx.x;
             if (c < kStage) { s_i[c] = ti[r]; s_v[c] = tv[r]; }
         }
     }
@@ -324,47 +327,63 @@ __global__ __launch_bounds__(kBlock) void k_union_path(
     const float* sav = s_v + 1;
     const float* sbv = s_v + na + 2;
     const uint32_t d = threadIdx.x * EPT;          // first slot of this thread, relative to p0
-    if (d >= nout) return;                         // nout is a multiple of EPT except in the last block
-    // A entries among the tile's first d slots
-    uint32_t x = d > nb ? d - nb : 0u;
-    {
-        uint32_t hi = d < na ? d : na;
-        while (x < hi) {
-            const uint32_t mid = (x + hi) >> 1;
-            if (sa[mid] <= sb[d - 1 - mid]) x = mid + 1; else hi = mid;
+    if (d < nout) {                                // nout is a multiple of EPT except in the last block
+        // A entries among the tile's first d slots
+        uint32_t x = d > nb ? d - nb : 0u;
+        {
+            uint32_t hi = d < na ? d : na;
+            while (x < hi) {
+                const uint32_t mid = (x + hi) >> 1;
+                if (sa[mid] <= sb[d - 1 - mid]) x = mid + 1; else hi = mid;
+            }
+        }
+        uint32_t y = d - x;
+        uint32_t oi[EPT];
+        float ov[EPT];
+        uint32_t a = sa[x], b = sb[y];
+        uint32_t aprev = sa[(int)x - 1];
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) {
+            if (d + j >= nout) {                   // padding of the row
+                oi[j] = kTomb;
+                ov[j] = 0.0f;
+            } else if (a <= b) {
+                float v = sav[x];
+                if (b == a) v = v + sbv[y];
+                oi[j] = a;
+                ov[j] = v;
+                aprev = a;
+                ++x;
+                a = sa[x];
+            } else {
+                oi[j] = b == aprev ? kTomb : b;
+                ov[j] = sbv[y];
+                ++y;
+                b = sb[y];
+            }
+        }
+        uint32_t* mi = m_idx + (size_t)s * m_stride + p0 + d;
+        float* mv = m_val + (size_t)s * m_stride + p0 + d;
+#pragma unroll
+        for (int j = 0; j < EPT; j += 4) {
+            *reinterpret_cast<uint4*>(mi + j) = make_uint4(oi[j], oi[j + 1], oi[j + 2], oi[j + 3]);
+            *reinterpret_cast<float4*>(mv + j) = make_float4(ov[j], ov[j + 1], ov[j + 2], ov[j + 3]);
+        }
+        if (HIST) {
+            // first digits of the keys just produced: what k_hist would read back
+            const Digit dg = hsrc.digit(s, false, hst);
+#pragma unroll
+            for (int j = 0; j < EPT; ++j)
+                if (oi[j] != kTomb) atomicAdd(&s_hist[dg.bin(__float_as_uint(ov[j]) & kAbs)], 1u);
         }
     }
-    uint32_t y = d - x;
-    uint32_t oi[EPT];
-    float ov[EPT];
-    uint32_t a = sa[x], b = sb[y];
-    uint32_t aprev = sa[(int)x - 1];
-#pragma unroll
-    for (int j = 0; j < EPT; ++j) {
-        if (d + j >= nout) {                       // padding of the row
-            oi[j] = kTomb;
-            ov[j] = 0.0f;
-        } else if (a <= b) {
-            float v = sav[x];
-            if (b == a) v = v + sbv[y];
-            oi[j] = a;
-            ov[j] = v;
-            aprev = a;
-            ++x;
-            a = sa[x];
-        } else {
-            oi[j] = b == aprev ? kTomb : b;
-            ov[j] = sbv[y];
-            ++y;
-            b = sb[y];
+    if (HIST) {
+        __syncthreads();
+        uint32_t* out = hst.hist + (size_t)s * kHistBins;
+        for (int b = threadIdx.x; b < kHistBins; b += BLOCK) {
+            const uint32_t c = s_hist[b];
+            if (c) atomicAdd(&out[b], c);
         }
-    }
-    uint32_t* mi = m_idx + (size_t)s * m_stride + p0 + d;
-    float* mv = m_val + (size_t)s * m_stride + p0 + d;
-#pragma unroll
-    for (int j = 0; j < EPT; j += 4) {
-        *reinterpret_cast<uint4*>(mi + j) = make_uint4(oi[j], oi[j + 1], oi[j + 2], oi[j + 3]);
-        *reinterpret_cast<float4*>(mv + j) = make_float4(ov[j], ov[j + 1], ov[j + 2], ov[j + 3]);
     }
 }
 
