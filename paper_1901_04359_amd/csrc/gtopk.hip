@@ -53,11 +53,13 @@ struct Carver {
 };
 
 // hist, list_cnt and grp_gt are carved back to back so that one clear covers them
-SelState carve_select(Carver& c, size_t sets, uint32_t list_cap, uint32_t maxgroups) {
+SelState carve_select(Carver& c, size_t sets, uint32_t list_cap, uint32_t maxgroups,
+                      bool with_dense_hist = false) {
     SelState s;
     s.hist = c.take<uint32_t>(sets * kHistBins);
     s.list_cnt = c.take<uint32_t>(sets);
     s.grp_gt = c.take<uint32_t>(sets * maxgroups);
+    s.hist_dense = with_dense_hist ? c.take<uint32_t>(sets * kHistBins) : nullptr;   // cleared as well
     s.d1 = c.take<uint32_t>(sets);
     s.krem = c.take<uint32_t>(sets);
     s.T = c.take<uint32_t>(sets);
@@ -70,7 +72,7 @@ SelState carve_select(Carver& c, size_t sets, uint32_t list_cap, uint32_t maxgro
     s.maxgroups = maxgroups;
     return s;
 }
-// words from s.hist to the end of s.grp_gt (padding included)
+// words from s.hist to the end of s.grp_gt / s.hist_dense (padding included)
 inline size_t select_clear_words(const SelState& s) { return (size_t)(s.d1 - s.hist); }
 
 // A second copy of the three arrays that must be zero when a select starts; everything
@@ -202,7 +204,7 @@ StepWs carve_step(void* ws, int64_t m, uint32_t k, uint32_t P) {
     s.ord_idx = c.take<uint32_t>((size_t)P * s.cap);
     s.ord_val = c.take<float>((size_t)P * s.cap);
     const uint32_t gc = ceil_div(s.cap, s.Lc), gd = ceil_div((uint64_t)m, s.Ld);
-    s.sel = carve_select(c, P, s.cap, gc > gd ? gc : gd);
+    s.sel = carve_select(c, P, s.cap, gc > gd ? gc : gd, /*with_dense_hist=*/true);
     const size_t pairs = P > 1 ? P / 2 : 1;
     s.mrg = carve_merge(c, k, pairs);
     s.x_idx = c.take<uint32_t>(pairs * k);
@@ -334,14 +336,28 @@ int do_local_select(const float* grad, float* residual, int64_t m, int64_t strid
                        w.tspec);
     mark_stage(1, armed, st);
 
-    hipLaunchKernelGGL(k_accum_filter, dim3(w.nchunks, P), dim3(kSBlock), 0, st, grad, residual,
-                       (uint32_t)m, stride, w.tspec, w.cand_idx, w.cand_val, w.cap, w.cand_count,
-                       w.run_table, w.nchunks);
+    // The pass can also histogram the candidates it keeps; the select's own histogram kernel
+    // then only serves workers that fall back to their dense row.  That costs LDS atomics and,
+    // per block and non-empty bin, a global atomic in the pass.  Measured against the
+    // histogram kernel it saves: at rho = 0.001 (45 candidates per 32768-element block) the
+    // pass does not change and the select gains 6-8 us; at rho = 0.01 (460 per block) the pass
+    // loses 55 us and the select gains 13 us; at rho = 0.25 (11,500 per block) the pass loses
+    // 80 us and the select gains 230 us.  So at both ends, not in between.
+    const double per_block = 1.4 * (double)k * (double)kChunk / (double)m;
+    const bool producer_hist = per_block <= 128.0 || per_block >= 4096.0;
+    if (producer_hist)
+        hipLaunchKernelGGL(k_accum_filter<true>, dim3(w.nchunks, P), dim3(kSBlock), 0, st, grad,
+                           residual, (uint32_t)m, stride, w.tspec, w.cand_idx, w.cand_val, w.cap,
+                           w.cand_count, w.run_table, w.nchunks, w.sel.hist);
+    else
+        hipLaunchKernelGGL(k_accum_filter<false>, dim3(w.nchunks, P), dim3(kSBlock), 0, st, grad,
+                           residual, (uint32_t)m, stride, w.tspec, w.cand_idx, w.cand_val, w.cap,
+                           w.cand_count, w.run_table, w.nchunks, w.sel.hist);
     mark_stage(2, armed, st);
 
     CandSrc src{residual, stride, (uint32_t)m, k, w.cap, w.nchunks, w.Lc, w.Ld,
                 w.cand_idx, w.cand_val, w.cand_count, w.tspec, w.run_table, w.run_off,
-                w.ord_idx, w.ord_val};
+                w.ord_idx, w.ord_val, producer_hist};
     run_select<CandSrc, false>(src, w.sel, P, w.sel.maxgroups, k, w.cap, out_idx, out_val, (int64_t)k,
                                1.0f, nullptr, st);
     // a kernel of its own: while the select runs, a dense row may still be read as a whole
@@ -642,7 +658,7 @@ int gtopk_dense_topk(const float* dense, int64_t m, int32_t k, uint32_t* g_idx, 
                select_clear_words(w.sel));
     CandSrc src{dense, m, (uint32_t)m, (uint32_t)k, w.cap, w.nchunks, w.Lc, w.Ld,
                 w.cand_idx, w.cand_val, w.cand_count, w.tspec, w.run_table, w.run_off,
-                w.ord_idx, w.ord_val};
+                w.ord_idx, w.ord_val, false};
     run_select<CandSrc, false>(src, w.sel, 1, w.sel.maxgroups, (uint32_t)k, (uint64_t)m, g_idx, g_val,
                                (int64_t)k, 1.0f, nullptr, st);
     return launch_status();

@@ -25,6 +25,8 @@ struct SelState {
     uint32_t* hist;       // [sets][4096]
     uint32_t* list_cnt;   // [sets]
     uint32_t* grp_gt;     // [sets][maxgroups] entries of the group above bin d1
+    uint32_t* hist_dense; // [sets][4096] or NULL: the histogram of a set that is read as a dense
+                          //   row although the producer of its candidates has already filled `hist`
     // --------------------------------------------------------------------------------
     uint32_t* d1;         // [sets] bin of the k-th key
     uint32_t* krem;       // [sets] rank of the k-th key inside bin d1 (1-based, from the top)
@@ -62,6 +64,7 @@ struct CandSrc {
     uint32_t* run_off;                    // [P][nchunks] first logical position of the run
     uint32_t* ord_idx;                    // [P][cap] candidates in index order
     float* ord_val;
+    bool producer_hist;                   // the streaming pass has histogrammed the candidates
 
     __device__ bool dense(int s) const {
         const uint32_t c = cand_count[s];
@@ -138,6 +141,7 @@ struct MergedSrc {
     uint32_t n, stride, L;       // L slots per group
     const uint32_t* in_min;
     bool inverted;
+    static constexpr bool producer_hist = false;
     __device__ bool dense(int) const { return false; }
     __device__ uint32_t nphys(int, bool) const { return n; }
     __device__ uint32_t group_slots(bool) const { return L; }
@@ -179,9 +183,10 @@ __global__ __launch_bounds__(kHistBlock) void k_hist(Src src, SelState st, uint3
         src.scan_runs(s, s_wave);
         return;
     }
+    const bool dn = src.dense(s);
+    if (src.producer_hist && !dn) return;        // block-uniform: this set's histogram exists already
     for (int b = threadIdx.x; b < kHistBins; b += kHistBlock) h[b] = 0u;
     __syncthreads();
-    const bool dn = src.dense(s);
     const uint32_t n = src.nphys(s, dn);
     const Digit dg = src.digit(s, dn, st);
     const uint64_t step = (uint64_t)hist_blocks * kHistBlock;
@@ -209,7 +214,7 @@ __global__ __launch_bounds__(kHistBlock) void k_hist(Src src, SelState st, uint3
         }
     }
     __syncthreads();
-    uint32_t* out = st.hist + (size_t)s * kHistBins;
+    uint32_t* out = (src.producer_hist ? st.hist_dense : st.hist) + (size_t)s * kHistBins;
     for (int b = threadIdx.x; b < kHistBins; b += kHistBlock) {
         const uint32_t c = h[b];
         if (c) atomicAdd(&out[b], c);
@@ -262,7 +267,7 @@ __global__ __launch_bounds__(kBlock) void k_bucket(Src src, SelState st, uint32_
     // every block picks the bin of the k-th key from the set's histogram
     {
         constexpr int kPer = kHistBins / kBlock;      // thread t owns 16 consecutive bins
-        const uint32_t* hist = st.hist + (size_t)s * kHistBins;
+        const uint32_t* hist = ((src.producer_hist && dn) ? st.hist_dense : st.hist) + (size_t)s * kHistBins;
         uint32_t loc[kPer];
 #pragma unroll
         for (int j = 0; j < kPer; ++j) loc[j] = hist[threadIdx.x * kPer + j];

@@ -79,14 +79,23 @@ __global__ __launch_bounds__(kSampleBlock) void k_sample_pick(
 // candidate list; phase 2 writes the block's candidates there in index order.
 // Blocks reserve in any order, nobody waits for anybody; run_table[w][chunk] =
 // (first slot, count) lets the select put the runs back into index order.
+// HIST: the block also adds the first digits of its candidates to the worker's histogram
+// (what the select's histogram kernel would read back), through an LDS histogram: one
+// global atomic per non-empty bin.  (One global atomic per candidate is as good where the
+// candidates are spread evenly, and far worse where they crowd into a few blocks.)
+template <bool HIST>
 __global__ __launch_bounds__(kSBlock) void k_accum_filter(
         const float* __restrict__ grad, float* __restrict__ res, uint32_t m, int64_t stride,
         const uint32_t* __restrict__ tspec, uint32_t* __restrict__ cand_idx,
         float* __restrict__ cand_val, uint32_t cap, uint32_t* __restrict__ cand_count,
-        uint2* __restrict__ run_table, uint32_t nchunks) {
+        uint2* __restrict__ run_table, uint32_t nchunks, uint32_t* __restrict__ hist) {
     constexpr int kWaves = kSBlock / kWave;
     __shared__ uint32_t s_cnt[kWaves];
     __shared__ uint32_t s_base;
+    __shared__ uint32_t s_total;
+    __shared__ uint32_t s_h[HIST ? kHistBins : 1];
+    if (HIST)
+        for (int b = threadIdx.x; b < kHistBins; b += kSBlock) s_h[b] = 0u;     // a barrier follows
     const int w = blockIdx.y;
     const uint32_t chunk = blockIdx.x;
     const uint32_t lane = lane_id();
@@ -160,9 +169,11 @@ __global__ __launch_bounds__(kSBlock) void k_accum_filter(
         if (total) base = atomicAdd(&cand_count[w], total);
         run_table[(size_t)w * nchunks + chunk] = make_uint2(base, total);
         s_base = base;
+        s_total = total;
     }
     __syncthreads();
-    if (cnt == 0) return;
+    if (HIST ? s_total == 0 : cnt == 0) return;      // HIST: block-uniform, a barrier follows
+    const Digit dg{ts, (uint32_t)kFineShift};
     uint32_t off = s_base;
     for (uint32_t v = 0; v < wave; ++v) off += s_cnt[v];
     uint32_t* ci = cand_idx + (size_t)w * cap;
@@ -183,10 +194,19 @@ __global__ __launch_bounds__(kSBlock) void k_accum_filter(
         for (int e = 0; e < 4; ++e) {
             if (c[e]) {
                 if (pos < cap) { ci[pos] = v + e - head; cv[pos] = a[i][e]; }
+                if (HIST) atomicAdd(&s_h[dg.bin(__float_as_uint(a[i][e]) & kAbs)], 1u);
                 ++pos;
             }
         }
         off += (uint32_t)(__popcll(b[0]) + __popcll(b[1]) + __popcll(b[2]) + __popcll(b[3]));
+    }
+    if (HIST) {
+        __syncthreads();
+        uint32_t* out = hist + (size_t)w * kHistBins;
+        for (int b = threadIdx.x; b < kHistBins; b += kSBlock) {
+            const uint32_t n = s_h[b];
+            if (n) atomicAdd(&out[b], n);
+        }
     }
 }
 
