@@ -7,7 +7,7 @@
 namespace gtopk {
 
 // Sample tile t of a row covers [t*tile_stride, t*tile_stride + 64) (clipped to m): one
-// wave per tile.  A block of 1024 threads takes sixteen tiles per round and keeps eight
+// wave per tile.  A block of 1024 threads takes sixteen tiles per round and keeps four
 // rounds of loads in flight.
 __global__ __launch_bounds__(kSampleBlock) void k_sample(
         const float* __restrict__ grad, const float* __restrict__ res, uint32_t m, int64_t stride,
