@@ -31,7 +31,7 @@ def oracle_step_parallel(res, grad, k):
     return loc_idx, loc_val, g_idx, g_val, out
 
 
-@pytest.mark.parametrize("name,iters", [("C3", 2), ("C4a", 2), ("C4b", 1), ("C5", 1)])
+@pytest.mark.parametrize("name,iters", [("C3", 5), ("C4a", 5), ("C4b", 5), ("C5", 5)])
 def test_full_size_step(name, iters):
     cfg = W.CONFIGS[name]
     P, m, k = cfg.P, cfg.m, cfg.k
