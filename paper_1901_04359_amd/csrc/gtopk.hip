@@ -88,13 +88,14 @@ SelState carve_select_alt(Carver& c, const SelState& base, size_t sets, size_t* 
     return s;
 }
 
-// slots per group of an array of n slots: a multiple of 256, at least 1024, and large
+// slots per group of an array of n slots: a multiple of 256, at least min_slots, and large
 // enough that there are at most max_groups (<= kMaxGroups) groups
-uint32_t group_slots_for(uint64_t n, uint32_t max_groups) {
+uint32_t group_slots_for(uint64_t n, uint32_t max_groups, uint32_t min_slots = 1024) {
     uint32_t L = ceil_div(n, max_groups);
     L = (L + 255u) & ~255u;
-    return L < 1024u ? 1024u : L;
+    return L < min_slots ? min_slots : L;
 }
+constexpr uint32_t kMergeMinSlots = 512;        // merged sets: one round of a block (swept 512 / 1024)
 
 // Groups per set when `sets` sets are selected from side by side.  Every block of k_bucket
 // and k_emit pays a fixed price (it reads the set's 4096-bin histogram, or the list of
@@ -128,7 +129,7 @@ struct MergeWs {
 
 MergeWs carve_merge(Carver& c, uint32_t k, size_t pairs) {
     MergeWs w;
-    w.L = group_slots_for(2ull * k, kMaxGroups);
+    w.L = group_slots_for(2ull * k, kMaxGroups, kMergeMinSlots);
     w.sel = carve_select(c, pairs, 2 * k, ceil_div(2ull * k, w.L));
     w.sel_alt = carve_select_alt(c, w.sel, pairs, &w.alt_clear_words);
     w.m_stride = (2 * k + 7u) & ~7u;
@@ -385,7 +386,7 @@ void do_merge_batch(const uint32_t* a_idx, const float* a_val, const uint32_t* b
     uint32_t* zp = odd ? w.sel.hist : w.sel_alt.hist;
     const uint32_t zw = (uint32_t)(odd ? select_clear_words(w.sel) : w.alt_clear_words);
     // w.L is the smallest group the workspace was sized for; a batch of many pairs takes larger ones
-    uint32_t L = group_slots_for(2ull * k, groups_for(batch));
+    uint32_t L = group_slots_for(2ull * k, groups_for(batch), kMergeMinSlots);
     if (L > 8192u) L = 8192u;
     if (L < w.L) L = w.L;
     const uint32_t groups = ceil_div(2ull * k, L);
