@@ -104,7 +104,10 @@ def run_merge(a_idx, a_val, b_idx, b_val, k):
 @pytest.mark.parametrize("k,m", [(1, 10), (2, 3), (64, 64), (255, 5000), (256, 5000), (257, 5000),
                                  (5000, 200_000), (14_728, 1_000_000), (65_536, 300_000),
                                  (65_537, 300_000), (70_001, 70_001), (131_075, 5_000_000),
-                                 (600_001, 5_000_000)])
+                                 (600_001, 5_000_000),
+                                 # either side of the sizes at which the union changes kernels
+                                 (131_072, 1_000_000), (131_073, 1_000_000),
+                                 (524_288, 3_000_000), (524_289, 3_000_000)])
 def test_merge_parity(kind, k, m):
     batch = 3
     idx, val = W.ksets(2 * batch, k, m, seed=k, overlap=0.4, value_kind=kind)
@@ -340,6 +343,7 @@ def test_step_density_schedule(rho, m):
     (4, 32_769, 33, 32_771),          # one element into a second block; rows not 16-byte aligned
     (8, 131_071, 1, None),            # k = 1
     (64, 40_000, 40, None),           # more workers than the configs use (six rounds)
+    (256, 5_000, 50, None),           # eight rounds, 128 pairs in the first
     (4, 300_001, 3_000, 300_005),     # padded rows, odd stride
 ])
 def test_step_shapes(P, m, k, stride):
