@@ -26,8 +26,7 @@ every add here is ONE IEEE-754 binary32 round-to-nearest add, in a fixed order;
 magnitudes are compared on the integer bit pattern, so no floating-point
 comparison decides anything.
 
-Readings taken where the paper is silent or inconsistent (each is listed in
-the design document as well):
+Readings taken where the paper is silent or inconsistent:
 
   R1  "Mask has k non-zero values" wins over the literal `|G| > thr` (which
       would select k-1): exactly k entries are selected, the first k under the
