@@ -645,3 +645,27 @@ def test_step_under_graph_capture():
         assert bits_equal(dev.residual(), exp["residual"]), it
         res = exp["residual"]
         assert float(scratch) > 0
+
+
+def test_non_finite_inputs_keep_the_structure():
+    """NaN / Inf are outside the method's domain (results unspecified), but every decision is
+    taken on integer keys, so the outputs keep their structure: k ascending, distinct indices
+    per worker, values copied from the accumulated row, and the global set drawn from the
+    union of the local ones."""
+    P, m, k = 4, 50_000, 100
+    rng = np.random.default_rng(5)
+    g = rng.standard_normal((P, m)).astype(np.float32)
+    g[:, ::97] = np.inf
+    g[:, 5::389] = -np.inf
+    g[:, 11::1013] = np.nan
+    dev = Device(P, m, k)
+    dev.set_grad(g)
+    say("non-finite inputs")
+    gi, gv = dev.step()
+    li = idx_np(dev.loc_idx)
+    for w in range(P):
+        assert (np.diff(li[w].astype(np.int64)) > 0).all() and li[w].max() < m
+        # the selected entries are the non-finite ones: their keys are the largest
+        assert (~np.isfinite(g[w][li[w]])).all()
+    assert (np.diff(gi.astype(np.int64)) > 0).all()
+    assert np.isin(gi, np.unique(li)).all()
