@@ -669,3 +669,27 @@ def test_non_finite_inputs_keep_the_structure():
         assert (~np.isfinite(g[w][li[w]])).all()
     assert (np.diff(gi.astype(np.int64)) > 0).all()
     assert np.isin(gi, np.unique(li)).all()
+
+
+@pytest.mark.parametrize("k", [300, 70_000, 600_000])
+def test_merge_of_unsorted_sets_stays_in_bounds(k):
+    """Unsorted or duplicate indices in caller-supplied sets give unspecified results, but the
+    call must complete and leave neighbouring memory alone (guard words around the output)."""
+    import torch
+    from paper_1901_04359_amd import binding as B
+    rng = np.random.default_rng(k)
+    batch = 2
+    mk = lambda: to_dev(rng.integers(0, 2 * k, (batch, k)).astype(np.uint32))
+    a_idx, b_idx = mk(), mk()
+    a_val = to_dev(rng.standard_normal((batch, k)).astype(np.float32))
+    b_val = to_dev(rng.standard_normal((batch, k)).astype(np.float32))
+    guard = 1024
+    out_idx = torch.full((batch * k + 2 * guard,), 0x5A5A5A5A, dtype=torch.int32, device="cuda")
+    out_val = torch.full((batch * k + 2 * guard,), 7.0, dtype=torch.float32, device="cuda")
+    ws = B.alloc_merge_workspace(k, batch)
+    say(f"merge of unsorted sets k={k}")
+    B.gtopk_merge(a_idx, a_val, b_idx, b_val, k, batch, k, out_idx[guard:guard + batch * k],
+                  out_val[guard:guard + batch * k], k, ws)
+    torch.cuda.synchronize()
+    assert bool((out_idx[:guard] == 0x5A5A5A5A).all()) and bool((out_idx[-guard:] == 0x5A5A5A5A).all())
+    assert bool((out_val[:guard] == 7.0).all()) and bool((out_val[-guard:] == 7.0).all())
