@@ -693,3 +693,21 @@ def test_merge_of_unsorted_sets_stays_in_bounds(k):
     torch.cuda.synchronize()
     assert bool((out_idx[:guard] == 0x5A5A5A5A).all()) and bool((out_idx[-guard:] == 0x5A5A5A5A).all())
     assert bool((out_val[:guard] == 7.0).all()) and bool((out_val[-guard:] == 7.0).all())
+
+
+def test_allreduce_of_unsorted_sets_stays_in_bounds():
+    """The same for the all-reduce: unsorted, duplicate and out-of-range indices."""
+    import torch
+    from paper_1901_04359_amd import binding as B
+    rng = np.random.default_rng(9)
+    P, k, m = 5, 20_000, 100_000
+    idx = to_dev(rng.integers(0, 2 * m, (P, k)).astype(np.uint32))
+    val = to_dev(rng.standard_normal((P, k)).astype(np.float32))
+    guard = 1024
+    buf = torch.full((m + 2 * guard,), 7.0, dtype=torch.float32, device="cuda")
+    ws = B.alloc_allreduce_workspace(m, P)
+    say("all-reduce of unsorted sets")
+    B.gtopk_topk_allreduce(idx, val, P, k, buf[guard:guard + m], ws)
+    torch.cuda.synchronize()
+    assert bool((buf[:guard] == 7.0).all()) and bool((buf[-guard:] == 7.0).all())
+    assert bool(torch.isfinite(buf[guard:guard + m]).all())
