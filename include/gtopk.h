@@ -32,9 +32,10 @@
  *   - Return value: GTOPK_OK (0) when the work was enqueued, a negative
  *     gtopk_status otherwise; on an argument error nothing is enqueued.
  *     Argument errors are found on the host, without touching the GPU.
- *   - Not checked (results unspecified, but no out-of-bounds access inside the
- *     given sizes): NaN/Inf inputs; unsorted, duplicate or >= 2^32-1 indices in
- *     caller-provided k-sets; buffers that overlap each other.
+ *   - Not checked (results unspecified, but no access outside the given sizes):
+ *     NaN/Inf inputs; unsorted, duplicate or out-of-range indices in
+ *     caller-provided k-sets (an entry whose index is >= m is skipped where it
+ *     would be written to a row).  Buffers must not overlap each other.
  */
 #ifndef GTOPK_H_
 #define GTOPK_H_

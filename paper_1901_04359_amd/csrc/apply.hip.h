@@ -9,11 +9,13 @@ namespace gtopk {
 // weights[c][g_idx[t]] -= lr * g_val[t]: one fp32 multiply, then one fp32 subtract
 // (no fused multiply-add: the library is built with -ffp-contract=off).
 __global__ __launch_bounds__(kBlock) void k_apply_update(
-        float* __restrict__ weights, int64_t stride, uint32_t k, const uint32_t* __restrict__ g_idx,
-        const float* __restrict__ g_val, float lr) {
+        float* __restrict__ weights, uint32_t m, int64_t stride, uint32_t k,
+        const uint32_t* __restrict__ g_idx, const float* __restrict__ g_val, float lr) {
     const uint32_t t = blockIdx.x * kBlock + threadIdx.x;
     if (t >= k) return;
-    float* w = weights + (int64_t)blockIdx.y * stride + g_idx[t];
+    const uint32_t i = g_idx[t];
+    if (i >= m) return;                    // not a valid set: nothing is written outside the row
+    float* w = weights + (int64_t)blockIdx.y * stride + i;
     const float p = lr * g_val[t];
     *w = *w - p;
 }
@@ -30,10 +32,10 @@ __global__ void k_mask_clear(uint8_t* __restrict__ mask, uint64_t m) {
     }
 }
 
-__global__ __launch_bounds__(kBlock) void k_mask_set(uint8_t* __restrict__ mask, uint32_t k,
+__global__ __launch_bounds__(kBlock) void k_mask_set(uint8_t* __restrict__ mask, uint32_t m, uint32_t k,
                                                      const uint32_t* __restrict__ g_idx) {
     const uint32_t t = blockIdx.x * kBlock + threadIdx.x;
-    if (t < k) mask[g_idx[t]] = 1;
+    if (t < k && g_idx[t] < m) mask[g_idx[t]] = 1;
 }
 
 }  // namespace gtopk

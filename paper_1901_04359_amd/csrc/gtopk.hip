@@ -555,7 +555,8 @@ int gtopk_residual_restore(float* residual, int64_t m, int64_t stride, int32_t P
     if (!aligned16(residual) || !aligned16(loc_idx) || !aligned16(loc_val) || !aligned16(g_idx))
         return GTOPK_EALIGN;
     hipLaunchKernelGGL(k_restore, dim3(ceil_div((uint32_t)k, kBlock), (uint32_t)P), dim3(kBlock), 0,
-                       (hipStream_t)stream, residual, stride, (uint32_t)k, loc_idx, loc_val, g_idx);
+                       (hipStream_t)stream, residual, (uint32_t)m, stride, (uint32_t)k, loc_idx, loc_val,
+                       g_idx);
     return launch_status();
 }
 
@@ -603,8 +604,8 @@ int gtopk_apply_update(float* weights, int64_t m, int64_t stride, int32_t copies
         return GTOPK_EINVAL;
     if (!aligned16(weights) || !aligned16(g_idx) || !aligned16(g_val)) return GTOPK_EALIGN;
     hipLaunchKernelGGL(k_apply_update, dim3(ceil_div((uint32_t)k, kBlock), (uint32_t)copies),
-                       dim3(kBlock), 0, (hipStream_t)stream, weights, stride, (uint32_t)k, g_idx, g_val,
-                       lr);
+                       dim3(kBlock), 0, (hipStream_t)stream, weights, (uint32_t)m, stride, (uint32_t)k, g_idx,
+                       g_val, lr);
     return launch_status();
 }
 
@@ -617,7 +618,7 @@ int gtopk_dense_mask(const uint32_t* g_idx, int32_t k, int64_t m, uint8_t* mask,
     if (blocks > 4096) blocks = 4096;
     hipLaunchKernelGGL(k_mask_clear, dim3(blocks), dim3(256), 0, st, mask, (uint64_t)m);
     hipLaunchKernelGGL(k_mask_set, dim3(ceil_div((uint32_t)k, kBlock)), dim3(kBlock), 0, st, mask,
-                       (uint32_t)k, g_idx);
+                       (uint32_t)m, (uint32_t)k, g_idx);
     return launch_status();
 }
 

@@ -443,12 +443,14 @@ __device__ __forceinline__ bool contains(const uint32_t* a, uint32_t n, uint32_t
 // The literal form: the slots were zeroed by the local selection; add the value back
 // where the index is not in the global set.
 __global__ __launch_bounds__(kBlock) void k_restore(
-        float* __restrict__ res, int64_t stride, uint32_t k, const uint32_t* __restrict__ loc_idx,
-        const float* __restrict__ loc_val, const uint32_t* __restrict__ g_idx) {
+        float* __restrict__ res, uint32_t m, int64_t stride, uint32_t k,
+        const uint32_t* __restrict__ loc_idx, const float* __restrict__ loc_val,
+        const uint32_t* __restrict__ g_idx) {
     const int w = blockIdx.y;
     const uint32_t t = blockIdx.x * kBlock + threadIdx.x;
     if (t >= k) return;
     const uint32_t i = loc_idx[(size_t)w * k + t];
+    if (i >= m) return;                         // not a valid set: nothing is written outside the row
     if (contains(g_idx, k, i)) return;          // index is in the global set: stays zero
     float* slot = res + (int64_t)w * stride + i;
     *slot = *slot + loc_val[(size_t)w * k + t];
