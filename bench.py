@@ -149,6 +149,37 @@ def time_three_calls(B, torch, cfg, grads, res, g_idx, g_val, ws, reps: int = 10
             "sum_ms": round(t_sel + t_tree + t_res, 4)}
 
 
+def time_per_iteration(B, torch, W, cfg, reps: int = 20):
+    """The config's own iterations (1 .. cfg.iters), each timed `reps` times from the residual the
+    previous iteration left (restored from a saved copy outside the timed region): iteration 1
+    starts from a zero residual, the later ones are the steady state."""
+    P, m, k = cfg.P, cfg.m, cfg.k
+    grads = [torch.from_numpy(W.gradients(cfg, it, threads=min(16, os.cpu_count() or 8))).cuda()
+             for it in range(cfg.iters)]
+    res = torch.zeros((P, m), dtype=torch.float32, device="cuda")
+    saved = torch.zeros_like(res)
+    g_idx = torch.zeros(k, dtype=torch.int32, device="cuda")
+    g_val = torch.zeros(k, dtype=torch.float32, device="cuda")
+    ws = B.alloc_workspace(m, k, P)
+    out = {}
+    for it in range(cfg.iters):
+        saved.copy_(res)
+        times = []
+        for rep in range(reps + 2):
+            res.copy_(saved)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            B.gtopk_step(grads[it], res, k, g_idx, g_val, None, None, ws)
+            e1.record()
+            torch.cuda.synchronize()
+            if rep >= 2:
+                times.append(e0.elapsed_time(e1))
+        times.sort()
+        out[str(it + 1)] = {"median_ms": round(times[len(times) // 2], 4), "min_ms": round(times[0], 4)}
+        # res now holds the residual after iteration `it` (every repetition ends in the same state)
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -159,6 +190,9 @@ def main() -> int:
     ap.add_argument("--k", type=int, default=0, help="override the workload's k (density studies)")
     ap.add_argument("--cpu-workers", type=int, default=-1,
                     help="workers in the oracle sample (0 = skip, -1 = as many as fit in ~15 s)")
+    ap.add_argument("--per-iteration", action="store_true",
+                    help="also time each of the config's iterations on its own, from the residual "
+                         "its predecessor left (iteration 1: zero residual)")
     ap.add_argument("--three-calls", action="store_true",
                     help="also time gtopk_local_select, gtopk_tree and gtopk_residual_restore "
                          "one by one")
@@ -271,6 +305,10 @@ def main() -> int:
     if args.aggregations:
         del res, ws
         out["aggregations"] = time_aggregations(B, torch, cfg, grads)
+        res = ws = None
+    if args.per_iteration:
+        del res, ws, grads
+        out["per_iteration"] = time_per_iteration(B, torch, W, cfg)
     if args.cpu_workers != 0:
         out["cpu_baseline"] = cpu_baseline(cfg, args.cpu_workers)
     print(json.dumps(out))
