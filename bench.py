@@ -50,31 +50,84 @@ def read_traffic_note(workload: str, what: str = "traffic_bytes_per_launch"):
     return None
 
 
-def cpu_baseline(cfg, n_workers: int, budget_s: float = 15.0):
+def cpu_baseline(cfg, n_workers: int, budget_s: float = 20.0):
     """The oracle as it stands on the first n_workers workers of the config (a power of
-    two, so that the tree is a real one).  n_workers < 0: probe one worker's local
-    selection first and take as many workers as fit in about `budget_s` seconds."""
+    two, so that the tree is a real one), its independent calls (workers in the selection
+    and the restore, pairs of a tree round) spread over the host's cores with a thread
+    pool; the same sample once more on one thread as a second, labelled figure.
+    n_workers < 0: probe one worker's local selection first and take as many workers as
+    fit in about `budget_s` seconds of CPU work for the two runs together."""
+    from concurrent.futures import ThreadPoolExecutor
     from oracle import gtopk_oracle as orc
     from paper_1901_04359_amd import workloads as W
+    cores = max(1, min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "0") or 0)
+                       or (os.cpu_count() or 1)))
     if n_workers < 0:
         g1 = W.gradient(cfg, 0, 0)
         t0 = time.perf_counter()
         orc.local_select(np.zeros_like(g1), g1, cfg.k)
         per_worker = max(time.perf_counter() - t0, 1e-3)
         n_workers = 2
-        while n_workers * 2 <= cfg.P and n_workers * 2 * per_worker * 1.3 <= budget_s:
+        # one single-threaded run plus one threaded run of the same sample
+        while (n_workers * 2 <= cfg.P and
+               n_workers * 2 * per_worker * 1.3 * (1.0 + 2.0 / cores) <= budget_s):
             n_workers *= 2
     g = W.gradients(cfg, 0, workers=range(n_workers))
     r = np.zeros_like(g)
+    threads = min(cores, n_workers)
+    with ThreadPoolExecutor(max_workers=threads) as ex:
+        t0 = time.perf_counter()
+        orc.step(r, g, cfg.k, map_fn=lambda f, it: list(ex.map(f, it)))
+        dt_pool = time.perf_counter() - t0
     t0 = time.perf_counter()
     orc.step(r, g, cfg.k)
-    dt = time.perf_counter() - t0
+    dt_one = time.perf_counter() - t0
+    what = (f"oracle.step on {n_workers} of the {cfg.P} workers at full m={cfg.m}, k={cfg.k} "
+            f"(select, {n_workers.bit_length() - 1}-round tree, restore), one iteration")
     return {
-        "value": n_workers * cfg.m / dt, "unit": "gradient elements/s", "cores": 1,
+        "value": n_workers * cfg.m / dt_pool, "unit": "gradient elements/s", "cores": threads,
         "kind": "oracle",
-        "sample": (f"oracle.step on {n_workers} of the {cfg.P} workers at full m={cfg.m}, "
-                   f"k={cfg.k} (select, {n_workers.bit_length() - 1}-round tree, restore), "
-                   f"one iteration, {dt:.1f} s, numpy single-threaded"),
+        "sample": (f"{what}, {dt_pool:.1f} s with its independent calls on a pool of {threads} "
+                   f"threads (numpy releases the GIL in its sorts); host reports "
+                   f"{os.cpu_count()} cpus"),
+        "single_thread": {"value": n_workers * cfg.m / dt_one, "cores": 1,
+                          "sample": f"the same sample on one thread, {dt_one:.1f} s"},
+    }
+
+
+def hbm_ceiling(B, torch, a, b, reps: int = 20):
+    """What the memory system gives to the streaming pass's access pattern, on the same two
+    buffers the step streams (outside the timed region): the library's probe kernel in its
+    add form (`b += a`: 8 bytes read, 4 written per element, exactly the pass's algorithmic
+    traffic) and in its read-only form, and torch's own `b.add_(a)` as an independent
+    reference.  HIP events on the current stream, `reps` launches each."""
+    n = (a.numel() // 32768) * 32768
+    av, bv = a.view(-1), b.view(-1)
+    sink = torch.zeros(n // 32768, dtype=torch.float32, device="cuda")
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    t_add = timed(lambda: B.gtopk_probe_stream(av, bv, n, 0, None))
+    t_read = timed(lambda: B.gtopk_probe_stream(av, bv, n, 1, sink))
+    t_torch = timed(lambda: bv.add_(av))
+    gbs = lambda nbytes, ms: round(nbytes / (ms * 1e-3) / 1e9, 1)
+    return {
+        "elements": n,
+        "probe_add_GBs": gbs(12.0 * n, t_add), "probe_add_ms": round(t_add, 4),
+        "probe_read_GBs": gbs(8.0 * n, t_read), "probe_read_ms": round(t_read, 4),
+        "torch_add_GBs": gbs(12.0 * a.numel(), t_torch), "torch_add_ms": round(t_torch, 4),
+        "note": ("probe = k_probe_stream, the streaming pass's block shape and cache policy with "
+                 "only the memory traffic left; add: 12 B per element, read: 8 B per element; "
+                 "torch_add = torch's b.add_(a) on the same buffers"),
     }
 
 
@@ -201,6 +254,12 @@ def main() -> int:
     ap.add_argument("--aggregations", action="store_true",
                     help="also time the paper's comparison aggregations (Algorithms 1 and 2) "
                          "against the tree on this workload's local sets")
+    ap.add_argument("--degenerate-workers", type=int, default=0,
+                    help="replace the gradient rows of this many workers by rows of equal "
+                         "magnitudes, which overflow the candidate list and are selected from "
+                         "the dense row (cost of the exact fallback)")
+    ap.add_argument("--no-ceiling", action="store_true",
+                    help="skip the HBM-ceiling probe passes")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device-to-device copy a few times (reference "
                          "reading for the rocprofv3 FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -237,6 +296,9 @@ def main() -> int:
     grads = []
     for b in range(args.batches):
         host = W.gradients(cfg, b, threads=min(16, os.cpu_count() or 8))
+        for w in range(min(args.degenerate_workers, P)):
+            sign = np.random.default_rng(1000 * b + w).integers(0, 2, m).astype(np.float32) * 2 - 1
+            host[(w * 7) % P] = sign * np.float32(0.125)
         grads.append(torch.from_numpy(host).cuda())
         del host
     t_gen = time.perf_counter() - t_gen
@@ -267,8 +329,8 @@ def main() -> int:
     # stage times and the dominant kernel's duration come from here
     t2 = time.perf_counter()
     for i in range(K):
-        B.gtopk_arm_stage_events([e.cuda_event for e in events[i]])
-        step(Wm + K + i)
+        B.gtopk_step_timed(grads[(Wm + K + i) % len(grads)], res, k, g_idx, g_val, None, None, ws,
+                           [e.cuda_event for e in events[i]])
     torch.cuda.synchronize()
     t3 = time.perf_counter()
 
@@ -313,6 +375,14 @@ def main() -> int:
                      "algorithmic_bytes_per_launch": alg_bytes},
         "input_generation_s": round(t_gen, 1),
     }
+    if args.degenerate_workers:
+        counts, cap = B.gtopk_debug_candidate_counts(ws, m, k, P)
+        out["degenerate_workers"] = {
+            "requested": args.degenerate_workers,
+            "served_from_dense_row_in_last_step": sum(1 for c in counts if c < k or c > cap)}
+    if not args.no_ceiling:
+        out["hbm_ceiling"] = hbm_ceiling(B, torch, grads[0], res)
+        res.zero_()
     if args.three_calls:
         out["three_calls"] = time_three_calls(B, torch, cfg, grads, res, g_idx, g_val, ws)
     if args.aggregations:

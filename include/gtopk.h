@@ -21,8 +21,8 @@
  *     A call only enqueues kernels on `stream` and returns; it never
  *     synchronises with the host.  Two calls that share a workspace must be
  *     ordered (same stream, or an event between them).
- *   - Values are IEEE-754 binary32 ("All models are trained with 32-bit floating
- *     points", note under Table III).  Every add is one round-to-nearest fp32
+ *   - Values are IEEE-754 binary32 (the paper trains in fp32: note under
+ *     Table III).  Every add is one round-to-nearest fp32
  *     add; denormals are not flushed.  Magnitude |v| is compared on the integer
  *     `bits(v) & 0x7fffffff`.  "Top k" means: the first k entries under the
  *     total order (|v| descending, index ascending) - exactly k entries, the
@@ -183,18 +183,34 @@ int gtopk_dense_topk(const float* dense, int64_t m, int32_t k, uint32_t* g_idx, 
                      void* ws, size_t ws_bytes, void* stream);
 
 /*
- * Instrumentation for benchmarks (not part of the method): arm the NEXT
- * gtopk_step call on this process to record the given HOST handles of six
- * hipEvent_t (created by the caller, passed as void*) on its stream at its
- * stage boundaries:
- *   [0] start  [1] after the sampling kernels  [2] after the streaming
+ * Instrumentation for benchmarks (not part of the method): gtopk_step with HIP event
+ * records at its stage boundaries.  `events` holds the HOST handles of six hipEvent_t
+ * (created by the caller, passed as void*), recorded on `stream`:
+ *   [0] start  [1] after the speculative-threshold kernels  [2] after the streaming
  *   accumulate/filter kernel  [3] after the exact local selection
  *   [4] after the tree  [5] after the residual restore.
- * The arming is consumed by that one call.  events == NULL disarms.  Not
- * thread-safe.  Returns GTOPK_EINVAL if one of the six handles is NULL.
+ * The handles belong to this one call: the library keeps nothing between calls, so
+ * concurrent callers (each with its own workspace, stream and events) do not interfere.
+ * Results are those of gtopk_step.  GTOPK_EINVAL if events or one of the handles is NULL.
  */
 #define GTOPK_STAGE_EVENTS 6
-int gtopk_arm_stage_events(void* const* events);
+int gtopk_step_timed(const float* grad, float* residual, int64_t m, int64_t stride,
+                     int32_t P, int32_t k, uint32_t* g_idx, float* g_val,
+                     uint32_t* loc_idx, float* loc_val,
+                     void* ws, size_t ws_bytes, void* stream, void* const* events);
+
+/*
+ * Instrumentation for benchmarks (not part of the method): the streaming pass of the local
+ * selection with everything but its memory traffic taken out (same block shape, same
+ * number of 16-byte accesses in flight, same cache policy), to put on record what the
+ * memory system gives to that access pattern.
+ *   mode 0: b[i] = b[i] + a[i] for i < n  (8 bytes read and 4 written per element, as the pass)
+ *   mode 1: a and b are only read; one float per 32768 elements is written to sink
+ *           (sink holds n / 32768 floats; it may be NULL in mode 0)
+ * n must be a positive multiple of 32768.
+ */
+int gtopk_probe_stream(const float* a, float* b, int64_t n, int32_t mode, float* sink,
+                       void* stream);
 
 /*
  * Instrumentation for tests (not part of the method): after a gtopk_local_select or
@@ -206,6 +222,24 @@ int gtopk_arm_stage_events(void* const* events);
  */
 int gtopk_debug_candidate_counts(const void* ws, int64_t m, int32_t k, int32_t P,
                                  uint32_t* host_counts, uint32_t* host_capacity);
+
+/*
+ * Instrumentation for tests (not part of the method; host only, touches no GPU): how the
+ * local selection of these sizes is laid out, so that a test can build rows that defeat
+ * the speculative threshold and can tell which regime it exercises.
+ *   plan[0] tile_stride  sample tile t of a row covers elements [t*tile_stride, +plan[2])
+ *   plan[1] n_tiles      tiles per row (t = 0 .. n_tiles-1, the last one clipped to m)
+ *   plan[2] tile_len     elements per tile
+ *   plan[3] target       sample rank whose histogram-bucket edge becomes the threshold
+ *   plan[4] capacity     entries a worker's candidate list holds
+ *   plan[5] pass_histogram  1 if the streaming pass counts the first digits of its
+ *                        candidates itself (the dense-row fallback then uses a histogram
+ *                        of its own), 0 if the select's histogram kernel does
+ *   plan[6] small_path   1 if these sizes take the few-launch path for small problems
+ *   plan[7] reserved (0)
+ */
+#define GTOPK_PLAN_WORDS 8
+int gtopk_debug_plan(int64_t m, int32_t k, int32_t P, uint32_t* plan);
 
 #ifdef __cplusplus
 }

@@ -4,13 +4,15 @@ THIS IS TEST INFRASTRUCTURE.  Only tests, the smoke check and the benchmark's
 `cpu_baseline` leg may import it.  It shares no code with the HIP library and
 imports nothing from the product package; inputs arrive as numpy arrays.
 
-It is a plain, slow, step-by-step transcription of the method, in the paper's
-order, so that it can be checked against the paper by eye:
+Every function is the plain definition of one step of the method (a full sort
+wherever something is selected, no blocking, no approximation), and the steps
+are composed in the order the paper gives them, so that each can be checked
+against its passage by eye:
 
-  * Algorithm 4 ("gTopKAllReduce based S-SGD on worker g"), lines 4-8:
+  * Algorithm 4 (the S-SGD iteration built on gTopKAllReduce), lines 4-8:
     accumulate, threshold, mask, extract, keep residual  -> `local_select`
   * Definition 1 (the Top-k operation between two sparse vectors) -> `merge`
-  * Algorithm 3 ("gTopKAllReduce"), lines 1-18: the binary tree  -> `tree`
+  * Algorithm 3 (gTopKAllReduce), lines 1-18: the binary tree    -> `tree`
   * Eq. 3 (S-SGD averages over the P workers)                  -> the /P in `tree`
   * Algorithm 3 lines 19-23 (broadcast, gMask) and Algorithm 4 line 10
     (extra residual)                                            -> `residual_restore`
@@ -28,9 +30,11 @@ comparison decides anything.
 
 Readings taken where the paper is silent or inconsistent:
 
-  R1  "Mask has k non-zero values" wins over the literal `|G| > thr` (which
-      would select k-1): exactly k entries are selected, the first k under the
-      total order (|v| descending, index ascending).
+  R1  Algorithm 4 lines 5-6 compare `|G| > thr` with thr the k-th largest
+      magnitude, which taken literally selects k-1 entries, while the comment
+      on line 6 says the mask has k of them.  The comment wins: exactly k
+      entries are selected, the first k under the total order (|v| descending,
+      index ascending).
   R2  |v| is compared as the unsigned integer `bits(v) & 0x7fffffff`
       (monotone in |v| for finite values; +0 and -0 are equal).
   R4  A merge selects among the UNION OF INDICES of its two operands, whatever
@@ -63,7 +67,13 @@ P = 2 against the dense sum, shared-support closed form, exact conservation
 hand-worked 4-worker example.  For P > 2 with general inputs the tree is
 pinned by composition of pinned merges in the R5 order plus the structural
 closed forms (log2 P rounds, P - 1 merges, rank 0 in every round); the paper
-prints no numeric example (its worked figures are images).  `topk_allreduce`
+prints no numeric example (its worked figures are images).
+
+The pairs of one tree round, and the workers in the local selection and the
+restore, are independent of each other: `tree_rounds`, `tree` and `step` take
+an optional `map_fn` (default: the builtin `map`) through which those
+independent calls are issued, so that a caller may hand in a thread pool's
+`map`.  The arithmetic of every call is the same either way.  `topk_allreduce`
 is pinned by a per-index Python loop, by exact integer-valued sums, by an
 input whose fp32 sum depends on the order, and through P = 2, where its top-k
 must equal the tree's result; `dense_topk` by the same brute force and library
@@ -153,11 +163,12 @@ def merge(a_idx: np.ndarray, a_val: np.ndarray, b_idx: np.ndarray, b_val: np.nda
     return out_idx, u_val[pos].copy()
 
 
-def tree_rounds(loc_idx: Sequence[np.ndarray], loc_val: Sequence[np.ndarray], k: int
-                ) -> List[List[Optional[Tuple[np.ndarray, np.ndarray]]]]:
+def tree_rounds(loc_idx: Sequence[np.ndarray], loc_val: Sequence[np.ndarray], k: int,
+                map_fn=map) -> List[List[Optional[Tuple[np.ndarray, np.ndarray]]]]:
     """Algorithm 3 lines 1-18 under R5.  Returns, for each round, the list of
     per-rank current sets after that round (None for ranks that have sent their
-    set away and gone idle).  Element [-1][0] is the undivided result."""
+    set away and gone idle).  Element [-1][0] is the undivided result.
+    The merges of one round are independent and go through `map_fn`."""
     P = len(loc_idx)
     assert P >= 1 and (P & (P - 1)) == 0, "the paper assumes P is a power of two"
     cur: List[Optional[Tuple[np.ndarray, np.ndarray]]] = [
@@ -168,24 +179,29 @@ def tree_rounds(loc_idx: Sequence[np.ndarray], loc_val: Sequence[np.ndarray], k:
     for j in range(n_rounds):
         step = 1 << j
         nxt = list(cur)
-        for i in range(0, P, 2 * step):
-            recv = cur[i + step]                      # Recv from the partner
+        receivers = list(range(0, P, 2 * step))
+
+        def one_pair(i, cur=cur, step=step):
+            recv = cur[i + step]                      # the partner's set arrives
             mine = cur[i]
-            nxt[i] = merge(recv[0], recv[1], mine[0], mine[1], k)   # sends = recvs TOP sends
+            return merge(recv[0], recv[1], mine[0], mine[1], k)    # received TOP own
+
+        for i, merged in zip(receivers, map_fn(one_pair, receivers)):
+            nxt[i] = merged
             nxt[i + step] = None                      # the sender goes idle
-        cur = nxt                                      # Barrier
+        cur = nxt                                      # end of the round
         history.append(list(cur))
     if not history:
         history.append(list(cur))
     return history
 
 
-def tree(loc_idx: Sequence[np.ndarray], loc_val: Sequence[np.ndarray], k: int
-         ) -> Tuple[np.ndarray, np.ndarray]:
+def tree(loc_idx: Sequence[np.ndarray], loc_val: Sequence[np.ndarray], k: int,
+         map_fn=map) -> Tuple[np.ndarray, np.ndarray]:
     """gTopKAllReduce's result as every worker sees it after the broadcast:
     the global index set and the AVERAGED values (R7: sum / P, one fp32 divide)."""
     P = len(loc_idx)
-    g_idx, g_sum = tree_rounds(loc_idx, loc_val, k)[-1][0]
+    g_idx, g_sum = tree_rounds(loc_idx, loc_val, k, map_fn)[-1][0]
     g_val = (g_sum / np.float32(P)).astype(np.float32)
     return g_idx.copy(), g_val
 
@@ -238,20 +254,24 @@ def dense_topk(dense: np.ndarray, k: int) -> Tuple[np.ndarray, np.ndarray]:
     return idx, dense[idx].copy()
 
 
-def step(residual: np.ndarray, grad: np.ndarray, k: int):
+def step(residual: np.ndarray, grad: np.ndarray, k: int, map_fn=map):
     """One full iteration for P workers.  residual, grad: [P][m] float32.
 
     Returns dict with loc_idx [P][k], loc_val [P][k], g_idx [k], g_val [k],
-    residual [P][m] (after the restore) and residual_after_select [P][m]."""
+    residual [P][m] (after the restore) and residual_after_select [P][m].
+    The per-worker calls and the pairs of a tree round go through `map_fn`."""
     P, m = grad.shape
     loc_idx = np.empty((P, k), dtype=np.uint32)
     loc_val = np.empty((P, k), dtype=np.float32)
     res_sel = np.empty((P, m), dtype=np.float32)
-    for w in range(P):
-        loc_idx[w], loc_val[w], res_sel[w] = local_select(residual[w], grad[w], k)
-    g_idx, g_val = tree(list(loc_idx), list(loc_val), k)
+    selected = map_fn(lambda w: local_select(residual[w], grad[w], k), range(P))
+    for w, (li, lv, rs) in enumerate(selected):
+        loc_idx[w], loc_val[w], res_sel[w] = li, lv, rs
+    g_idx, g_val = tree(list(loc_idx), list(loc_val), k, map_fn)
     res_out = np.empty((P, m), dtype=np.float32)
-    for w in range(P):
-        res_out[w] = residual_restore(res_sel[w], loc_idx[w], loc_val[w], g_idx)
+    restored = map_fn(lambda w: residual_restore(res_sel[w], loc_idx[w], loc_val[w], g_idx),
+                      range(P))
+    for w, r in enumerate(restored):
+        res_out[w] = r
     return {"loc_idx": loc_idx, "loc_val": loc_val, "g_idx": g_idx, "g_val": g_val,
             "residual": res_out, "residual_after_select": res_sel}

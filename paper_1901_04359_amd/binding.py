@@ -21,7 +21,7 @@ EXPORTS = (
     "gtopk_local_select", "gtopk_merge", "gtopk_tree", "gtopk_residual_restore", "gtopk_step",
     "gtopk_apply_update", "gtopk_dense_mask",
     "gtopk_allreduce_workspace_bytes", "gtopk_topk_allreduce", "gtopk_dense_topk",
-    "gtopk_arm_stage_events", "gtopk_debug_candidate_counts",
+    "gtopk_step_timed", "gtopk_probe_stream", "gtopk_debug_candidate_counts", "gtopk_debug_plan",
 )
 
 GTOPK_OK, GTOPK_EINVAL, GTOPK_EWORKSPACE, GTOPK_EALIGN, GTOPK_EHIP = 0, -1, -2, -3, -4
@@ -75,8 +75,13 @@ def load() -> ctypes.CDLL:
     lib.gtopk_topk_allreduce.argtypes = [vp, vp, i32, i32, i64, vp, vp, sz, vp]
     lib.gtopk_dense_topk.restype = c.c_int
     lib.gtopk_dense_topk.argtypes = [vp, i64, i32, vp, vp, vp, sz, vp]
-    lib.gtopk_arm_stage_events.restype = c.c_int
-    lib.gtopk_arm_stage_events.argtypes = [c.POINTER(c.c_void_p)]
+    lib.gtopk_step_timed.restype = c.c_int
+    lib.gtopk_step_timed.argtypes = [vp, vp, i64, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp,
+                                     c.POINTER(c.c_void_p)]
+    lib.gtopk_probe_stream.restype = c.c_int
+    lib.gtopk_probe_stream.argtypes = [vp, vp, i64, i32, vp, vp]
+    lib.gtopk_debug_plan.restype = c.c_int
+    lib.gtopk_debug_plan.argtypes = [i64, i32, i32, c.POINTER(c.c_uint32)]
     lib.gtopk_debug_candidate_counts.restype = c.c_int
     lib.gtopk_debug_candidate_counts.argtypes = [vp, i64, i32, i32, c.POINTER(c.c_uint32),
                                                  c.POINTER(c.c_uint32)]
@@ -265,13 +270,45 @@ def gtopk_dense_topk(dense, k: int, g_idx, g_val, ws) -> None:
     _check(rc, "gtopk_dense_topk")
 
 
-def gtopk_arm_stage_events(events) -> None:
-    """events: sequence of six raw hipEvent_t handles (ints), or None to disarm."""
-    if events is None:
-        _check(load().gtopk_arm_stage_events(None), "gtopk_arm_stage_events")
-        return
-    arr = (ctypes.c_void_p * len(events))(*events)
-    _check(load().gtopk_arm_stage_events(arr), "gtopk_arm_stage_events")
+def gtopk_step_timed(grad, residual, k: int, g_idx, g_val, loc_idx, loc_val, ws, events) -> None:
+    """gtopk_step that records the caller's six raw hipEvent_t handles (ints) at its stage
+    boundaries."""
+    torch = _torch()
+    m, stride = _rows(residual, "residual")
+    mg, sg = _rows(grad, "grad")
+    P = residual.shape[0]
+    if (mg, grad.shape[0]) != (m, P) or (P > 1 and sg != stride):
+        raise ValueError("grad and residual must have the same shape and row stride")
+    if len(events) != 6:
+        raise ValueError("six event handles are needed")
+    arr = (ctypes.c_void_p * 6)(*events)
+    rc = load().gtopk_step_timed(
+        _ptr(grad, torch.float32, "grad"), _ptr(residual, torch.float32, "residual"),
+        m, stride, P, k, _ptr(g_idx, torch.int32, "g_idx"), _ptr(g_val, torch.float32, "g_val"),
+        _ptr(loc_idx, torch.int32, "loc_idx", allow_none=True),
+        _ptr(loc_val, torch.float32, "loc_val", allow_none=True),
+        _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream(), arr)
+    _check(rc, "gtopk_step_timed")
+
+
+def gtopk_probe_stream(a, b, n: int, mode: int, sink=None) -> None:
+    """a, b: float32 GPU tensors of at least n elements (b is updated in mode 0)."""
+    torch = _torch()
+    rc = load().gtopk_probe_stream(
+        _ptr(a, torch.float32, "a"), _ptr(b, torch.float32, "b"), n, mode,
+        _ptr(sink, torch.float32, "sink", allow_none=True), _stream())
+    _check(rc, "gtopk_probe_stream")
+
+
+PLAN_FIELDS = ("tile_stride", "n_tiles", "tile_len", "target", "capacity", "pass_histogram",
+               "small_path", "reserved")
+
+
+def gtopk_debug_plan(m: int, k: int, P: int) -> dict:
+    """Layout of the local selection for these sizes (host only; see gtopk.h)."""
+    plan = (ctypes.c_uint32 * len(PLAN_FIELDS))()
+    _check(load().gtopk_debug_plan(m, k, P, plan), "gtopk_debug_plan")
+    return dict(zip(PLAN_FIELDS, (int(x) for x in plan)))
 
 
 def gtopk_debug_candidate_counts(ws, m: int, k: int, P: int):

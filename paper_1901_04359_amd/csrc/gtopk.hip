@@ -230,12 +230,9 @@ bool sizes_ok(int64_t m, int64_t k, int64_t P) {
 
 int launch_status() { return hipGetLastError() == hipSuccess ? GTOPK_OK : GTOPK_EHIP; }
 
-// Instrumentation: events the next gtopk_step records at its stage boundaries.
-hipEvent_t g_stage_events[GTOPK_STAGE_EVENTS];
-bool g_stage_armed = false;
-
-void mark_stage(int i, bool armed, hipStream_t st) {
-    if (armed) (void)hipEventRecord(g_stage_events[i], st);
+// Instrumentation: the caller's events of one gtopk_step_timed call (NULL: none).
+void mark_stage(int i, void* const* events, hipStream_t st) {
+    if (events) (void)hipEventRecord((hipEvent_t)events[i], st);
 }
 
 void zero_async(hipStream_t st, uint32_t* p0, size_t n0, uint32_t* p1 = nullptr, size_t n1 = 0,
@@ -315,12 +312,24 @@ SamplePlan plan_sample(int64_t m, uint32_t k) {
     return p;
 }
 
+// The pass can also histogram the candidates it keeps; the select's own histogram kernel
+// then only serves workers that fall back to their dense row.  That costs LDS atomics and,
+// per block and non-empty bin, a global atomic in the pass.  Measured against the
+// histogram kernel it saves: at rho = 0.001 (45 candidates per 32768-element block) the
+// pass does not change and the select gains 6-8 us; at rho = 0.01 (460 per block) the pass
+// loses 55 us and the select gains 13 us; at rho = 0.25 (11,500 per block) the pass loses
+// 80 us and the select gains 230 us.  So at both ends, not in between.
+bool pass_histograms(int64_t m, uint32_t k) {
+    const double per_block = 1.4 * (double)k * (double)kChunk / (double)m;
+    return per_block <= 128.0 || per_block >= 4096.0;
+}
+
 // `zero_rows`: store +0.0 at the selected entries (the stand-alone call); gtopk_step
 // passes false and settles the rows in k_restore_fused.  `pre_cleared`: the caller has
 // already cleared this call's counters and histograms.
 int do_local_select(const float* grad, float* residual, int64_t m, int64_t stride, uint32_t P,
                     uint32_t k, uint32_t* out_idx, float* out_val, const StepWs& w, bool zero_rows,
-                    bool pre_cleared, hipStream_t st, bool armed = false) {
+                    bool pre_cleared, hipStream_t st, void* const* events = nullptr) {
     if (!pre_cleared)
         zero_async(st, w.samp_hist, (size_t)(w.tspec - w.samp_hist), w.sel.hist,
                    select_clear_words(w.sel));
@@ -335,17 +344,9 @@ int do_local_select(const float* grad, float* residual, int64_t m, int64_t strid
                        (uint32_t)m, stride, sp.tile_stride, sp.n_tiles, w.samp_hist);
     hipLaunchKernelGGL(k_sample_pick, dim3(P), dim3(kSampleBlock), 0, st, w.samp_hist, sp.target,
                        w.tspec);
-    mark_stage(1, armed, st);
+    mark_stage(1, events, st);
 
-    // The pass can also histogram the candidates it keeps; the select's own histogram kernel
-    // then only serves workers that fall back to their dense row.  That costs LDS atomics and,
-    // per block and non-empty bin, a global atomic in the pass.  Measured against the
-    // histogram kernel it saves: at rho = 0.001 (45 candidates per 32768-element block) the
-    // pass does not change and the select gains 6-8 us; at rho = 0.01 (460 per block) the pass
-    // loses 55 us and the select gains 13 us; at rho = 0.25 (11,500 per block) the pass loses
-    // 80 us and the select gains 230 us.  So at both ends, not in between.
-    const double per_block = 1.4 * (double)k * (double)kChunk / (double)m;
-    const bool producer_hist = per_block <= 128.0 || per_block >= 4096.0;
+    const bool producer_hist = pass_histograms(m, k);
     if (producer_hist)
         hipLaunchKernelGGL(k_accum_filter<true>, dim3(w.nchunks, P), dim3(kSBlock), 0, st, grad,
                            residual, (uint32_t)m, stride, w.tspec, w.cand_idx, w.cand_val, w.cap,
@@ -354,7 +355,7 @@ int do_local_select(const float* grad, float* residual, int64_t m, int64_t strid
         hipLaunchKernelGGL(k_accum_filter<false>, dim3(w.nchunks, P), dim3(kSBlock), 0, st, grad,
                            residual, (uint32_t)m, stride, w.tspec, w.cand_idx, w.cand_val, w.cap,
                            w.cand_count, w.run_table, w.nchunks, w.sel.hist);
-    mark_stage(2, armed, st);
+    mark_stage(2, events, st);
 
     CandSrc src{residual, stride, (uint32_t)m, k, w.cap, w.nchunks, w.Lc, w.Ld,
                 w.cand_idx, w.cand_val, w.cand_count, w.tspec, w.run_table, w.run_off,
@@ -560,9 +561,9 @@ int gtopk_residual_restore(float* residual, int64_t m, int64_t stride, int32_t P
     return launch_status();
 }
 
-int gtopk_step(const float* grad, float* residual, int64_t m, int64_t stride, int32_t P, int32_t k,
-               uint32_t* g_idx, float* g_val, uint32_t* loc_idx, float* loc_val, void* ws,
-               size_t ws_bytes, void* stream) {
+static int step_impl(const float* grad, float* residual, int64_t m, int64_t stride, int32_t P,
+                     int32_t k, uint32_t* g_idx, float* g_val, uint32_t* loc_idx, float* loc_val,
+                     void* ws, size_t ws_bytes, void* stream, void* const* events) {
     if (!grad || !residual || !g_idx || !g_val || !ws) return GTOPK_EINVAL;
     if ((loc_idx == nullptr) != (loc_val == nullptr)) return GTOPK_EINVAL;
     if (!sizes_ok(m, k, P) || stride < m) return GTOPK_EINVAL;
@@ -574,26 +575,41 @@ int gtopk_step(const float* grad, float* residual, int64_t m, int64_t stride, in
     hipStream_t st = (hipStream_t)stream;
     uint32_t* li = loc_idx ? loc_idx : w.loc_idx;
     float* lv = loc_val ? loc_val : w.loc_val;
-    const bool armed = g_stage_armed;
-    g_stage_armed = false;
-    mark_stage(0, armed, st);
+    mark_stage(0, events, st);
     // one clear for everything this step needs zeroed: the sampler's histograms and the
     // candidate counters; both selects' histograms and tickets; the global-set bitmap
     zero_async(st, w.samp_hist, (size_t)(w.tspec - w.samp_hist), w.sel.hist,
                select_clear_words(w.sel), w.mrg.sel.hist, select_clear_words(w.mrg.sel),
                w.mrg.sel_alt.hist, w.mrg.alt_clear_words, w.gbits, w.gbits_words);
     int rc = do_local_select(grad, residual, m, stride, (uint32_t)P, (uint32_t)k, li, lv, w, false,
-                             true, st, armed);
+                             true, st, events);
     if (rc != GTOPK_OK) return rc;
-    mark_stage(3, armed, st);
+    mark_stage(3, events, st);
     rc = do_tree(li, lv, w.sel.T, (uint32_t)P, (uint32_t)k, g_idx, g_val, w, w.gbits, true, st);
     if (rc != GTOPK_OK) return rc;
-    mark_stage(4, armed, st);
+    mark_stage(4, events, st);
     hipLaunchKernelGGL(k_restore_fused, dim3(ceil_div((uint32_t)k, kBlock), (uint32_t)P), dim3(kBlock),
                        0, st, residual, stride, (uint32_t)k, li, lv, w.gbits);
     rc = launch_status();
-    mark_stage(5, armed, st);
+    mark_stage(5, events, st);
     return rc;
+}
+
+int gtopk_step(const float* grad, float* residual, int64_t m, int64_t stride, int32_t P, int32_t k,
+               uint32_t* g_idx, float* g_val, uint32_t* loc_idx, float* loc_val, void* ws,
+               size_t ws_bytes, void* stream) {
+    return step_impl(grad, residual, m, stride, P, k, g_idx, g_val, loc_idx, loc_val, ws, ws_bytes,
+                     stream, nullptr);
+}
+
+int gtopk_step_timed(const float* grad, float* residual, int64_t m, int64_t stride, int32_t P,
+                     int32_t k, uint32_t* g_idx, float* g_val, uint32_t* loc_idx, float* loc_val,
+                     void* ws, size_t ws_bytes, void* stream, void* const* events) {
+    if (!events) return GTOPK_EINVAL;
+    for (int i = 0; i < GTOPK_STAGE_EVENTS; ++i)
+        if (!events[i]) return GTOPK_EINVAL;
+    return step_impl(grad, residual, m, stride, P, k, g_idx, g_val, loc_idx, loc_val, ws, ws_bytes,
+                     stream, events);
 }
 
 int gtopk_apply_update(float* weights, int64_t m, int64_t stride, int32_t copies, int32_t k,
@@ -677,13 +693,33 @@ int gtopk_debug_candidate_counts(const void* ws, int64_t m, int32_t k, int32_t P
     return GTOPK_OK;
 }
 
-int gtopk_arm_stage_events(void* const* events) {
-    if (!events) { g_stage_armed = false; return GTOPK_OK; }
-    for (int i = 0; i < GTOPK_STAGE_EVENTS; ++i) {
-        if (!events[i]) return GTOPK_EINVAL;
-        g_stage_events[i] = (hipEvent_t)events[i];
-    }
-    g_stage_armed = true;
+int gtopk_probe_stream(const float* a, float* b, int64_t n, int32_t mode, float* sink,
+                       void* stream) {
+    if (!a || !b || n < 1 || n % kChunk != 0 || n / kChunk > 0x7fffffff) return GTOPK_EINVAL;
+    if (mode != 0 && mode != 1) return GTOPK_EINVAL;
+    if (mode == 1 && !sink) return GTOPK_EINVAL;
+    if (!aligned16(a) || !aligned16(b) || !aligned16(sink)) return GTOPK_EALIGN;
+    const uint32_t blocks = (uint32_t)(n / kChunk);
+    if (mode == 0)
+        hipLaunchKernelGGL(k_probe_stream<true>, dim3(blocks), dim3(kSBlock), 0, (hipStream_t)stream, a, b,
+                           sink);
+    else
+        hipLaunchKernelGGL(k_probe_stream<false>, dim3(blocks), dim3(kSBlock), 0, (hipStream_t)stream, a,
+                           b, sink);
+    return launch_status();
+}
+
+int gtopk_debug_plan(int64_t m, int32_t k, int32_t P, uint32_t* plan) {
+    if (!plan || !sizes_ok(m, k, P)) return GTOPK_EINVAL;
+    const SamplePlan sp = plan_sample(m, (uint32_t)k);
+    plan[0] = sp.tile_stride;
+    plan[1] = sp.n_tiles;
+    plan[2] = (uint32_t)kSampleTile;
+    plan[3] = sp.target;
+    plan[4] = cand_capacity(m, (uint32_t)k);
+    plan[5] = pass_histograms(m, (uint32_t)k) ? 1u : 0u;
+    plan[6] = 0u;
+    plan[7] = 0u;
     return GTOPK_OK;
 }
 

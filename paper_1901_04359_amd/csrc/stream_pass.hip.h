@@ -210,4 +210,43 @@ __global__ __launch_bounds__(kSBlock) void k_accum_filter(
     }
 }
 
+// ---------------------------------------------------------------------------------
+// instrumentation: what the memory system gives to the pass's access pattern
+// ---------------------------------------------------------------------------------
+
+// The streaming pass with everything but its memory traffic taken out: same block shape,
+// same 16 float4 per lane and array in flight, same non-temporal accesses.
+//   ADD:  b[i] = b[i] + a[i]          (8 bytes read, 4 written per element, as the pass)
+//   !ADD: both arrays read, one float per block written to `sink` (read-only ceiling)
+// n is a multiple of kChunk (the caller checks).
+template <bool ADD>
+__global__ __launch_bounds__(kSBlock) void k_probe_stream(
+        const float* __restrict__ a, float* __restrict__ b, float* __restrict__ sink) {
+    const uint32_t lane = lane_id();
+    const uint32_t wave = threadIdx.x / kWave;
+    const size_t base = (size_t)blockIdx.x * kChunk + (size_t)wave * kWaveSpan;
+    floatx4 av[kIters], bv[kIters];
+#pragma unroll
+    for (int i = 0; i < kIters; ++i) {
+        const size_t v = base + i * 256 + lane * 4;
+        av[i] = __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(a + v));
+        bv[i] = __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(b + v));
+    }
+    if (ADD) {
+#pragma unroll
+        for (int i = 0; i < kIters; ++i) {
+            const size_t v = base + i * 256 + lane * 4;
+            __builtin_nontemporal_store(bv[i] + av[i], reinterpret_cast<floatx4*>(b + v));
+        }
+    } else {
+        floatx4 acc = av[0] + bv[0];
+#pragma unroll
+        for (int i = 1; i < kIters; ++i) acc = acc + av[i] + bv[i];
+        float s = acc.x + acc.y + acc.z + acc.w;
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) s += __shfl_xor(s, d);
+        if (lane == 0 && wave == 0) sink[blockIdx.x] = s;      // keeps the loads alive
+    }
+}
+
 }  // namespace gtopk

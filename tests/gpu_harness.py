@@ -1,14 +1,26 @@
 """Helpers for the GPU parity tests: move numpy arrays to the device, call the
 library through the ctypes binding (the C ABI), bring results back as numpy."""
+import os
 import sys
+import time
 
 import numpy as np
 
+_ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+_CASE_LOG = os.path.join(_ROOT, "gpurun_out", "gpu_cases.log")
+
 
 def say(msg: str) -> None:
-    """Name the case before the GPU step runs, and flush, so a dead box names its test."""
+    """Name the case before the GPU step runs, and flush, so a dead box names its test.
+    The line also goes to a log file that a test runner's output capture does not hold back."""
     print(f"[gpu-case] {msg}", flush=True)
     sys.stdout.flush()
+    try:
+        os.makedirs(os.path.dirname(_CASE_LOG), exist_ok=True)
+        with open(_CASE_LOG, "a") as fh:
+            fh.write(f"{time.strftime('%H:%M:%S')} {msg}\n")
+    except OSError:
+        pass
 
 
 def to_dev(a: np.ndarray):

@@ -19,16 +19,15 @@ THREADS = min(16, os.cpu_count() or 8)
 
 
 def oracle_step_parallel(res, grad, k):
-    P = grad.shape[0]
+    """orc.step with its independent calls (workers; the pairs of a tree round) issued through
+    a thread pool."""
     with ThreadPoolExecutor(max_workers=THREADS) as ex:
-        sel = list(ex.map(lambda w: orc.local_select(res[w], grad[w], k), range(P)))
-    loc_idx = [s[0] for s in sel]
-    loc_val = [s[1] for s in sel]
-    g_idx, g_val = orc.tree(loc_idx, loc_val, k)
-    with ThreadPoolExecutor(max_workers=THREADS) as ex:
-        out = list(ex.map(lambda w: orc.residual_restore(sel[w][2], loc_idx[w], loc_val[w], g_idx),
-                          range(P)))
-    return loc_idx, loc_val, g_idx, g_val, out
+        def pool_map(f, items):
+            items = list(items)
+            say(f"  oracle: {len(items)} independent calls")
+            return list(ex.map(f, items))
+        out = orc.step(res, grad, k, map_fn=pool_map)
+    return out["loc_idx"], out["loc_val"], out["g_idx"], out["g_val"], out["residual"]
 
 
 @pytest.mark.parametrize("name,iters", [("C3", 5), ("C4a", 5), ("C4b", 5), ("C5", 5)])
@@ -58,6 +57,43 @@ def test_full_size_step(name, iters):
         # every worker must have been served from its candidate list (the timed path)
         counts, cap = dev.B.gtopk_debug_candidate_counts(dev.ws, m, k, P)
         assert all(k <= c <= cap for c in counts), (name, it, min(counts), max(counts), cap)
+
+
+@pytest.mark.parametrize("rho,iters", [(0.25, 2), (0.0725, 2)])
+def test_full_size_warmup_densities(rho, iters):
+    """The first two densities of the paper's warm-up schedule (Section IV-B) at the
+    ResNet-50-sized configuration's full size (m = 25,557,032, P = 32): the sizes at which
+    the large-density timings are quoted.  Merged sets have up to 12.8 M slots here and a
+    worker's candidate list millions of entries, which no smaller case reaches."""
+    base = W.CONFIGS["C4a"]
+    k = int(round(rho * base.m))
+    cfg = W.scaled(base, base.m, k=k, name=f"C4/rho={rho}")
+    P, m = cfg.P, cfg.m
+    dev = Device(P, m, k)
+    res = np.zeros((P, m), dtype=np.float32)
+    for it in range(iters):
+        say(f"full size rho={rho} it={it}: generating P={P} m={m}")
+        g = W.gradients(cfg, it, threads=THREADS)
+        dev.set_grad(g)
+        say(f"full size rho={rho} it={it}: gtopk_step k={k}")
+        gi, gv = dev.step()
+        counts, cap = dev.B.gtopk_debug_candidate_counts(dev.ws, m, k, P)
+        li, lv = idx_np(dev.loc_idx), val_np(dev.loc_val)
+        out = dev.residual()
+        say(f"full size rho={rho} it={it}: oracle")
+        o_li, o_lv, o_gi, o_gv, o_res = oracle_step_parallel(res, g, k)
+        for w in range(P):
+            assert np.array_equal(li[w], o_li[w]), f"it={it} w={w} loc_idx {first_diff(li[w], o_li[w])}"
+            assert bits_equal(lv[w], o_lv[w]), f"it={it} w={w} loc_val {first_diff(lv[w], o_lv[w])}"
+        del li, lv
+        assert np.array_equal(gi, o_gi), f"it={it} g_idx {first_diff(gi, o_gi)}"
+        assert bits_equal(gv, o_gv), f"it={it} g_val {first_diff(gv, o_gv)}"
+        for w in range(P):
+            assert bits_equal(out[w], o_res[w]), f"it={it} w={w} residual {first_diff(out[w], o_res[w])}"
+        res = o_res
+        del out, o_li, o_lv
+        # the timed path: every worker served from its candidate list
+        assert all(k <= c <= cap for c in counts), (rho, it, min(counts), max(counts), cap)
 
 
 @pytest.mark.parametrize("name", ["C4a", "C4b"])

@@ -561,14 +561,14 @@ def _mut_merge_dense_add(a_idx, a_val, b_idx, b_val, k, _orig=orc.merge):
     return oi, (ov + f32(0.0)).astype(np.float32)        # -0.0 becomes +0.0
 
 
-def _mut_tree_chain(loc_idx, loc_val, k):
+def _mut_tree_chain(loc_idx, loc_val, k, map_fn=map):
     cur = (loc_idx[0], loc_val[0])
     for w in range(1, len(loc_idx)):
         cur = orc.merge(cur[0], cur[1], loc_idx[w], loc_val[w], k)
     return cur[0], (cur[1] / f32(len(loc_idx))).astype(np.float32)
 
 
-def _mut_tree_no_average(loc_idx, loc_val, k):
+def _mut_tree_no_average(loc_idx, loc_val, k, map_fn=map):
     gi, gs = orc.tree_rounds(loc_idx, loc_val, k)[-1][0]
     return gi.copy(), gs.copy()
 
@@ -619,3 +619,18 @@ def test_planted_mistake_is_caught(monkeypatch, name, mutant):
         except AssertionError:
             tripped.append(pin.__name__)
     assert tripped, f"no pin noticed the planted mistake {mutant.__name__}"
+
+
+def test_step_through_a_thread_pool_is_the_same_step():
+    """`map_fn` only changes who issues the independent calls (workers, pairs of a round),
+    never their arithmetic: a thread pool's map must give the bits the builtin map gives."""
+    from concurrent.futures import ThreadPoolExecutor
+    rng = np.random.default_rng(2024)
+    P, m, k = 8, 3000, 40
+    res = (rng.standard_normal((P, m)) * 1e-3).astype(np.float32)
+    g = (rng.standard_normal((P, m)) * 1e-3).astype(np.float32)
+    a = orc.step(res, g, k)
+    with ThreadPoolExecutor(max_workers=4) as ex:
+        b = orc.step(res, g, k, map_fn=lambda f, it: list(ex.map(f, it)))
+    for key in a:
+        assert np.array_equal(np.asarray(a[key]).view(np.uint32), np.asarray(b[key]).view(np.uint32)), key
