@@ -159,3 +159,34 @@ def test_argument_errors_allreduce_and_dense_topk():
     # merged pairs have 2k slots in a uint32
     assert B.gtopk_merge_workspace_bytes(2**30 + 1, 1) == 0
     assert B.gtopk_workspace_bytes(2**31, 2**30 + 1, 2) == 0
+
+
+def test_argument_errors_timed_probe():
+    lib = B.load()
+    ws = B.gtopk_workspace_bytes(1000, 10, 2)
+    assert lib.gtopk_step_timed(FAKE, FAKE, 1000, 1000, 2, 10, FAKE, FAKE, FAKE, FAKE, FAKE, ws,
+                                None, None) == B.GTOPK_EINVAL
+    ev = (ctypes.c_void_p * 6)(1, 2, 3, 0, 5, 6)               # one NULL handle
+    assert lib.gtopk_step_timed(FAKE, FAKE, 1000, 1000, 2, 10, FAKE, FAKE, FAKE, FAKE, FAKE, ws,
+                                None, ev) == B.GTOPK_EINVAL
+    pr = lambda **kw: lib.gtopk_probe_stream(kw.get("a", FAKE), FAKE, kw.get("n", 32768),
+                                             kw.get("mode", 0), kw.get("sink", FAKE), None)
+    assert pr(a=None) == B.GTOPK_EINVAL
+    assert pr(n=1000) == B.GTOPK_EINVAL                         # not a multiple of 32768
+    assert pr(mode=2) == B.GTOPK_EINVAL
+    assert pr(mode=1, sink=None) == B.GTOPK_EINVAL
+    assert pr(a=ODD) == B.GTOPK_EALIGN
+
+
+def test_debug_plan_describes_the_sampler():
+    plan = B.gtopk_debug_plan(25_557_032, 25_557, 32)
+    assert plan["tile_len"] == 64 and plan["n_tiles"] >= 4096
+    assert (plan["n_tiles"] - 1) * plan["tile_stride"] < 25_557_032 <= plan["n_tiles"] * plan["tile_stride"]
+    assert plan["tile_stride"] >= plan["tile_len"]
+    assert 256 <= plan["target"] < plan["n_tiles"] * plan["tile_len"]
+    assert 25_557 < plan["capacity"] <= 25_557_032
+    # a short row is sampled whole: the "sample" is an exact count
+    small = B.gtopk_debug_plan(5000, 50, 2)
+    assert small["tile_stride"] == small["tile_len"] and small["target"] == 50
+    with pytest.raises(B.GtopkError):
+        B.gtopk_debug_plan(100, 0, 2)
