@@ -133,6 +133,27 @@ int gtopk_step(const float* grad, float* residual, int64_t m, int64_t stride,
                void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * gtopk_step for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The workspace
+ * is a device array of GTOPK_STATIC_WORKSPACE_BYTES that is part of the library's code
+ * object (every GPU the process uses holds one copy until the process ends); the call
+ * allocates and frees nothing.  Arguments and results are those of gtopk_step.
+ *   - GTOPK_EWORKSPACE if gtopk_workspace_bytes(m, k, P) exceeds
+ *     GTOPK_STATIC_WORKSPACE_BYTES (nothing is enqueued); the two small configurations
+ *     of the benchmark set (m = 65,536 / P = 4 / k = 66 and m = 269,722 / P = 8 / k = 270)
+ *     fit, the large ones do not - use gtopk_step with a caller-owned workspace there.
+ *   - All calls on one GPU share that GPU's array: two calls that overlap in time on one
+ *     GPU (different streams without an event between them, or different threads) race.
+ *     Calls on one stream are ordered and safe; the array needs no clearing between them.
+ *   - The array's address is looked up on the first call on each device, with that device
+ *     current; GTOPK_EHIP if the lookup fails.
+ */
+#define GTOPK_STATIC_WORKSPACE_BYTES (16u << 20)
+int gtopk_step_static(const float* grad, float* residual, int64_t m, int64_t stride,
+                      int32_t P, int32_t k, uint32_t* g_idx, float* g_val,
+                      uint32_t* loc_idx, float* loc_val, void* stream);
+
+/*
  * Model update, Algorithm 4 line 11: W_i = W_{i-1} - eta * G~_i, applied at the k entries
  * of the global set (every other entry of G~_i is zero): for each of `copies` replicas
  * of the weights (row c starts at weights + c*stride, m floats; in the paper every

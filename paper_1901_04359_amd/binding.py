@@ -19,6 +19,7 @@ _lib: Optional[ctypes.CDLL] = None
 EXPORTS = (
     "gtopk_status_string", "gtopk_workspace_bytes", "gtopk_merge_workspace_bytes",
     "gtopk_local_select", "gtopk_merge", "gtopk_tree", "gtopk_residual_restore", "gtopk_step",
+    "gtopk_step_static",
     "gtopk_apply_update", "gtopk_dense_mask",
     "gtopk_allreduce_workspace_bytes", "gtopk_topk_allreduce", "gtopk_dense_topk",
     "gtopk_step_timed", "gtopk_probe_stream", "gtopk_debug_candidate_counts", "gtopk_debug_plan",
@@ -65,6 +66,8 @@ def load() -> ctypes.CDLL:
     lib.gtopk_residual_restore.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp]
     lib.gtopk_step.restype = c.c_int
     lib.gtopk_step.argtypes = [vp, vp, i64, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.gtopk_step_static.restype = c.c_int
+    lib.gtopk_step_static.argtypes = [vp, vp, i64, i64, i32, i32, vp, vp, vp, vp, vp]
     lib.gtopk_apply_update.restype = c.c_int
     lib.gtopk_apply_update.argtypes = [vp, i64, i64, i32, i32, vp, vp, c.c_float, vp]
     lib.gtopk_dense_mask.restype = c.c_int
@@ -217,6 +220,25 @@ def gtopk_step(grad, residual, k: int, g_idx, g_val, loc_idx, loc_val, ws) -> No
         _ptr(loc_val, torch.float32, "loc_val", allow_none=True),
         _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream())
     _check(rc, "gtopk_step")
+
+
+STATIC_WORKSPACE_BYTES = 16 << 20
+
+
+def gtopk_step_static(grad, residual, k: int, g_idx, g_val, loc_idx, loc_val) -> None:
+    """gtopk_step on the library's own static workspace (no allocation anywhere)."""
+    torch = _torch()
+    m, stride = _rows(residual, "residual")
+    mg, sg = _rows(grad, "grad")
+    P = residual.shape[0]
+    if (mg, grad.shape[0]) != (m, P) or (P > 1 and sg != stride):
+        raise ValueError("grad and residual must have the same shape and row stride")
+    rc = load().gtopk_step_static(
+        _ptr(grad, torch.float32, "grad"), _ptr(residual, torch.float32, "residual"),
+        m, stride, P, k, _ptr(g_idx, torch.int32, "g_idx"), _ptr(g_val, torch.float32, "g_val"),
+        _ptr(loc_idx, torch.int32, "loc_idx", allow_none=True),
+        _ptr(loc_val, torch.float32, "loc_val", allow_none=True), _stream())
+    _check(rc, "gtopk_step_static")
 
 
 def gtopk_apply_update(weights, k: int, g_idx, g_val, lr: float) -> None:

@@ -21,6 +21,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "gtopk.h"
 #include "common.hip.h"
 #include "stream_pass.hip.h"
@@ -600,6 +602,53 @@ int gtopk_step(const float* grad, float* residual, int64_t m, int64_t stride, in
                size_t ws_bytes, void* stream) {
     return step_impl(grad, residual, m, stride, P, k, g_idx, g_val, loc_idx, loc_val, ws, ws_bytes,
                      stream, nullptr);
+}
+
+// ---------------------------------------------------------------------------------
+// gtopk_step for callers that cannot allocate: the workspace is a file-scope device array
+// ---------------------------------------------------------------------------------
+}  // extern "C"
+
+// Every GPU the library runs on holds its own copy of this array until the process ends.
+// In host code the name is only a handle for hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) unsigned char scratch[GTOPK_STATIC_WORKSPACE_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};     // device address of `scratch` on each device, once known
+
+// device address of `scratch` on the current device (looked up once per device), or NULL
+void* scratch_on_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace
+
+extern "C" {
+
+int gtopk_step_static(const float* grad, float* residual, int64_t m, int64_t stride, int32_t P,
+                      int32_t k, uint32_t* g_idx, float* g_val, uint32_t* loc_idx, float* loc_val,
+                      void* stream) {
+    if (!sizes_ok(m, k, P)) return GTOPK_EINVAL;
+    const size_t need = carve_step(nullptr, m, (uint32_t)k, (uint32_t)P).bytes;
+    if (need > (size_t)GTOPK_STATIC_WORKSPACE_BYTES) return GTOPK_EWORKSPACE;
+    void* ws = scratch_on_current_device();
+    if (!ws) return GTOPK_EHIP;
+    // everything the step needs zeroed is cleared by its first kernel, so what the
+    // previous call left in the array does not matter
+    return step_impl(grad, residual, m, stride, P, k, g_idx, g_val, loc_idx, loc_val, ws,
+                     (size_t)GTOPK_STATIC_WORKSPACE_BYTES, stream, nullptr);
 }
 
 int gtopk_step_timed(const float* grad, float* residual, int64_t m, int64_t stride, int32_t P,

@@ -190,3 +190,16 @@ def test_debug_plan_describes_the_sampler():
     assert small["tile_stride"] == small["tile_len"] and small["target"] == 50
     with pytest.raises(B.GtopkError):
         B.gtopk_debug_plan(100, 0, 2)
+
+
+def test_argument_errors_step_static():
+    lib = B.load()
+    st = lambda **kw: lib.gtopk_step_static(
+        kw.get("grad", FAKE), FAKE, kw.get("m", 1000), kw.get("stride", 1000), kw.get("P", 2),
+        kw.get("k", 10), FAKE, FAKE, FAKE, FAKE, None)
+    assert st(P=3) == B.GTOPK_EINVAL
+    assert st(k=0) == B.GTOPK_EINVAL
+    # a problem whose workspace exceeds the library's static array is refused on the host
+    assert B.gtopk_workspace_bytes(25_557_032, 25_557, 32) > B.STATIC_WORKSPACE_BYTES
+    assert st(m=25_557_032, stride=25_557_032, P=32, k=25_557) == B.GTOPK_EWORKSPACE
+    assert B.gtopk_workspace_bytes(269_722, 270, 8) <= B.STATIC_WORKSPACE_BYTES
