@@ -54,13 +54,16 @@ struct Carver {
     }
 };
 
-// hist, list_cnt and grp_gt are carved back to back so that one clear covers them
+// hist .. hist_dense are carved back to back so that one clear covers them
 SelState carve_select(Carver& c, size_t sets, uint32_t list_cap, uint32_t maxgroups,
                       bool with_dense_hist = false) {
     SelState s;
     s.hist = c.take<uint32_t>(sets * kHistBins);
     s.list_cnt = c.take<uint32_t>(sets);
     s.grp_gt = c.take<uint32_t>(sets * maxgroups);
+    s.grp_in = c.take<uint32_t>(sets * maxgroups);
+    s.bin_hi = c.take<uint32_t>(sets);
+    s.bin_lo_inv = c.take<uint32_t>(sets);
     s.hist_dense = with_dense_hist ? c.take<uint32_t>(sets * kHistBins) : nullptr;   // cleared as well
     s.d1 = c.take<uint32_t>(sets);
     s.krem = c.take<uint32_t>(sets);
@@ -74,10 +77,10 @@ SelState carve_select(Carver& c, size_t sets, uint32_t list_cap, uint32_t maxgro
     s.maxgroups = maxgroups;
     return s;
 }
-// words from s.hist to the end of s.grp_gt / s.hist_dense (padding included)
+// words from s.hist to the end of s.bin_lo_inv / s.hist_dense (padding included)
 inline size_t select_clear_words(const SelState& s) { return (size_t)(s.d1 - s.hist); }
 
-// A second copy of the three arrays that must be zero when a select starts; everything
+// A second copy of the arrays that must be zero when a select starts; everything
 // else is shared with `base`.  Two such states alternate between the rounds of the tree,
 // so that one can be cleared while the other is in use.
 SelState carve_select_alt(Carver& c, const SelState& base, size_t sets, size_t* clear_words) {
@@ -85,6 +88,9 @@ SelState carve_select_alt(Carver& c, const SelState& base, size_t sets, size_t* 
     s.hist = c.take<uint32_t>(sets * kHistBins);
     s.list_cnt = c.take<uint32_t>(sets);
     s.grp_gt = c.take<uint32_t>(sets * base.maxgroups);
+    s.grp_in = c.take<uint32_t>(sets * base.maxgroups);
+    s.bin_hi = c.take<uint32_t>(sets);
+    s.bin_lo_inv = c.take<uint32_t>(sets);
     uint32_t* end = c.take<uint32_t>(1);
     *clear_words = base.hist ? (size_t)(end - s.hist) : 0;
     return s;
@@ -151,7 +157,7 @@ struct StepWs {
     // local select
     uint32_t* samp_hist;   // [P][16384]    } cleared together
     uint32_t* cand_count;  // [P]           }
-    uint32_t* tspec;       // [P]
+    uint32_t* tspec;       // [P] speculative threshold of the streaming pass
     uint32_t* cand_idx;    // [P][cap] candidates as the streaming pass left them (runs)
     float* cand_val;
     uint2* run_table;      // [P][nchunks]
@@ -159,7 +165,9 @@ struct StepWs {
     uint32_t* ord_idx;     // [P][cap] candidates in index order
     float* ord_val;
     SelState sel;          // P sets
-    uint32_t cap, nchunks, Lc, Ld;
+    uint32_t cap, nchunks;
+    uint32_t Lc, gcand;    // candidate list: slots per group, groups
+    uint32_t Ld, gdense;   // dense row: slots per group, groups
     // tree
     MergeWs mrg;           // P/2 pairs
     uint32_t* x_idx;       // [P/2][k] ping
@@ -180,6 +188,9 @@ uint32_t cand_capacity(int64_t m, uint32_t k) {
     return (uint32_t)cap;
 }
 
+struct SamplePlan { uint32_t tile_stride, n_tiles, target; };
+SamplePlan plan_sample(int64_t m, uint32_t k);
+
 StepWs carve_step(void* ws, int64_t m, uint32_t k, uint32_t P) {
     Carver c{reinterpret_cast<char*>(ws)};
     StepWs s;
@@ -191,12 +202,12 @@ StepWs carve_step(void* ws, int64_t m, uint32_t k, uint32_t P) {
         s.Lc = group_slots_for(s.cap, g);
         const uint32_t lmin = group_slots_for(s.cap, kMaxGroups);
         if (s.Lc > 8192u) s.Lc = lmin > 8192u ? lmin : 8192u;
+        s.gcand = ceil_div(s.cap, s.Lc);
     }
-    const uint32_t gcand = ceil_div(s.cap, s.Lc);
-    // dense rows are a fallback when there are several workers: coarse groups keep the
-    // grids small; with one set (also the dense top-k) they get as many groups as any set
-    const uint32_t gdense = P == 1 ? (uint32_t)kMaxGroups : 256u;
-    s.Ld = group_slots_for((uint64_t)m, gcand > gdense ? gcand : gdense);
+    // dense rows (a worker whose candidate list cannot be used; the dense top-k)
+    s.gdense = P == 1 ? (uint32_t)kMaxGroups : 1024u;
+    s.Ld = group_slots_for((uint64_t)m, s.gdense);
+    s.gdense = ceil_div((uint64_t)m, s.Ld);
     s.samp_hist = c.take<uint32_t>((size_t)P * kSampleBins);
     s.cand_count = c.take<uint32_t>(P);
     s.tspec = c.take<uint32_t>(P);
@@ -206,8 +217,7 @@ StepWs carve_step(void* ws, int64_t m, uint32_t k, uint32_t P) {
     s.run_off = c.take<uint32_t>((size_t)P * s.nchunks);
     s.ord_idx = c.take<uint32_t>((size_t)P * s.cap);
     s.ord_val = c.take<float>((size_t)P * s.cap);
-    const uint32_t gc = ceil_div(s.cap, s.Lc), gd = ceil_div((uint64_t)m, s.Ld);
-    s.sel = carve_select(c, P, s.cap, gc > gd ? gc : gd, /*with_dense_hist=*/true);
+    s.sel = carve_select(c, P, s.cap, s.gcand > s.gdense ? s.gcand : s.gdense, /*with_dense_hist=*/true);
     const size_t pairs = P > 1 ? P / 2 : 1;
     s.mrg = carve_merge(c, k, pairs);
     s.x_idx = c.take<uint32_t>(pairs * k);
@@ -237,41 +247,55 @@ void mark_stage(int i, void* const* events, hipStream_t st) {
     if (events) (void)hipEventRecord((hipEvent_t)events[i], st);
 }
 
-void zero_async(hipStream_t st, uint32_t* p0, size_t n0, uint32_t* p1 = nullptr, size_t n1 = 0,
-                uint32_t* p2 = nullptr, size_t n2 = 0, uint32_t* p3 = nullptr, size_t n3 = 0,
-                uint32_t* p4 = nullptr, size_t n4 = 0) {
-    ZeroJob job{{p0, p1, p2, p3, p4, nullptr}, {n0, n1, n2, n3, n4, 0}};
+ZeroJob zero_job(uint32_t* p0 = nullptr, size_t n0 = 0, uint32_t* p1 = nullptr, size_t n1 = 0,
+                 uint32_t* p2 = nullptr, size_t n2 = 0, uint32_t* p3 = nullptr, size_t n3 = 0,
+                 uint32_t* p4 = nullptr, size_t n4 = 0) {
+    return ZeroJob{{p0, p1, p2, p3, p4, nullptr}, {n0, n1, n2, n3, n4, 0}};
+}
+
+void zero_async(hipStream_t st, const ZeroJob& job) {
     size_t n = 0;
     for (int a = 0; a < kZeroSlots; ++a) n = job.n[a] > n ? job.n[a] : n;
+    if (n == 0) return;
     uint32_t blocks = (uint32_t)((n + 1023) / 1024 > 1024 ? 1024 : (n + 1023) / 1024);
     hipLaunchKernelGGL(k_zero_u32, dim3(blocks ? blocks : 1), dim3(256), 0, st, job);
 }
 
-// histogram + bucket + emit over `sets` sets of at most nphys_max slots each
+// how a batch of sets is walked and emitted
+struct SelGrid {
+    uint32_t sets;
+    uint32_t walk_blocks;   // blocks per set of k_bucket
+    uint32_t groups;        // blocks per set of k_emit (= emit groups, at most)
+    uint64_t nphys_max;     // slots of a set's list, at most (sizes k_hist)
+    bool own_finish;        // k_finish once per set instead of a finish in every emit block
+};
+
+// histogram + bucket + emit
 template <class Src, bool DIVIDE>
-void run_select(const Src& src, const SelState& ss, uint32_t sets, uint32_t groups, uint32_t k,
-                uint64_t nphys_max, uint32_t* out_idx, float* out_val, int64_t out_stride,
-                float divisor, uint32_t* gbits, hipStream_t st, bool with_hist = true) {
+void run_select(const Src& src, const SelState& ss, const SelGrid& gr, uint32_t k, uint32_t* out_idx,
+                float* out_val, int64_t out_stride, float divisor, uint32_t* gbits, hipStream_t st,
+                bool with_hist = true) {
     // few blocks per set (a popular bin takes one same-address atomic per block): 4 slots per
     // thread up to 32 blocks, then 32 blocks with more slots per thread, then 32 slots per
     // thread up to 256 blocks (swept at k = 255,570 .. 6.4 M)
-    uint32_t hb = ceil_div(nphys_max, 4 * kHistBlock);
+    uint32_t hb = ceil_div(gr.nphys_max, 4 * kHistBlock);
     if (hb > 32) {
-        hb = ceil_div(nphys_max, 32 * kHistBlock);
+        hb = ceil_div(gr.nphys_max, 32 * kHistBlock);
         hb = hb < 32 ? 32 : (hb > 256 ? 256 : hb);
     }
+    if (hb < 1) hb = 1;
     if (with_hist)
-        hipLaunchKernelGGL((k_hist<Src>), dim3(hb + (Src::kRunScan ? 1 : 0), sets), dim3(kHistBlock), 0,
+        hipLaunchKernelGGL((k_hist<Src>), dim3(hb + (Src::kRunScan ? 1 : 0), gr.sets), dim3(kHistBlock), 0,
                            st, src, ss, hb);
-    hipLaunchKernelGGL((k_bucket<Src>), dim3(groups, sets), dim3(kBlock), 0, st, src, ss, k);
+    hipLaunchKernelGGL((k_bucket<Src>), dim3(gr.walk_blocks, gr.sets), dim3(kBlock), 0, st, src, ss, k);
     // small sets: every block of the emit finishes the select itself (the list of keys it
     // needs for that is short); large sets: once per set, in a kernel of its own
-    if (nphys_max <= kInlineFinishMax) {
-        hipLaunchKernelGGL((k_emit<Src, DIVIDE, true>), dim3(groups, sets), dim3(kBlock), 0, st,
+    if (!gr.own_finish) {
+        hipLaunchKernelGGL((k_emit<Src, DIVIDE, true>), dim3(gr.groups, gr.sets), dim3(kBlock), 0, st,
                            src, ss, k, out_idx, out_val, out_stride, divisor, gbits);
     } else {
-        hipLaunchKernelGGL((k_finish<Src>), dim3(sets), dim3(1024), 0, st, src, ss);
-        hipLaunchKernelGGL((k_emit<Src, DIVIDE, false>), dim3(groups, sets), dim3(kBlock), 0, st,
+        hipLaunchKernelGGL((k_finish<Src>), dim3(gr.sets), dim3(1024), 0, st, src, ss);
+        hipLaunchKernelGGL((k_emit<Src, DIVIDE, false>), dim3(gr.groups, gr.sets), dim3(kBlock), 0, st,
                            src, ss, k, out_idx, out_val, out_stride, divisor, gbits);
     }
 }
@@ -282,8 +306,6 @@ void run_select(const Src& src, const SelState& ss, uint32_t sets, uint32_t grou
 // expected sample rank of the k-th key plus 5.5 standard deviations, so that the
 // candidate list holds at least k entries except with probability ~1e-8 per worker
 // (and then that worker is merely selected from its dense row).
-struct SamplePlan { uint32_t tile_stride, n_tiles, target; };
-
 SamplePlan plan_sample(int64_t m, uint32_t k) {
     const double kSampleMean = 256.0;        // expected sample rank of the k-th key, at least
     const double kMinTiles = 4096.0;         // spread: a layer of 1 % of the row still gets ~40 tiles
@@ -329,12 +351,31 @@ bool pass_histograms(int64_t m, uint32_t k) {
 // `zero_rows`: store +0.0 at the selected entries (the stand-alone call); gtopk_step
 // passes false and settles the rows in k_restore_fused.  `pre_cleared`: the caller has
 // already cleared this call's counters and histograms.
+CandSrc cand_source(const float* rows, int64_t stride, int64_t m, uint32_t k, const StepWs& w,
+                    bool producer_hist, bool no_bounds) {
+    return CandSrc{rows, stride, (uint32_t)m, k, w.cap, w.nchunks, w.Lc, w.Ld,
+                   w.cand_idx, w.cand_val, w.cand_count, w.tspec, w.run_table, w.run_off,
+                   w.ord_idx, w.ord_val, producer_hist, no_bounds};
+}
+
+// The grids are sized for the candidate lists.  A worker that is selected from its dense
+// row has more groups than that; its blocks take several each.  Every emit block finishes
+// the select itself: the list of in-bin keys is short.
+SelGrid local_grid(const StepWs& w, uint32_t P) {
+    const uint32_t gd = w.gdense < 256u ? w.gdense : 256u;
+    const uint32_t gx = w.gcand > gd ? w.gcand : gd;
+    return SelGrid{P, gx, gx, (uint64_t)w.cap, false};
+}
+
+// `zero_rows`: store +0.0 at the selected entries (the stand-alone call); gtopk_step
+// passes false and settles the rows in k_restore_fused.  `pre_cleared`: the caller has
+// already cleared this call's counters and histograms.
 int do_local_select(const float* grad, float* residual, int64_t m, int64_t stride, uint32_t P,
                     uint32_t k, uint32_t* out_idx, float* out_val, const StepWs& w, bool zero_rows,
                     bool pre_cleared, hipStream_t st, void* const* events = nullptr) {
     if (!pre_cleared)
-        zero_async(st, w.samp_hist, (size_t)(w.tspec - w.samp_hist), w.sel.hist,
-                   select_clear_words(w.sel));
+        zero_async(st, zero_job(w.samp_hist, (size_t)(w.tspec - w.samp_hist), w.sel.hist,
+                                select_clear_words(w.sel)));
 
     const SamplePlan sp = plan_sample(m, k);
     uint32_t sblocks = ceil_div(sp.n_tiles, (kSampleBlock / kSampleTile) * 8);
@@ -359,11 +400,11 @@ int do_local_select(const float* grad, float* residual, int64_t m, int64_t strid
                            w.cand_count, w.run_table, w.nchunks, w.sel.hist);
     mark_stage(2, events, st);
 
-    CandSrc src{residual, stride, (uint32_t)m, k, w.cap, w.nchunks, w.Lc, w.Ld,
-                w.cand_idx, w.cand_val, w.cand_count, w.tspec, w.run_table, w.run_off,
-                w.ord_idx, w.ord_val, producer_hist};
-    run_select<CandSrc, false>(src, w.sel, P, w.sel.maxgroups, k, w.cap, out_idx, out_val, (int64_t)k,
-                               1.0f, nullptr, st);
+    const CandSrc src = cand_source(residual, stride, m, k, w, producer_hist, false);
+    // the histogram kernel always runs: where the pass has counted its candidates it serves
+    // only the workers that came back with fewer than k of them
+    run_select<CandSrc, false>(src, w.sel, local_grid(w, P), k, out_idx, out_val, (int64_t)k, 1.0f,
+                               nullptr, st);
     // a kernel of its own: while the select runs, a dense row may still be read as a whole
     if (zero_rows)
         hipLaunchKernelGGL(k_zero_selected, dim3(ceil_div(k, kBlock), P), dim3(kBlock), 0, st, out_idx,
@@ -418,8 +459,9 @@ void do_merge_batch(const uint32_t* a_idx, const float* a_val, const uint32_t* b
                            dim3(kUnionHistBlock), 0, st, a_idx, a_val, b_idx, b_val, k, in_stride, w.m_idx,
                            w.m_val, w.m_stride, (const uint32_t*)w.cuts, zp, zw, src, ss);
     }
-    run_select<MergedSrc, DIVIDE>(src, ss, batch, groups, k, 2ull * k, out_idx, out_val, out_stride,
-                                  divisor, gbits, st, /*with_hist=*/false);
+    run_select<MergedSrc, DIVIDE>(src, ss, SelGrid{batch, groups, groups, 2ull * k, 2ull * k > kInlineFinishMax},
+                                  k, out_idx, out_val, out_stride, divisor, gbits, st,
+                                  /*with_hist=*/false);
 }
 
 // loc_min: the smallest key of each of the P input sets (the local selection's T), or NULL
@@ -434,8 +476,8 @@ int do_tree(const uint32_t* loc_idx, const float* loc_val, const uint32_t* loc_m
         return launch_status();
     }
     if (!pre_cleared)
-        zero_async(st, w.mrg.sel.hist, select_clear_words(w.mrg.sel), w.mrg.sel_alt.hist,
-                   w.mrg.alt_clear_words, w.mrg.inv_min, P);
+        zero_async(st, zero_job(w.mrg.sel.hist, select_clear_words(w.mrg.sel), w.mrg.sel_alt.hist,
+                                w.mrg.alt_clear_words, w.mrg.inv_min, P));
     bool inverted = false;
     if (!loc_min) {
         // sets from the caller: find their smallest keys, the first round's lower bounds
@@ -527,7 +569,7 @@ int gtopk_merge(const uint32_t* a_idx, const float* a_val, const uint32_t* b_idx
     const MergeWs w = carve_merge(c, (uint32_t)k, (size_t)batch);
     if (ws_bytes < w.bytes) return GTOPK_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
-    zero_async(st, w.sel.hist, select_clear_words(w.sel), w.inv_min, 2 * (size_t)batch);
+    zero_async(st, zero_job(w.sel.hist, select_clear_words(w.sel), w.inv_min, 2 * (size_t)batch));
     hipLaunchKernelGGL(k_set_min_key, dim3(min_key_blocks((uint32_t)k), 2 * (uint32_t)batch),
                        dim3(kBlock), 0, st, a_val, b_val, in_stride, (uint32_t)k, w.inv_min);
     do_merge_batch<false>(a_idx, a_val, b_idx, b_val, (uint32_t)k, (uint32_t)batch, in_stride,
@@ -580,9 +622,9 @@ static int step_impl(const float* grad, float* residual, int64_t m, int64_t stri
     mark_stage(0, events, st);
     // one clear for everything this step needs zeroed: the sampler's histograms and the
     // candidate counters; both selects' histograms and tickets; the global-set bitmap
-    zero_async(st, w.samp_hist, (size_t)(w.tspec - w.samp_hist), w.sel.hist,
-               select_clear_words(w.sel), w.mrg.sel.hist, select_clear_words(w.mrg.sel),
-               w.mrg.sel_alt.hist, w.mrg.alt_clear_words, w.gbits, w.gbits_words);
+    zero_async(st, zero_job(w.samp_hist, (size_t)(w.tspec - w.samp_hist), w.sel.hist,
+                            select_clear_words(w.sel), w.mrg.sel.hist, select_clear_words(w.mrg.sel),
+                            w.mrg.sel_alt.hist, w.mrg.alt_clear_words, w.gbits, w.gbits_words));
     int rc = do_local_select(grad, residual, m, stride, (uint32_t)P, (uint32_t)k, li, lv, w, false,
                              true, st, events);
     if (rc != GTOPK_OK) return rc;
@@ -721,13 +763,12 @@ int gtopk_dense_topk(const float* dense, int64_t m, int32_t k, uint32_t* g_idx, 
     if (ws_bytes < w.bytes) return GTOPK_EWORKSPACE;
     hipStream_t st = (hipStream_t)stream;
     // a candidate count of zero makes the select read the dense row itself
-    zero_async(st, w.samp_hist, (size_t)(w.tspec - w.samp_hist), w.sel.hist,
-               select_clear_words(w.sel));
-    CandSrc src{dense, m, (uint32_t)m, (uint32_t)k, w.cap, w.nchunks, w.Lc, w.Ld,
-                w.cand_idx, w.cand_val, w.cand_count, w.tspec, w.run_table, w.run_off,
-                w.ord_idx, w.ord_val, false};
-    run_select<CandSrc, false>(src, w.sel, 1, w.sel.maxgroups, (uint32_t)k, (uint64_t)m, g_idx, g_val,
-                               (int64_t)k, 1.0f, nullptr, st);
+    zero_async(st, zero_job(w.samp_hist, (size_t)(w.tspec - w.samp_hist), w.sel.hist, select_clear_words(w.sel)));
+    const CandSrc src = cand_source(dense, m, m, (uint32_t)k, w, false, /*no_bounds=*/true);
+    // one set, always read as a dense row: the grids follow the row's groups; without a
+    // lower bound of the k-th key the list can be long, so large rows are finished once
+    const SelGrid gr{1, w.gdense, w.gdense, (uint64_t)m, m > ((int64_t)1 << 20)};
+    run_select<CandSrc, false>(src, w.sel, gr, (uint32_t)k, g_idx, g_val, (int64_t)k, 1.0f, nullptr, st);
     return launch_status();
 }
 

@@ -27,6 +27,9 @@ struct SelState {
     uint32_t* hist;       // [sets][4096]
     uint32_t* list_cnt;   // [sets]
     uint32_t* grp_gt;     // [sets][maxgroups] entries of the group above bin d1
+    uint32_t* grp_in;     // [sets][maxgroups] entries of the group inside bin d1
+    uint32_t* bin_hi;     // [sets] largest key seen inside bin d1
+    uint32_t* bin_lo_inv; // [sets] 0x7fffffff - smallest key seen inside bin d1
     uint32_t* hist_dense; // [sets][4096] or NULL: the histogram of a set that is read as a dense
                           //   row although the producer of its candidates has already filled `hist`
     // --------------------------------------------------------------------------------
@@ -46,11 +49,18 @@ struct SelState {
 // ---------------------------------------------------------------------------------
 // A source presents, per set s, nphys(s) "physical" slots in storage order and the same
 // items in "logical" = index order, cut into groups of group_slots() consecutive logical
-// positions.  logical() maps a physical slot to its logical position; kIdentity says the
-// two orders coincide.  fetch_*() return false for a slot that holds nothing.
+// positions.  k_hist and k_bucket walk the physical slots; logical() maps a physical slot
+// to its logical position; kIdentity says the two orders coincide.  fetch_ord() reads an
+// item by logical position (for the ordered emit).  fetch_*() return false for a slot that
+// holds nothing.
 
 // Local select: the candidate list of worker s, or - when the speculative threshold
 // left fewer than k candidates or more than the list holds - the worker's dense row.
+// The streaming pass leaves the candidates as one run per 32768-element chunk of the row,
+// in index order inside a run, the runs in the order in which the blocks reserved them
+// (run_table[w][chunk] = first slot, count); one extra block of k_hist scans the run
+// counts (run_off[w][chunk] = first logical position of the run), and k_bucket's walk
+// copies the candidates into index order on the side.
 struct CandSrc {
     static constexpr bool kIdentity = false;
     static constexpr bool kRunScan = true;
@@ -67,15 +77,35 @@ struct CandSrc {
     uint32_t* ord_idx;                    // [P][cap] candidates in index order
     float* ord_val;
     bool producer_hist;                   // the streaming pass has histogrammed the candidates
+    bool no_bounds;                       // dense rows without any threshold (the dense top-k)
 
     __device__ bool dense(int s) const {
         const uint32_t c = cand_count[s];
         return c < k || c > cap;
     }
+    // A dense row with MORE candidates than the list holds: the k-th key is at or above the
+    // speculative threshold, and if the pass has histogrammed its candidates, that
+    // histogram (which counts every candidate, stored or not) is the row's.
+    __device__ bool overfull(int s) const { return !no_bounds && cand_count[s] > cap; }
+    __device__ bool wants_hist(int s, bool dn) const {
+        return !producer_hist || (dn && !overfull(s));
+    }
+    // Entries of such a row below the speculative threshold cannot be selected (more than k
+    // others lie above it); the select ignores them, as if the row were a candidate list.
+    __device__ uint32_t floor_key(int s, bool dn) const {
+        return (dn && overfull(s)) ? tspec[s] : 0u;
+    }
+    __device__ uint32_t* hist_of(int s, bool dn, const SelState& st) const {
+        return ((producer_hist && dn && !overfull(s)) ? st.hist_dense : st.hist) + (size_t)s * kHistBins;
+    }
     __device__ uint32_t nphys(int s, bool dn) const { return dn ? m : cand_count[s]; }
     __device__ uint32_t group_slots(bool dn) const { return dn ? Ld : Lc; }
+    // Lower bound of the k-th key: the speculative threshold while at least k entries
+    // reached it; for a worker with fewer the k-th key lies below it, and nothing bounds
+    // it from below: plain coarse bins.
     __device__ Digit digit(int s, bool dn, const SelState&) const {
-        return dn ? Digit{0u, (uint32_t)kCoarseShift} : Digit{tspec[s], (uint32_t)kFineShift};
+        if (dn && !overfull(s)) return Digit{0u, (uint32_t)kCoarseShift};
+        return Digit{tspec[s], (uint32_t)kFineShift};
     }
     __device__ bool fetch_phys(int s, bool dn, uint32_t p, uint32_t& idx, uint32_t& bits) const {
         if (dn) {
@@ -95,8 +125,11 @@ struct CandSrc {
         if (dn) return p;
         // the streaming pass cuts a row into chunks at multiples of 32768 of idx + head
         const uint32_t head = (uint32_t)(((int64_t)s * stride) & 3);
-        const size_t r = (size_t)s * nchunks + ((idx + head) >> kChunkLog2);
-        return run_off[r] + (p - run_table[r].x);
+        uint32_t chunk = (idx + head) >> kChunkLog2;
+        if (chunk >= nchunks) chunk = nchunks - 1;       // never for a list the pass wrote
+        const size_t r = (size_t)s * nchunks + chunk;
+        const uint32_t lp = run_off[r] + (p - run_table[r].x);
+        return lp < cap ? lp : cap - 1;                  // likewise
     }
     __device__ void store_ordered(int s, bool dn, uint32_t lp, uint32_t idx, uint32_t bits) const {
         if (!dn) {
@@ -143,8 +176,12 @@ struct MergedSrc {
     uint32_t n, stride, L;       // L slots per group
     const uint32_t* in_min;
     bool inverted;
-    static constexpr bool producer_hist = false;
     __device__ bool dense(int) const { return false; }
+    __device__ uint32_t floor_key(int, bool) const { return 0u; }
+    __device__ bool wants_hist(int, bool) const { return true; }
+    __device__ uint32_t* hist_of(int s, bool, const SelState& st) const {
+        return st.hist + (size_t)s * kHistBins;
+    }
     __device__ uint32_t nphys(int, bool) const { return n; }
     __device__ uint32_t group_slots(bool) const { return L; }
     __device__ Digit digit(int s, bool, const SelState&) const {
@@ -174,35 +211,24 @@ struct MergedSrc {
 // kernel 1: histogram of the first digit
 // ---------------------------------------------------------------------------------
 
-// Few, large blocks per set: a popular bin receives one global atomic per block.  For a
-// source whose runs need ordering, one extra block per set scans the run counts.
-template <class Src>
-__global__ __launch_bounds__(kHistBlock) void k_hist(Src src, SelState st, uint32_t hist_blocks) {
-    __shared__ uint32_t h[kHistBins];
-    __shared__ uint32_t s_wave[kHistBlock / kWave];
-    const int s = blockIdx.y;
-    if (Src::kRunScan && blockIdx.x == hist_blocks) {
-        src.scan_runs(s, s_wave);
-        return;
-    }
-    const bool dn = src.dense(s);
-    if (src.producer_hist && !dn) return;        // block-uniform: this set's histogram exists already
-    for (int b = threadIdx.x; b < kHistBins; b += kHistBlock) h[b] = 0u;
-    __syncthreads();
-    const uint32_t n = src.nphys(s, dn);
-    const Digit dg = src.digit(s, dn, st);
+// Few, large blocks per set: a popular bin receives one global atomic per block.  The grid
+// is sized for the sets' lists; a set that is read as a dense row (far longer) is walked
+// by the same blocks with more loads in flight.
+template <class Src, int BATCH>
+__device__ __forceinline__ void hist_walk(const Src& src, int s, bool dn, const Digit& dg, uint32_t n,
+                                          uint32_t fl, uint32_t hist_blocks, uint32_t* h) {
     const uint64_t step = (uint64_t)hist_blocks * kHistBlock;
-    for (uint64_t p0 = (uint64_t)blockIdx.x * kHistBlock + threadIdx.x; p0 < n; p0 += step * kHistBatch) {
-        uint32_t key[kHistBatch];
-        bool ok[kHistBatch];
+    for (uint64_t p0 = (uint64_t)blockIdx.x * kHistBlock + threadIdx.x; p0 < n; p0 += step * BATCH) {
+        uint32_t key[BATCH];
+        bool ok[BATCH];
 #pragma unroll
-        for (int j = 0; j < kHistBatch; ++j) {
+        for (int j = 0; j < BATCH; ++j) {
             const uint64_t p = p0 + j * step;
             key[j] = 0;
-            ok[j] = p < n && src.fetch_key_phys(s, dn, (uint32_t)p, key[j]);
+            ok[j] = p < n && src.fetch_key_phys(s, dn, (uint32_t)p, key[j]) && key[j] >= fl;
         }
 #pragma unroll
-        for (int j = 0; j < kHistBatch; ++j) {
+        for (int j = 0; j < BATCH; ++j) {
             // a wave whose keys all fall into one bin (rows of zeros, equal values) adds once
             const uint32_t b = dg.bin(key[j]);
             const uint64_t act = __ballot(ok[j]);
@@ -215,8 +241,30 @@ __global__ __launch_bounds__(kHistBlock) void k_hist(Src src, SelState st, uint3
             }
         }
     }
+}
+
+// For a source whose runs need ordering, one extra block per set (the last one of the
+// grid's x dimension) scans the run counts.
+template <class Src>
+__global__ __launch_bounds__(kHistBlock) void k_hist(Src src, SelState st, uint32_t hist_blocks) {
+    __shared__ uint32_t h[kHistBins];
+    __shared__ uint32_t s_wave[kHistBlock / kWave];
+    const int s = blockIdx.y;
+    if (Src::kRunScan && blockIdx.x == hist_blocks) {
+        src.scan_runs(s, s_wave);
+        return;
+    }
+    const bool dn = src.dense(s);
+    if (!src.wants_hist(s, dn)) return;          // block-uniform: this set's histogram exists already
+    for (int b = threadIdx.x; b < kHistBins; b += kHistBlock) h[b] = 0u;
     __syncthreads();
-    uint32_t* out = (src.producer_hist ? st.hist_dense : st.hist) + (size_t)s * kHistBins;
+    const uint32_t n = src.nphys(s, dn);
+    const Digit dg = src.digit(s, dn, st);
+    const uint32_t fl = src.floor_key(s, dn);
+    if (dn) hist_walk<Src, 8>(src, s, dn, dg, n, fl, hist_blocks, h);
+    else hist_walk<Src, kHistBatch>(src, s, dn, dg, n, fl, hist_blocks, h);
+    __syncthreads();
+    uint32_t* out = src.hist_of(s, dn, st);
     for (int b = threadIdx.x; b < kHistBins; b += kHistBlock) {
         const uint32_t c = h[b];
         if (c) atomicAdd(&out[b], c);
@@ -224,12 +272,20 @@ __global__ __launch_bounds__(kHistBlock) void k_hist(Src src, SelState st, uint3
 }
 
 // ---------------------------------------------------------------------------------
-// kernel 2: pick the bin; per group, count keys above it, list keys inside it
+// kernel 2: pick the bin; count keys above it per group, list keys inside it
 // ---------------------------------------------------------------------------------
 
-// Block g of set s walks the physical slots [g*L, (g+1)*L).
+// Block b of set s walks the physical slots [b*L, (b+1)*L), L = group_slots(); a set with
+// more such segments than the grid has blocks (a dense row) is walked in several turns.
+// For a dense row, whose list can overflow, every group's count of in-bin keys and the
+// row's smallest and largest in-bin key are recorded besides the list: if the list
+// overflows although all in-bin keys are equal (rows of equal magnitudes), the finish needs
+// nothing more than those.
+// ---- the plain walk ----
+// The walk of a set that is NOT read as a dense row: one segment per block, nothing that
+// only a dense row needs.
 template <class Src>
-__global__ __launch_bounds__(kBlock) void k_bucket(Src src, SelState st, uint32_t k) {
+__device__ __forceinline__ void bucket_fast(const Src& src, const SelState& st, uint32_t k) {
     __shared__ uint32_t s_wave[kBlock / kWave];
     __shared__ uint32_t s_out[3];
     __shared__ uint32_t s_gt[kBlock / kWave];
@@ -241,7 +297,7 @@ __global__ __launch_bounds__(kBlock) void k_bucket(Src src, SelState st, uint32_
     const int s = blockIdx.y;
     const uint32_t g = blockIdx.x;
     if (threadIdx.x == 0) s_nstash = 0u;       // visible after the barrier inside the pick
-    const bool dn = src.dense(s);
+    constexpr bool dn = false;
     const uint32_t n = src.nphys(s, dn);
     const uint32_t L = src.group_slots(dn);
     const uint64_t first = (uint64_t)g * L;
@@ -269,7 +325,7 @@ __global__ __launch_bounds__(kBlock) void k_bucket(Src src, SelState st, uint32_
     // every block picks the bin of the k-th key from the set's histogram
     {
         constexpr int kPer = kHistBins / kBlock;      // thread t owns 16 consecutive bins
-        const uint32_t* hist = ((src.producer_hist && dn) ? st.hist_dense : st.hist) + (size_t)s * kHistBins;
+        const uint32_t* hist = src.hist_of(s, dn, st);
         uint32_t loc[kPer];
 #pragma unroll
         for (int j = 0; j < kPer; ++j) loc[j] = hist[threadIdx.x * kPer + j];
@@ -347,6 +403,214 @@ __global__ __launch_bounds__(kBlock) void k_bucket(Src src, SelState st, uint32_
     }
 }
 
+// ---- the general walk ----
+template <class Src>
+__device__ __forceinline__ void bucket_general(const Src& src, const SelState& st, uint32_t k) {
+    __shared__ uint32_t s_wave[kBlock / kWave];
+    __shared__ uint32_t s_out[3];
+    __shared__ uint32_t s_gt[kBlock / kWave];
+    __shared__ uint32_t s_in[kBlock / kWave];
+    __shared__ uint32_t s_base;
+    constexpr int kStash = 1024;
+    __shared__ uint2 s_stash[kStash];
+    __shared__ uint32_t s_nstash;
+    __shared__ uint32_t s_hi, s_lo_inv;
+    const int s = blockIdx.y;
+    if (threadIdx.x == 0) { s_nstash = 0u; s_hi = 0u; s_lo_inv = 0u; }   // visible after the barrier inside the pick
+    const bool dn = src.dense(s);
+    const uint32_t n = src.nphys(s, dn);
+    const uint32_t L = src.group_slots(dn);
+    if ((uint64_t)blockIdx.x * L >= n) return;
+    const Digit dg = src.digit(s, dn, st);
+    const uint32_t fl = src.floor_key(s, dn);
+    // one round of the walk: the block's next kBlock * kBatch slots, their items and groups
+    uint32_t idx[kBatch], bits[kBatch], lp[kBatch], grp[kBatch];
+    bool ok[kBatch];
+    uint32_t g = blockIdx.x;                       // the segment being walked
+    uint32_t end = 0;
+    auto load_round = [&](uint32_t i0) {
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            const uint32_t p = i0 + j * kBlock + threadIdx.x;
+            idx[j] = 0; bits[j] = 0;
+            ok[j] = p < end && src.fetch_phys(s, dn, p, idx[j], bits[j]) && (bits[j] & kAbs) >= fl;
+        }
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            const uint32_t p = i0 + j * kBlock + threadIdx.x;
+            lp[j] = p < end ? src.logical(s, dn, p, idx[j]) : 0u;
+            grp[j] = Src::kIdentity ? g : lp[j] / L;
+        }
+    };
+    // the first round is fetched before the pick, so that its latency overlaps with it
+    {
+        const uint64_t first = (uint64_t)g * L;
+        end = (uint32_t)(first + L < n ? first + L : n);
+        load_round((uint32_t)first);
+    }
+    // every block picks the bin of the k-th key from the set's histogram
+    {
+        constexpr int kPer = kHistBins / kBlock;      // thread t owns 16 consecutive bins
+        const uint32_t* hist = src.hist_of(s, dn, st);
+        uint32_t loc[kPer];
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) loc[j] = hist[threadIdx.x * kPer + j];
+        suffix_pick<kPer>(loc, k, s_wave, s_out);
+    }
+    const uint32_t d1 = s_out[0];
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        st.d1[s] = d1;
+        st.krem[s] = k - s_out[1];
+    }
+    const uint32_t wave = threadIdx.x / kWave;
+    uint32_t* ggt = st.grp_gt + (size_t)s * st.maxgroups;
+    uint32_t* gin = st.grp_in + (size_t)s * st.maxgroups;
+    uint2* list = st.list + (size_t)s * st.list_cap;
+    uint32_t hi = 0, lo_inv = 0;                   // this thread's in-bin extremes
+    for (;;) {
+        const uint32_t first = (uint32_t)((uint64_t)g * L);
+        uint32_t gt = 0, in = 0;     // wave-uniform
+        for (uint32_t i0 = first; i0 < end; i0 += kBlock * kBatch) {
+            if (i0 != first || g != blockIdx.x) load_round(i0);
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+                if (i0 + j * kBlock + threadIdx.x < end) src.store_ordered(s, dn, lp[j], idx[j], bits[j]);
+                const uint32_t key = bits[j] & kAbs;
+                const uint32_t d = dg.bin(key);
+                const bool above = ok[j] && d > d1;
+                const bool inside = ok[j] && d == d1;
+                if (Src::kIdentity) {
+                    gt += (uint32_t)__popcll(__ballot(above));
+                } else {
+                    add_grouped(above, grp[j], ggt);
+                    if (dn) add_grouped(inside, grp[j], gin);
+                }
+                // in-bin entries are parked in LDS (in any order) as long as they fit
+                const uint64_t inm = __ballot(inside);
+                if (inm) {
+                    const uint32_t cnt = (uint32_t)__popcll(inm);
+                    uint32_t base = 0;
+                    if (lane_id() == 0) base = atomicAdd(&s_nstash, cnt);
+                    base = __shfl(base, 0);
+                    const uint32_t pos = base + rank_in(inm);
+                    if (inside) {
+                        if (pos < (uint32_t)kStash) s_stash[pos] = make_uint2(key, grp[j]);
+                        hi = key > hi ? key : hi;
+                        lo_inv = kAbs - key > lo_inv ? kAbs - key : lo_inv;
+                    }
+                    in += cnt;
+                }
+            }
+        }
+        if (lane_id() == 0) { s_gt[wave] = gt; s_in[wave] = in; }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            uint32_t tg = 0, ti = 0;
+            for (int v = 0; v < kBlock / kWave; ++v) { tg += s_gt[v]; ti += s_in[v]; }
+            if (Src::kIdentity) ggt[g] = tg;
+            s_base = ti ? atomicAdd(&st.list_cnt[s], ti) : 0u;     // one reservation per segment
+        }
+        __syncthreads();
+        const uint32_t total = s_nstash;
+        const uint32_t base = s_base;
+        if (total != 0 && total <= (uint32_t)kStash) {
+            for (uint32_t i = threadIdx.x; i < total; i += kBlock)
+                if (base + i < st.list_cap) list[base + i] = s_stash[i];
+        } else if (total != 0 && base < st.list_cap && in != 0) {
+            // more in-bin entries than the stash holds: walk the segment again; this wave's
+            // entries go to its slice of the reservation (nothing to do once the list is full)
+            uint32_t off = base;
+            for (uint32_t v = 0; v < wave; ++v) off += s_in[v];
+            for (uint32_t i0 = first; i0 < end; i0 += kBlock * kBatch) {
+                load_round(i0);
+#pragma unroll
+                for (int j = 0; j < kBatch; ++j) {
+                    const uint32_t key = bits[j] & kAbs;
+                    const bool inside = ok[j] && dg.bin(key) == d1;
+                    const uint64_t inm = __ballot(inside);
+                    if (inside) {
+                        const uint32_t pos = off + rank_in(inm);
+                        if (pos < st.list_cap) list[pos] = make_uint2(key, grp[j]);
+                    }
+                    off += (uint32_t)__popcll(inm);
+                }
+            }
+        }
+        // next segment of this block, if the set has more segments than the grid has blocks
+        if ((uint64_t)(g + gridDim.x) * L >= n) break;
+        g += gridDim.x;
+        end = (uint32_t)((uint64_t)g * L + L < n ? (uint64_t)g * L + L : n);
+        __syncthreads();                           // the stash and the counts have been read
+        if (threadIdx.x == 0) s_nstash = 0u;
+        __syncthreads();
+    }
+    // only a dense row's list can overflow (any other list holds the whole set)
+    if (!dn) return;
+    if (hi | lo_inv) {
+        atomicMax(&s_hi, hi);
+        atomicMax(&s_lo_inv, lo_inv);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0 && (s_hi | s_lo_inv)) {
+        atomicMax(&st.bin_hi[s], s_hi);
+        atomicMax(&st.bin_lo_inv[s], s_lo_inv);
+    }
+}
+
+// Block b of set s walks the physical slots [b*L, (b+1)*L), L = group_slots().  A set
+// that is read as a dense row takes the general walk (several segments per block, the
+// bookkeeping for an overflowing list); every other set the plain one.
+template <class Src>
+__global__ __launch_bounds__(kBlock) void k_bucket(Src src, SelState st, uint32_t k) {
+    if (src.dense(blockIdx.y)) bucket_general(src, st, k);
+    else bucket_fast(src, st, k);
+}
+
+// ---------------------------------------------------------------------------------
+// the finish: exact key, ties to take, per-group offsets
+// ---------------------------------------------------------------------------------
+
+// Calls f(key, group) for every entry of set s whose key lies in bin d1 - from the list
+// that k_bucket wrote, or, if that list overflowed (more in-bin keys than it holds: rows
+// of equal magnitudes), from the set's own slots.  Every thread of the block calls f the
+// same number of times; key == kNoKey stands for "nothing".  T threads per block.
+constexpr uint32_t kNoKey = 0xFFFFFFFFu;            // no key has bit 31 set
+
+template <int T, class Src, class F>
+__device__ __forceinline__ void for_each_in_bin(const Src& src, int s, bool dn, const Digit& dg,
+                                                uint32_t d1, const uint2* list, uint32_t nlist,
+                                                bool overflow, uint32_t nphys, uint32_t fl, F&& f) {
+    const uint32_t t = threadIdx.x;
+    if (!overflow) {
+        for (uint32_t i0 = 0; i0 < nlist; i0 += T * kBatch) {
+            uint2 e[kBatch];
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+                const uint32_t i = i0 + j * T + t;
+                e[j] = i < nlist ? list[i] : make_uint2(kNoKey, 0u);
+            }
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) f(e[j].x, e[j].y);
+        }
+    } else {
+        constexpr int kWide = T >= 1024 ? 8 : kBatch;     // loads in flight per thread
+        for (uint64_t p0 = 0; p0 < nphys; p0 += (uint64_t)T * kWide) {
+            uint32_t key[kWide], grp[kWide];
+#pragma unroll
+            for (int j = 0; j < kWide; ++j) {
+                const uint64_t p = p0 + (uint64_t)j * T + t;
+                uint32_t idx = 0, bits = 0;
+                const bool ok = p < nphys && src.fetch_phys(s, dn, (uint32_t)p, idx, bits) &&
+                                (bits & kAbs) >= fl;
+                key[j] = (ok && dg.bin(bits & kAbs) == d1) ? (bits & kAbs) : kNoKey;
+                grp[j] = ok ? src.logical(s, dn, (uint32_t)p, idx) / src.group_slots(dn) : 0u;
+            }
+#pragma unroll
+            for (int j = 0; j < kWide; ++j) f(key[j], grp[j]);
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------------
 // kernel 3 (large sets only): one block per set finishes the key and scans the groups
 // ---------------------------------------------------------------------------------
@@ -366,9 +630,9 @@ __global__ __launch_bounds__(1024) void k_finish(Src src, SelState st) {
     const uint32_t t = threadIdx.x;
     const bool dn = src.dense(s);
     const uint32_t nphys = src.nphys(s, dn);
-    const uint32_t L = src.group_slots(dn);
-    const uint32_t ng = (uint32_t)(((uint64_t)nphys + L - 1) / L);
+    const uint32_t ng = (uint32_t)(((uint64_t)nphys + src.group_slots(dn) - 1) / src.group_slots(dn));   // <= kMaxGroups
     const Digit dg = src.digit(s, dn, st);
+    const uint32_t fl = src.floor_key(s, dn);
     const uint32_t d1 = st.d1[s];
     uint32_t krem = st.krem[s];
     const uint32_t nlist = st.list_cnt[s];
@@ -378,75 +642,69 @@ __global__ __launch_bounds__(1024) void k_finish(Src src, SelState st) {
     // per-group counts of keys above the bin (two groups per thread), loaded early
     const uint32_t ggt0 = 2 * t < ng ? st.grp_gt[(size_t)s * st.maxgroups + 2 * t] : 0u;
     const uint32_t ggt1 = 2 * t + 1 < ng ? st.grp_gt[(size_t)s * st.maxgroups + 2 * t + 1] : 0u;
-    constexpr uint32_t kNone = 0xFFFFFFFFu;            // no key has bit 31 set
-    // f(key, group) is called by every thread the same number of times; key == kNone = nothing
-    auto for_each_entry = [&](auto&& f) {
-        if (!overflow) {
-            for (uint32_t i0 = 0; i0 < nlist; i0 += kT * kBatch) {
-                uint2 e[kBatch];
-#pragma unroll
-                for (int j = 0; j < kBatch; ++j) {
-                    const uint32_t i = i0 + j * kT + t;
-                    e[j] = i < nlist ? list[i] : make_uint2(kNone, 0u);
-                }
-#pragma unroll
-                for (int j = 0; j < kBatch; ++j) f(e[j].x, e[j].y);
-            }
-        } else {
-            // every item of the set in logical order; items outside bin d1 are skipped
-            for (uint64_t p0 = 0; p0 < nphys; p0 += (uint64_t)kT * kBatch) {
-                uint32_t key[kBatch], grp[kBatch];
-#pragma unroll
-                for (int j = 0; j < kBatch; ++j) {
-                    const uint64_t p = p0 + (uint64_t)j * kT + t;
-                    uint32_t idx, bits = 0;
-                    const bool ok = p < nphys && src.fetch_ord(s, dn, (uint32_t)p, idx, bits);
-                    key[j] = (ok && dg.bin(bits & kAbs) == d1) ? (bits & kAbs) : kNone;
-                    grp[j] = (uint32_t)(p / L);
-                }
-#pragma unroll
-                for (int j = 0; j < kBatch; ++j) f(key[j], grp[j]);
-            }
-        }
-    };
-    // radix passes over rel = key - lo: bits 30..20, 19..10, 9..0; a pass whose bits are
-    // zero for the whole bin is skipped
-    uint32_t prefix = 0;          // value of the rel bits above the current pass
-    for (int pass = 0; pass < 3; ++pass) {
-        const int shift = pass == 0 ? 20 : (pass == 1 ? 10 : 0);
-        const int bits = pass == 0 ? 11 : 10;
-        if (shift > 0 && width <= (1u << shift)) continue;       // uniform
-        h[t] = 0u;
-        h[t + kT] = 0u;
+    // an overflowed list whose in-bin keys are all one key (rows of equal magnitudes): that
+    // key is T, and k_bucket's per-group in-bin counts are the tie counts
+    const uint32_t bin_hi = st.bin_hi[s], bin_lo = kAbs - st.bin_lo_inv[s];
+    const bool one_key = overflow && bin_hi == bin_lo;
+    const uint32_t gin0 = (one_key && 2 * t < ng) ? st.grp_in[(size_t)s * st.maxgroups + 2 * t] : 0u;
+    const uint32_t gin1 = (one_key && 2 * t + 1 < ng) ? st.grp_in[(size_t)s * st.maxgroups + 2 * t + 1] : 0u;
+    uint32_t T, need;
+    if (one_key) {
+        T = bin_hi;
+        need = krem;
+        g_gt[2 * t] = ggt0;
+        g_gt[2 * t + 1] = ggt1;
+        g_eq[2 * t] = gin0;
+        g_eq[2 * t + 1] = gin1;
         __syncthreads();
-        for_each_entry([&](uint32_t key, uint32_t) {
-            if (key != kNone) {
+    } else {
+        // radix passes over rel = key - lo: bits 30..20, 19..10, 9..0; a pass whose bits are
+        // zero for the whole bin is skipped
+        uint32_t prefix = 0;          // value of the rel bits above the current pass
+        for (int pass = 0; pass < 3; ++pass) {
+            const int shift = pass == 0 ? 20 : (pass == 1 ? 10 : 0);
+            const int bits = pass == 0 ? 11 : 10;
+            if (shift > 0 && width <= (1u << shift)) continue;       // uniform
+            h[t] = 0u;
+            h[t + kT] = 0u;
+            __syncthreads();
+            for_each_in_bin<kT>(src, s, dn, dg, d1, list, nlist, overflow, nphys, fl, [&](uint32_t key, uint32_t) {
                 const uint32_t rel = key - lo;
-                if ((rel >> (shift + bits)) == prefix)
-                    atomicAdd(&h[(rel >> shift) & ((1u << bits) - 1u)], 1u);
-            }
+                const bool mine = key != kNoKey && (rel >> (shift + bits)) == prefix;
+                const uint32_t b = (rel >> shift) & ((1u << bits) - 1u);
+                // a wave whose keys all fall into one bin (masses of equal keys) adds once
+                const uint64_t act = __ballot(mine);
+                if (act) {
+                    const uint32_t b0 = __shfl(b, __builtin_ctzll(act));
+                    if (__ballot(mine && b == b0) == act) {
+                        if (lane_id() == (uint32_t)__builtin_ctzll(act)) atomicAdd(&h[b0], (uint32_t)__popcll(act));
+                    } else if (mine) {
+                        atomicAdd(&h[b], 1u);
+                    }
+                }
+            });
+            __syncthreads();
+            const uint32_t loc[2] = {h[2 * t], h[2 * t + 1]};
+            suffix_pick<2>(loc, krem, s_wave, s_out);
+            prefix = (prefix << bits) | s_out[0];
+            krem -= s_out[1];
+        }
+        T = lo + prefix;
+        need = krem;
+
+        // per-group counts of selected-for-sure (key > T) and tied (key == T) entries
+        g_gt[2 * t] = ggt0;
+        g_gt[2 * t + 1] = ggt1;
+        g_eq[2 * t] = 0u;
+        g_eq[2 * t + 1] = 0u;
+        __syncthreads();
+        for_each_in_bin<kT>(src, s, dn, dg, d1, list, nlist, overflow, nphys, fl, [&](uint32_t key, uint32_t g) {
+            g &= (uint32_t)kMaxGroups - 1;
+            add_grouped(key != kNoKey && key > T, g, g_gt);
+            add_grouped(key != kNoKey && key == T, g, g_eq);
         });
         __syncthreads();
-        const uint32_t loc[2] = {h[2 * t], h[2 * t + 1]};
-        suffix_pick<2>(loc, krem, s_wave, s_out);
-        prefix = (prefix << bits) | s_out[0];
-        krem -= s_out[1];
     }
-    const uint32_t T = lo + prefix;
-    const uint32_t need = krem;
-
-    // per-group counts of selected-for-sure (key > T) and tied (key == T) entries
-    g_gt[2 * t] = ggt0;
-    g_gt[2 * t + 1] = ggt1;
-    g_eq[2 * t] = 0u;
-    g_eq[2 * t + 1] = 0u;
-    __syncthreads();
-    for_each_entry([&](uint32_t key, uint32_t g) {
-        g &= (uint32_t)kMaxGroups - 1;
-        add_grouped(key != kNone && key > T, g, g_gt);
-        add_grouped(key != kNone && key == T, g, g_eq);
-    });
-    __syncthreads();
     // exclusive scans over the groups (ng <= 2048: two per thread)
     {
         const uint32_t g0 = 2 * t, g1 = 2 * t + 1;
@@ -471,27 +729,27 @@ __global__ __launch_bounds__(1024) void k_finish(Src src, SelState st) {
 // kernel 4: finish the key (unless k_finish has), then ordered emit
 // ---------------------------------------------------------------------------------
 
-// One block per group of logical positions.
+// One block per group.
 //
-// Every block first finishes the select of its set on its own - the list of keys inside
-// bin d1 is short, so doing it per block is cheaper than a kernel in between: LDS radix
-// passes over the list give the exact k-th key T and the number `need` of entries with
-// key == T to take; the block's output offsets are the counts, over the groups before its
-// own, of keys above the bin (grp_gt) plus list keys above T, and of list keys equal to T.
-// (If the list overflowed - only possible for a dense row with masses of equal keys -
-// every block reads the whole set instead: correct, slow.)
+// INLINE: every block first finishes the select of its set on its own - the list of keys
+// inside bin d1 is short, so doing it per block is cheaper than a kernel in between: LDS
+// radix passes over the list give the exact k-th key T and the number `need` of entries
+// with key == T to take; the block's output offsets are the counts, over the groups before
+// its own, of keys above the bin (grp_gt) plus list keys above T, and of list keys equal to
+// T.  (If the list overflowed every block reads the whole set instead: correct, slow; the
+// host side uses k_finish wherever such a set can be large.)
 //
 // Then the emit: an entry is selected if key > T, or key == T and fewer than `need`
 // equal-key entries precede it in index order; its output slot is the number of selected
 // entries before it.  DIVIDE: value / divisor (Eq. 3).  gbits != NULL: also set bit
 // `index` of that bitmap (the dense gMask of Algorithm 3 lines 21-22, one bit per gradient
-// element).  A block takes kBlock * kBatch positions per round: their order inside a round is
+// element).  A block takes kBlock * kBatch items per round: their order inside a round is
 // (sub-step j, wave, lane).
-// The kernel writes nothing that a source reads: in the overflow case other blocks of the
-// set are still reading all of it.
+// The kernel writes nothing that a source reads.
+// ---- the plain emit: one group per block ----
 template <class Src, bool DIVIDE, bool INLINE>
-__global__ __launch_bounds__(kBlock) void k_emit(
-        Src src, SelState st, uint32_t k, uint32_t* __restrict__ out_idx,
+__device__ __forceinline__ void emit_fast(
+        const Src& src, const SelState& st, uint32_t k, uint32_t* __restrict__ out_idx,
         float* __restrict__ out_val, int64_t out_stride, float divisor,
         uint32_t* __restrict__ gbits) {
     constexpr int kWaves = kBlock / kWave;
@@ -506,7 +764,7 @@ __global__ __launch_bounds__(kBlock) void k_emit(
     const int s = blockIdx.y;
     const uint32_t g = blockIdx.x;
     const uint32_t t = threadIdx.x;
-    const bool dn = src.dense(s);
+    constexpr bool dn = false;
     const uint32_t n = src.nphys(s, dn);
     const uint32_t L = src.group_slots(dn);
     const uint64_t first = (uint64_t)g * L;
@@ -721,6 +979,256 @@ __global__ __launch_bounds__(kBlock) void k_emit(
             }
         }
     }
+}
+
+// ---- the general emit: several groups per block, dense-row bookkeeping ----
+template <class Src, bool DIVIDE, bool INLINE, int BLOCK>
+__device__ __forceinline__ void emit_general(
+        const Src& src, const SelState& st, uint32_t k, uint32_t* __restrict__ out_idx,
+        float* __restrict__ out_val, int64_t out_stride, float divisor,
+        uint32_t* __restrict__ gbits) {
+    constexpr int kWaves = BLOCK / kWave;
+    constexpr int kT = BLOCK;
+    __shared__ uint32_t h[2048];
+    __shared__ uint32_t s_wave[kWaves];
+    __shared__ uint32_t s_out[3];
+    __shared__ uint32_t s_red[2][kWaves];
+    __shared__ uint32_t s_eq[kBatch * kWaves];
+    __shared__ uint32_t s_sel[kBatch * kWaves];
+    __shared__ uint32_t s_cmp[BLOCK];
+    const int s = blockIdx.y;
+    const uint32_t t = threadIdx.x;
+    const bool dn = src.dense(s);
+    const uint32_t nitems = src.nphys(s, dn);
+    const uint32_t L = src.group_slots(dn);
+    const uint32_t ngroups = (uint32_t)(((uint64_t)nitems + L - 1) / L);
+    if (blockIdx.x >= ngroups) return;
+    const uint32_t fl = src.floor_key(s, dn);
+    const uint32_t wave = t / kWave;
+
+    // what the INLINE finish keeps between the groups of this block
+    constexpr int kCache = 4;
+    uint2 ent[kCache];                   // a short list is read once and kept in registers
+    bool cached = false, overflow = false, one_key = false, finished = false;
+    uint32_t nlist = 0, d1 = 0, n = 0;
+    Digit dg{0u, (uint32_t)kCoarseShift};
+    const uint2* list = st.list + (size_t)s * st.list_cap;
+    uint32_t T = 0, need = 0;
+    if (!INLINE) {
+        T = st.T[s];
+        need = st.need[s];
+    }
+
+    // a set with more groups than the grid has blocks (a dense row) takes several turns
+    for (uint32_t g = blockIdx.x; g < ngroups; g += gridDim.x) {
+        if (g != blockIdx.x) __syncthreads();           // the previous group's LDS use is over
+        const uint32_t first = g * L;                   // < nitems
+        const uint32_t ng_items = nitems - first < L ? nitems - first : L;
+        // the group's first round of items is fetched up front: its latency overlaps the finish
+        uint32_t idx[kBatch], vb[kBatch];
+        bool ok[kBatch];
+        auto load_round = [&](uint32_t i0) {
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+                const uint32_t q = i0 + j * BLOCK + t;
+                idx[j] = 0; vb[j] = 0;
+                ok[j] = q < ng_items && src.fetch_ord(s, dn, first + q, idx[j], vb[j]) &&
+                        (vb[j] & kAbs) >= fl;
+            }
+        };
+        load_round(0u);
+
+        // ---- finish ---------------------------------------------------------------------
+        uint32_t off_gt, eq_before;
+        if (!INLINE) {
+            off_gt = st.off_gt[(size_t)s * st.maxgroups + g];
+            eq_before = st.off_eq[(size_t)s * st.maxgroups + g];
+        } else {
+            // keys above the bin (and, for a one-key bin, keys inside it) in the groups before
+            uint32_t before_gt = 0, before_in = 0;
+            for (uint32_t gp = t; gp < g; gp += kT) before_gt += st.grp_gt[(size_t)s * st.maxgroups + gp];
+            // f(key, group): key == kNoKey = nothing
+            auto for_each_entry = [&](auto&& f) {
+                if (cached) {
+#pragma unroll
+                    for (int j = 0; j < kCache; ++j) f(ent[j].x, ent[j].y);
+                } else {
+                    for_each_in_bin<kT>(src, s, dn, dg, d1, list, nlist, overflow, n, fl, f);
+                }
+            };
+            if (!finished) {
+                finished = true;
+                dg = src.digit(s, dn, st);
+                d1 = st.d1[s];
+                uint32_t krem = st.krem[s];
+                nlist = st.list_cnt[s];
+                n = src.nphys(s, dn);
+                overflow = nlist > st.list_cap;       // the list is incomplete
+                // all in-bin keys are one key (rows of equal magnitudes): no pass over the set
+                const uint32_t bin_hi = st.bin_hi[s], bin_lo = kAbs - st.bin_lo_inv[s];
+                one_key = overflow && bin_hi == bin_lo;
+                const uint32_t lo = dg.lo(d1), width = dg.width(d1);    // bin d1 = [lo, lo + width)
+                cached = !overflow && nlist <= (uint32_t)(kCache * kT);
+#pragma unroll
+                for (int j = 0; j < kCache; ++j) {
+                    const uint32_t i = t + (uint32_t)j * kT;
+                    ent[j] = (cached && i < nlist) ? list[i] : make_uint2(kNoKey, 0u);
+                }
+                if (one_key) {
+                    T = bin_hi;
+                    need = krem;
+                } else {
+                    // radix passes over rel = key - lo: bits 30..20, 19..10, 9..0; a pass whose
+                    // bits are zero for the whole bin is skipped
+                    uint32_t prefix = 0;          // value of the rel bits above the current pass
+                    for (int pass = 0; pass < 3; ++pass) {
+                        const int shift = pass == 0 ? 20 : (pass == 1 ? 10 : 0);
+                        const int bits = pass == 0 ? 11 : 10;
+                        if (shift > 0 && width <= (1u << shift)) continue;       // uniform
+#pragma unroll
+                        for (int j = 0; j < 2048 / kT; ++j) h[t + j * kT] = 0u;
+                        __syncthreads();
+                        for_each_entry([&](uint32_t key, uint32_t) {
+                            if (key != kNoKey) {
+                                const uint32_t rel = key - lo;
+                                if ((rel >> (shift + bits)) == prefix)
+                                    atomicAdd(&h[(rel >> shift) & ((1u << bits) - 1u)], 1u);
+                            }
+                        });
+                        __syncthreads();
+                        constexpr int kPer = 2048 / kT;
+                        uint32_t loc[kPer];
+#pragma unroll
+                        for (int j = 0; j < kPer; ++j) loc[j] = h[t * kPer + j];
+                        suffix_pick<kPer>(loc, krem, s_wave, s_out);
+                        prefix = (prefix << bits) | s_out[0];
+                        krem -= s_out[1];
+                    }
+                    T = lo + prefix;
+                    need = krem;
+                }
+                if (g == 0 && t == 0) {
+                    st.T[s] = T;
+                    st.need[s] = need;
+                    if (st.T_out) st.T_out[s] = T;
+                }
+            }
+            // entries of the groups before this one: above T, equal to T
+            uint32_t c_gt = before_gt, c_eq = 0;
+            if (one_key) {
+                for (uint32_t gp = t; gp < g; gp += kT) before_in += st.grp_in[(size_t)s * st.maxgroups + gp];
+                c_eq = before_in;
+            } else {
+                for_each_entry([&](uint32_t key, uint32_t grp) {
+                    if (key != kNoKey && grp < g) {
+                        c_gt += key > T ? 1u : 0u;
+                        c_eq += key == T ? 1u : 0u;
+                    }
+                });
+            }
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) {
+                c_gt += __shfl_xor(c_gt, d);
+                c_eq += __shfl_xor(c_eq, d);
+            }
+            if (lane_id() == 0) { s_red[0][wave] = c_gt; s_red[1][wave] = c_eq; }
+            __syncthreads();
+            off_gt = 0;
+            eq_before = 0;
+#pragma unroll
+            for (int v = 0; v < kWaves; ++v) { off_gt += s_red[0][v]; eq_before += s_red[1][v]; }
+        }
+
+        // ---- emit -----------------------------------------------------------------------
+        uint32_t outp = off_gt + (eq_before < need ? eq_before : need);
+        for (uint32_t i0 = 0; i0 < ng_items; i0 += BLOCK * kBatch) {
+            if (i0 != 0) load_round(i0);
+            bool is_gt[kBatch], is_eq[kBatch];
+            uint64_t eqm[kBatch];
+            __syncthreads();                  // the previous round's s_eq / s_sel are no longer read
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+                const uint32_t key = vb[j] & kAbs;
+                is_gt[j] = ok[j] && key > T;
+                is_eq[j] = ok[j] && key == T;
+                eqm[j] = __ballot(is_eq[j]);
+                if (lane_id() == 0) s_eq[j * kWaves + wave] = (uint32_t)__popcll(eqm[j]);
+            }
+            __syncthreads();
+            bool sel[kBatch];
+            uint64_t selm[kBatch];
+            uint32_t eq_all = 0;
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+                uint32_t eq_base = eq_before + eq_all;
+                for (uint32_t v = 0; v < (uint32_t)kWaves; ++v) {
+                    const uint32_t c = s_eq[j * kWaves + v];
+                    if (v < wave) eq_base += c;
+                    eq_all += c;
+                }
+                sel[j] = is_gt[j] || (is_eq[j] && (eq_base + rank_in(eqm[j]) < need));
+                selm[j] = __ballot(sel[j]);
+                if (lane_id() == 0) s_sel[j * kWaves + wave] = (uint32_t)__popcll(selm[j]);
+            }
+            __syncthreads();
+            uint32_t sel_all = 0;
+#pragma unroll
+            for (int j = 0; j < kBatch; ++j) {
+                uint32_t sel_base = outp + sel_all;
+                for (uint32_t v = 0; v < (uint32_t)kWaves; ++v) {
+                    const uint32_t c = s_sel[j * kWaves + v];
+                    if (v < wave) sel_base += c;
+                    sel_all += c;
+                }
+                if (sel[j]) {
+                    const uint32_t pos = sel_base + rank_in(selm[j]);
+                    if (pos < k) {      // always true when the select state is consistent
+                        out_idx[(int64_t)s * out_stride + pos] = idx[j];
+                        float v = __uint_as_float(vb[j]);
+                        if (DIVIDE) v = v / divisor;
+                        out_val[(int64_t)s * out_stride + pos] = v;
+                    }
+                }
+            }
+            outp += sel_all;
+            eq_before += eq_all;
+            if (gbits) {                      // block-uniform
+                // a wave's selected indices, compacted, are ascending: the first of each run that
+                // shares a bitmap word sets the bits of the whole run with one atomic
+#pragma unroll
+                for (int j = 0; j < kBatch; ++j) {
+                    const uint32_t nsel = (uint32_t)__popcll(selm[j]);
+                    if (sel[j]) s_cmp[wave * kWave + rank_in(selm[j])] = idx[j];
+                    __syncthreads();
+                    const uint32_t lane = lane_id();
+                    if (lane < nsel) {
+                        const uint32_t* c = s_cmp + wave * kWave;
+                        const uint32_t word = c[lane] >> 5;
+                        if (lane == 0 || (c[lane - 1] >> 5) != word) {
+                            uint32_t bits = 1u << (c[lane] & 31);
+                            for (uint32_t q = lane + 1; q < nsel && (c[q] >> 5) == word; ++q)
+                                bits |= 1u << (c[q] & 31);
+                            atomicOr(&gbits[word], bits);
+                        }
+                    }
+                    __syncthreads();
+                }
+            }
+        }
+    }
+}
+
+// (The register budget is the plain emit's: the general one, which runs for the rare dense
+// row only, may spill.)
+template <class Src, bool DIVIDE, bool INLINE>
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(7, 8))) void k_emit(
+        Src src, SelState st, uint32_t k, uint32_t* __restrict__ out_idx,
+        float* __restrict__ out_val, int64_t out_stride, float divisor,
+        uint32_t* __restrict__ gbits) {
+    if (src.dense(blockIdx.y))
+        emit_general<Src, DIVIDE, INLINE, kBlock>(src, st, k, out_idx, out_val, out_stride, divisor, gbits);
+    else
+        emit_fast<Src, DIVIDE, INLINE>(src, st, k, out_idx, out_val, out_stride, divisor, gbits);
 }
 
 // Algorithm 4 line 8 for the stand-alone local selection: +0.0 at the k selected entries of
