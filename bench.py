@@ -258,6 +258,9 @@ def main() -> int:
                     help="replace the gradient rows of this many workers by rows of equal "
                          "magnitudes, which overflow the candidate list and are selected from "
                          "the dense row (cost of the exact fallback)")
+    ap.add_argument("--carry", action="store_true",
+                    help="call gtopk_step_carry (speculative thresholds carried from step to step) "
+                         "instead of gtopk_step (a fresh sample of every row on every step)")
     ap.add_argument("--no-ceiling", action="store_true",
                     help="skip the HBM-ceiling probe passes")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -307,8 +310,14 @@ def main() -> int:
     g_val = torch.zeros(k, dtype=torch.float32, device="cuda")
     ws = B.alloc_workspace(m, k, P)
 
+    # thresholds carried from step to step (zero: every worker starts from a sample)
+    thr_state = None if not args.carry else torch.zeros((P, 4), dtype=torch.int32, device="cuda")
+
     def step(i: int) -> None:
-        B.gtopk_step(grads[i % len(grads)], res, k, g_idx, g_val, None, None, ws)
+        if thr_state is None:
+            B.gtopk_step(grads[i % len(grads)], res, k, g_idx, g_val, None, None, ws)
+        else:
+            B.gtopk_step_carry(grads[i % len(grads)], res, k, g_idx, g_val, None, None, thr_state, ws)
 
     # stage events: created up front (a first record forces creation), recorded by the library
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(N_STAGES)] for _ in range(K)]
@@ -324,13 +333,14 @@ def main() -> int:
         step(Wm + i)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    modes_after_timed = None if thr_state is None else thr_state[:, 0].cpu().numpy().tolist()
     # the same K steps once more with the library recording its stage events (six event
     # records per step cost about 30 us, which is why they stay out of the region above):
     # stage times and the dominant kernel's duration come from here
     t2 = time.perf_counter()
     for i in range(K):
         B.gtopk_step_timed(grads[(Wm + K + i) % len(grads)], res, k, g_idx, g_val, None, None, ws,
-                           [e.cuda_event for e in events[i]])
+                           [e.cuda_event for e in events[i]], thr_state)
     torch.cuda.synchronize()
     t3 = time.perf_counter()
 
@@ -374,7 +384,15 @@ def main() -> int:
                      "measured": "HIP events around the kernel in a second pass over the same K steps",
                      "algorithmic_bytes_per_launch": alg_bytes},
         "input_generation_s": round(t_gen, 1),
+        "entry_point": "gtopk_step" if thr_state is None else "gtopk_step_carry",
     }
+    if thr_state is not None:
+        out["carried_thresholds"] = {
+            "workers_not_sampling_after_timed_steps": sum(1 for md in modes_after_timed if md == 2),
+            "workers": P,
+            "note": ("gtopk_step_carry: same results as gtopk_step; a worker whose k-th magnitude "
+                     "moves predictably filters with a threshold extrapolated from its previous "
+                     "steps instead of sampling its row")}
     if args.degenerate_workers:
         counts, cap = B.gtopk_debug_candidate_counts(ws, m, k, P)
         out["degenerate_workers"] = {

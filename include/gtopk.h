@@ -133,6 +133,29 @@ int gtopk_step(const float* grad, float* residual, int64_t m, int64_t stride,
                void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * gtopk_step with every worker's speculative threshold carried from one call to the next.
+ * The local selection (Algorithm 4 lines 5-7) first filters each row with a threshold
+ * that is only a guess of the k-th largest magnitude, then selects exactly among what
+ * passed; gtopk_step takes that guess from a sample of the row on every call.  In training
+ * the k-th largest magnitude of a worker moves little from one iteration to the next, so
+ * here the exact value found by one call, extrapolated and lowered by a margin, serves the
+ * next call, and the sampling kernels have nothing to do for that worker.  Results are
+ * bit-identical to gtopk_step whatever the carried threshold is worth: a worker whose
+ * guess left fewer than k entries, or more than its candidate list holds, is selected
+ * from its dense row (slower), and samples again on the following call.
+ *
+ *   thr_state [P][4] uint32 i/o : caller-owned device memory (16-byte aligned), one entry
+ *       per worker; all zero before the first call and whenever the caller wants every
+ *       worker to start from a sample again (a new model, a different k).  Its contents
+ *       are otherwise opaque.
+ * All other arguments, and all errors, as gtopk_step; GTOPK_EINVAL if thr_state is NULL.
+ */
+int gtopk_step_carry(const float* grad, float* residual, int64_t m, int64_t stride,
+                     int32_t P, int32_t k, uint32_t* g_idx, float* g_val,
+                     uint32_t* loc_idx, float* loc_val, uint32_t* thr_state,
+                     void* ws, size_t ws_bytes, void* stream);
+
+/*
  * gtopk_step for callers that cannot allocate device memory or pass a workspace: code under
  * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The workspace
  * is a device array of GTOPK_STATIC_WORKSPACE_BYTES that is part of the library's code
@@ -212,12 +235,13 @@ int gtopk_dense_topk(const float* dense, int64_t m, int32_t k, uint32_t* g_idx, 
  *   [4] after the tree  [5] after the residual restore.
  * The handles belong to this one call: the library keeps nothing between calls, so
  * concurrent callers (each with its own workspace, stream and events) do not interfere.
+ * thr_state: NULL (then the call is gtopk_step) or as in gtopk_step_carry.
  * Results are those of gtopk_step.  GTOPK_EINVAL if events or one of the handles is NULL.
  */
 #define GTOPK_STAGE_EVENTS 6
 int gtopk_step_timed(const float* grad, float* residual, int64_t m, int64_t stride,
                      int32_t P, int32_t k, uint32_t* g_idx, float* g_val,
-                     uint32_t* loc_idx, float* loc_val,
+                     uint32_t* loc_idx, float* loc_val, uint32_t* thr_state,
                      void* ws, size_t ws_bytes, void* stream, void* const* events);
 
 /*

@@ -19,7 +19,7 @@ _lib: Optional[ctypes.CDLL] = None
 EXPORTS = (
     "gtopk_status_string", "gtopk_workspace_bytes", "gtopk_merge_workspace_bytes",
     "gtopk_local_select", "gtopk_merge", "gtopk_tree", "gtopk_residual_restore", "gtopk_step",
-    "gtopk_step_static",
+    "gtopk_step_static", "gtopk_step_carry",
     "gtopk_apply_update", "gtopk_dense_mask",
     "gtopk_allreduce_workspace_bytes", "gtopk_topk_allreduce", "gtopk_dense_topk",
     "gtopk_step_timed", "gtopk_probe_stream", "gtopk_debug_candidate_counts", "gtopk_debug_plan",
@@ -79,8 +79,10 @@ def load() -> ctypes.CDLL:
     lib.gtopk_dense_topk.restype = c.c_int
     lib.gtopk_dense_topk.argtypes = [vp, i64, i32, vp, vp, vp, sz, vp]
     lib.gtopk_step_timed.restype = c.c_int
-    lib.gtopk_step_timed.argtypes = [vp, vp, i64, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp,
+    lib.gtopk_step_timed.argtypes = [vp, vp, i64, i64, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp,
                                      c.POINTER(c.c_void_p)]
+    lib.gtopk_step_carry.restype = c.c_int
+    lib.gtopk_step_carry.argtypes = [vp, vp, i64, i64, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.gtopk_probe_stream.restype = c.c_int
     lib.gtopk_probe_stream.argtypes = [vp, vp, i64, i32, vp, vp]
     lib.gtopk_debug_plan.restype = c.c_int
@@ -292,9 +294,31 @@ def gtopk_dense_topk(dense, k: int, g_idx, g_val, ws) -> None:
     _check(rc, "gtopk_dense_topk")
 
 
-def gtopk_step_timed(grad, residual, k: int, g_idx, g_val, loc_idx, loc_val, ws, events) -> None:
-    """gtopk_step that records the caller's six raw hipEvent_t handles (ints) at its stage
-    boundaries."""
+def gtopk_step_carry(grad, residual, k: int, g_idx, g_val, loc_idx, loc_val, thr_state, ws) -> None:
+    """gtopk_step with the speculative thresholds carried in `thr_state` ([P][4] int32, zeroed
+    by the caller before the first call)."""
+    torch = _torch()
+    m, stride = _rows(residual, "residual")
+    mg, sg = _rows(grad, "grad")
+    P = residual.shape[0]
+    if (mg, grad.shape[0]) != (m, P) or (P > 1 and sg != stride):
+        raise ValueError("grad and residual must have the same shape and row stride")
+    if thr_state.numel() != 4 * P:
+        raise ValueError("thr_state must hold 4 words per worker")
+    rc = load().gtopk_step_carry(
+        _ptr(grad, torch.float32, "grad"), _ptr(residual, torch.float32, "residual"),
+        m, stride, P, k, _ptr(g_idx, torch.int32, "g_idx"), _ptr(g_val, torch.float32, "g_val"),
+        _ptr(loc_idx, torch.int32, "loc_idx", allow_none=True),
+        _ptr(loc_val, torch.float32, "loc_val", allow_none=True),
+        _ptr(thr_state, torch.int32, "thr_state"),
+        _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream())
+    _check(rc, "gtopk_step_carry")
+
+
+def gtopk_step_timed(grad, residual, k: int, g_idx, g_val, loc_idx, loc_val, ws, events,
+                     thr_state=None) -> None:
+    """gtopk_step (or, with thr_state, gtopk_step_carry) that records the caller's six raw
+    hipEvent_t handles (ints) at its stage boundaries."""
     torch = _torch()
     m, stride = _rows(residual, "residual")
     mg, sg = _rows(grad, "grad")
@@ -309,6 +333,7 @@ def gtopk_step_timed(grad, residual, k: int, g_idx, g_val, loc_idx, loc_val, ws,
         m, stride, P, k, _ptr(g_idx, torch.int32, "g_idx"), _ptr(g_val, torch.float32, "g_val"),
         _ptr(loc_idx, torch.int32, "loc_idx", allow_none=True),
         _ptr(loc_val, torch.float32, "loc_val", allow_none=True),
+        _ptr(thr_state, torch.int32, "thr_state", allow_none=True),
         _ptr(ws, torch.uint8, "ws"), ws.numel(), _stream(), arr)
     _check(rc, "gtopk_step_timed")
 

@@ -352,10 +352,10 @@ bool pass_histograms(int64_t m, uint32_t k) {
 // passes false and settles the rows in k_restore_fused.  `pre_cleared`: the caller has
 // already cleared this call's counters and histograms.
 CandSrc cand_source(const float* rows, int64_t stride, int64_t m, uint32_t k, const StepWs& w,
-                    bool producer_hist, bool no_bounds) {
+                    bool producer_hist, bool no_bounds, uint32_t* thr_state = nullptr) {
     return CandSrc{rows, stride, (uint32_t)m, k, w.cap, w.nchunks, w.Lc, w.Ld,
                    w.cand_idx, w.cand_val, w.cand_count, w.tspec, w.run_table, w.run_off,
-                   w.ord_idx, w.ord_val, producer_hist, no_bounds};
+                   w.ord_idx, w.ord_val, producer_hist, no_bounds, reinterpret_cast<uint4*>(thr_state)};
 }
 
 // The grids are sized for the candidate lists.  A worker that is selected from its dense
@@ -372,7 +372,11 @@ SelGrid local_grid(const StepWs& w, uint32_t P) {
 // already cleared this call's counters and histograms.
 int do_local_select(const float* grad, float* residual, int64_t m, int64_t stride, uint32_t P,
                     uint32_t k, uint32_t* out_idx, float* out_val, const StepWs& w, bool zero_rows,
-                    bool pre_cleared, hipStream_t st, void* const* events = nullptr) {
+                    bool pre_cleared, hipStream_t st, void* const* events = nullptr,
+                    uint32_t* thr_state = nullptr) {
+    // workers whose threshold is carried over from the previous call skip the sampling (both
+    // kernels are launched all the same: who samples is decided on the device)
+    const uint4* carry = reinterpret_cast<const uint4*>(thr_state);
     if (!pre_cleared)
         zero_async(st, zero_job(w.samp_hist, (size_t)(w.tspec - w.samp_hist), w.sel.hist,
                                 select_clear_words(w.sel)));
@@ -384,9 +388,9 @@ int do_local_select(const float* grad, float* residual, int64_t m, int64_t strid
     if (sblocks > sb_max) sblocks = sb_max;
     if (sblocks < 1) sblocks = 1;
     hipLaunchKernelGGL(k_sample, dim3(sblocks, P), dim3(kSampleBlock), 0, st, grad, residual,
-                       (uint32_t)m, stride, sp.tile_stride, sp.n_tiles, w.samp_hist);
+                       (uint32_t)m, stride, sp.tile_stride, sp.n_tiles, w.samp_hist, carry);
     hipLaunchKernelGGL(k_sample_pick, dim3(P), dim3(kSampleBlock), 0, st, w.samp_hist, sp.target,
-                       w.tspec);
+                       w.tspec, carry);
     mark_stage(1, events, st);
 
     const bool producer_hist = pass_histograms(m, k);
@@ -400,7 +404,7 @@ int do_local_select(const float* grad, float* residual, int64_t m, int64_t strid
                            w.cand_count, w.run_table, w.nchunks, w.sel.hist);
     mark_stage(2, events, st);
 
-    const CandSrc src = cand_source(residual, stride, m, k, w, producer_hist, false);
+    const CandSrc src = cand_source(residual, stride, m, k, w, producer_hist, false, thr_state);
     // the histogram kernel always runs: where the pass has counted its candidates it serves
     // only the workers that came back with fewer than k of them
     run_select<CandSrc, false>(src, w.sel, local_grid(w, P), k, out_idx, out_val, (int64_t)k, 1.0f,
@@ -607,8 +611,10 @@ int gtopk_residual_restore(float* residual, int64_t m, int64_t stride, int32_t P
 
 static int step_impl(const float* grad, float* residual, int64_t m, int64_t stride, int32_t P,
                      int32_t k, uint32_t* g_idx, float* g_val, uint32_t* loc_idx, float* loc_val,
-                     void* ws, size_t ws_bytes, void* stream, void* const* events) {
+                     void* ws, size_t ws_bytes, void* stream, void* const* events,
+                     uint32_t* thr_state = nullptr) {
     if (!grad || !residual || !g_idx || !g_val || !ws) return GTOPK_EINVAL;
+    if (!aligned16(thr_state)) return GTOPK_EALIGN;
     if ((loc_idx == nullptr) != (loc_val == nullptr)) return GTOPK_EINVAL;
     if (!sizes_ok(m, k, P) || stride < m) return GTOPK_EINVAL;
     if (!aligned16(grad) || !aligned16(residual) || !aligned16(g_idx) || !aligned16(g_val) ||
@@ -626,7 +632,7 @@ static int step_impl(const float* grad, float* residual, int64_t m, int64_t stri
                             select_clear_words(w.sel), w.mrg.sel.hist, select_clear_words(w.mrg.sel),
                             w.mrg.sel_alt.hist, w.mrg.alt_clear_words, w.gbits, w.gbits_words));
     int rc = do_local_select(grad, residual, m, stride, (uint32_t)P, (uint32_t)k, li, lv, w, false,
-                             true, st, events);
+                             true, st, events, thr_state);
     if (rc != GTOPK_OK) return rc;
     mark_stage(3, events, st);
     rc = do_tree(li, lv, w.sel.T, (uint32_t)P, (uint32_t)k, g_idx, g_val, w, w.gbits, true, st);
@@ -693,14 +699,23 @@ int gtopk_step_static(const float* grad, float* residual, int64_t m, int64_t str
                      (size_t)GTOPK_STATIC_WORKSPACE_BYTES, stream, nullptr);
 }
 
+int gtopk_step_carry(const float* grad, float* residual, int64_t m, int64_t stride, int32_t P,
+                     int32_t k, uint32_t* g_idx, float* g_val, uint32_t* loc_idx, float* loc_val,
+                     uint32_t* thr_state, void* ws, size_t ws_bytes, void* stream) {
+    if (!thr_state) return GTOPK_EINVAL;
+    return step_impl(grad, residual, m, stride, P, k, g_idx, g_val, loc_idx, loc_val, ws, ws_bytes,
+                     stream, nullptr, thr_state);
+}
+
 int gtopk_step_timed(const float* grad, float* residual, int64_t m, int64_t stride, int32_t P,
                      int32_t k, uint32_t* g_idx, float* g_val, uint32_t* loc_idx, float* loc_val,
-                     void* ws, size_t ws_bytes, void* stream, void* const* events) {
+                     uint32_t* thr_state, void* ws, size_t ws_bytes, void* stream,
+                     void* const* events) {
     if (!events) return GTOPK_EINVAL;
     for (int i = 0; i < GTOPK_STAGE_EVENTS; ++i)
         if (!events[i]) return GTOPK_EINVAL;
     return step_impl(grad, residual, m, stride, P, k, g_idx, g_val, loc_idx, loc_val, ws, ws_bytes,
-                     stream, events);
+                     stream, events, thr_state);
 }
 
 int gtopk_apply_update(float* weights, int64_t m, int64_t stride, int32_t copies, int32_t k,

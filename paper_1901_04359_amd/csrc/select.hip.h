@@ -78,6 +78,48 @@ struct CandSrc {
     float* ord_val;
     bool producer_hist;                   // the streaming pass has histogrammed the candidates
     bool no_bounds;                       // dense rows without any threshold (the dense top-k)
+    uint4* carry_state;                   // [P] or NULL: thresholds carried from call to call
+
+    // Called once per set, by the thread that records the set's exact k-th key T: works out
+    // the speculative threshold of the worker's NEXT call from what this call has seen.
+    //   x  0: nothing known, 1: learning (the next call samples), 2: the next call filters
+    //      with w instead of sampling
+    //   y  T of this call          z  margin d between the predicted T and the threshold
+    //   w  threshold for the next call = predicted T - d; the prediction is T + (T - previous T)
+    // The margin follows the number of candidates the pass kept (aim: 1.25 k .. 2.2 k); the
+    // next call may skip sampling once a prediction has come true to within half the
+    // margin, and goes back to sampling when the list came close to either of its limits.
+    // A wrong threshold costs time only: the select is exact whatever it filters with.
+    __device__ void carry(int s, uint32_t T) const {
+        if (!carry_state) return;
+        uint4 c = carry_state[s];
+        const uint32_t n = cand_count[s], ts = tspec[s];
+        if (n < k || n > cap || no_bounds) {             // this call fell back to the dense row
+            carry_state[s] = make_uint4(0u, T, c.z, 0u);
+            return;
+        }
+        uint32_t d = c.z;
+        uint32_t mode = 1;
+        long long pred_next = (long long)T;
+        if (c.x == 0) {
+            d = T - ts;                                  // what the sampler chose
+        } else {
+            const long long pred = (long long)c.w + (long long)c.z;      // last call's prediction of T
+            const long long err = pred > (long long)T ? pred - (long long)T : (long long)T - pred;
+            if ((uint64_t)n * 100 > (uint64_t)k * 220) d -= d / 4;
+            else if ((uint64_t)n * 100 < (uint64_t)k * 125) d += d / 2;
+            const bool came_true = err * 2 <= (long long)d;
+            const bool roomy = (uint64_t)n * 100 >= (uint64_t)k * 108 && (uint64_t)n * 100 <= (uint64_t)cap * 85;
+            mode = (came_true && roomy) ? 2u : 1u;
+            pred_next = 2ll * (long long)T - (long long)c.y;
+        }
+        if (d < 256u) d = 256u;
+        if (d > T / 2 + 256u) d = T / 2 + 256u;
+        if (pred_next < 0) pred_next = 0;
+        if (pred_next > (long long)kAbs) pred_next = (long long)kAbs;
+        const uint32_t next = pred_next > (long long)d ? (uint32_t)(pred_next - (long long)d) : 0u;
+        carry_state[s] = make_uint4(mode, T, d, next);
+    }
 
     __device__ bool dense(int s) const {
         const uint32_t c = cand_count[s];
@@ -177,6 +219,7 @@ struct MergedSrc {
     const uint32_t* in_min;
     bool inverted;
     __device__ bool dense(int) const { return false; }
+    __device__ void carry(int, uint32_t) const {}
     __device__ uint32_t floor_key(int, bool) const { return 0u; }
     __device__ bool wants_hist(int, bool) const { return true; }
     __device__ uint32_t* hist_of(int s, bool, const SelState& st) const {
@@ -722,6 +765,7 @@ __global__ __launch_bounds__(1024) void k_finish(Src src, SelState st) {
         st.T[s] = T;
         st.need[s] = need;
         if (st.T_out) st.T_out[s] = T;
+        src.carry(s, T);
     }
 }
 
@@ -900,6 +944,7 @@ __device__ __forceinline__ void emit_fast(
             st.T[s] = T;
             st.need[s] = need;
             if (st.T_out) st.T_out[s] = T;
+            src.carry(s, T);
         }
     }
 
@@ -1111,6 +1156,7 @@ __device__ __forceinline__ void emit_general(
                     st.T[s] = T;
                     st.need[s] = need;
                     if (st.T_out) st.T_out[s] = T;
+                    src.carry(s, T);
                 }
             }
             // entries of the groups before this one: above T, equal to T

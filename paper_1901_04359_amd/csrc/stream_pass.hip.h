@@ -11,9 +11,11 @@ namespace gtopk {
 // rounds of loads in flight.
 __global__ __launch_bounds__(kSampleBlock) void k_sample(
         const float* __restrict__ grad, const float* __restrict__ res, uint32_t m, int64_t stride,
-        uint32_t tile_stride, uint32_t n_tiles, uint32_t* __restrict__ samp_hist) {
+        uint32_t tile_stride, uint32_t n_tiles, uint32_t* __restrict__ samp_hist,
+        const uint4* __restrict__ carry) {
     __shared__ uint32_t h[kSampleBins];
     const int w = blockIdx.y;
+    if (carry && carry[w].x == 2u) return;        // this worker filters with a carried threshold
     for (int b = threadIdx.x; b < kSampleBins; b += kSampleBlock) h[b] = 0u;
     __syncthreads();
     const float* g = grad + (int64_t)w * stride;
@@ -53,10 +55,18 @@ __global__ __launch_bounds__(kSampleBlock) void k_sample(
 // threshold: the lower edge of the bucket at which the count from the top reaches
 // `target`.
 __global__ __launch_bounds__(kSampleBlock) void k_sample_pick(
-        const uint32_t* __restrict__ samp_hist, uint32_t target, uint32_t* __restrict__ tspec) {
+        const uint32_t* __restrict__ samp_hist, uint32_t target, uint32_t* __restrict__ tspec,
+        const uint4* __restrict__ carry) {
     __shared__ uint32_t s_wave[kSampleBlock / kWave];
     __shared__ uint32_t s_out[3];
     const int w = blockIdx.x;
+    if (carry) {
+        const uint4 c = carry[w];
+        if (c.x == 2u) {                          // block-uniform
+            if (threadIdx.x == 0) tspec[w] = c.w;
+            return;
+        }
+    }
     constexpr int kPer = kSampleBins / kSampleBlock;
     const uint32_t* hist = samp_hist + (size_t)w * kSampleBins;
     uint32_t loc[kPer];

@@ -79,6 +79,8 @@ class Device:
         self.ws = B.alloc_workspace(m, k, P)
         # a dirty workspace must not matter
         self.ws.fill_(0xA5)
+        # thresholds carried from call to call (gtopk_step_carry): zero = start from a sample
+        self.thr_state = torch.zeros((P, 4), dtype=torch.int32, device="cuda")
 
     def set_grad(self, g: np.ndarray):
         self.grad.copy_(self.torch.from_numpy(np.ascontiguousarray(g)))
@@ -102,6 +104,17 @@ class Device:
     def restore(self):
         self.B.gtopk_residual_restore(self.res, self.k, self.loc_idx, self.loc_val, self.g_idx)
         self.torch.cuda.synchronize()
+
+    def step_carry(self, want_loc=True):
+        self.B.gtopk_step_carry(self.grad, self.res, self.k, self.g_idx, self.g_val,
+                                self.loc_idx if want_loc else None,
+                                self.loc_val if want_loc else None, self.thr_state, self.ws)
+        self.torch.cuda.synchronize()
+        return idx_np(self.g_idx), val_np(self.g_val)
+
+    def carry_modes(self):
+        """Per worker: 0 nothing known, 1 learning (next call samples), 2 next call skips sampling."""
+        return self.thr_state[:, 0].cpu().numpy().tolist()
 
     def step(self, want_loc=True):
         self.B.gtopk_step(self.grad, self.res, self.k, self.g_idx, self.g_val,

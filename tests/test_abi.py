@@ -164,11 +164,18 @@ def test_argument_errors_allreduce_and_dense_topk():
 def test_argument_errors_timed_probe():
     lib = B.load()
     ws = B.gtopk_workspace_bytes(1000, 10, 2)
-    assert lib.gtopk_step_timed(FAKE, FAKE, 1000, 1000, 2, 10, FAKE, FAKE, FAKE, FAKE, FAKE, ws,
-                                None, None) == B.GTOPK_EINVAL
+    assert lib.gtopk_step_timed(FAKE, FAKE, 1000, 1000, 2, 10, FAKE, FAKE, FAKE, FAKE, None, FAKE,
+                                ws, None, None) == B.GTOPK_EINVAL
     ev = (ctypes.c_void_p * 6)(1, 2, 3, 0, 5, 6)               # one NULL handle
-    assert lib.gtopk_step_timed(FAKE, FAKE, 1000, 1000, 2, 10, FAKE, FAKE, FAKE, FAKE, FAKE, ws,
-                                None, ev) == B.GTOPK_EINVAL
+    assert lib.gtopk_step_timed(FAKE, FAKE, 1000, 1000, 2, 10, FAKE, FAKE, FAKE, FAKE, None, FAKE,
+                                ws, None, ev) == B.GTOPK_EINVAL
+    carry = lambda **kw: lib.gtopk_step_carry(FAKE, FAKE, 1000, 1000, kw.get("P", 2), 10, FAKE, FAKE,
+                                              FAKE, FAKE, kw.get("state", FAKE), FAKE,
+                                              kw.get("wsb", ws), None)
+    assert carry(state=None) == B.GTOPK_EINVAL
+    assert carry(state=ODD) == B.GTOPK_EALIGN
+    assert carry(P=3) == B.GTOPK_EINVAL
+    assert carry(wsb=8) == B.GTOPK_EWORKSPACE
     pr = lambda **kw: lib.gtopk_probe_stream(kw.get("a", FAKE), FAKE, kw.get("n", 32768),
                                              kw.get("mode", 0), kw.get("sink", FAKE), None)
     assert pr(a=None) == B.GTOPK_EINVAL

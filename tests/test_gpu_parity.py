@@ -256,6 +256,88 @@ def test_step_correlated_workers():
     check_steps(cfg, lambda it: W.correlated_gradients(cfg.m, cfg.P, it), 3, "correlated")
 
 
+def check_carry_steps(cfg, iters, label, event=None):
+    """gtopk_step_carry over `iters` iterations against the oracle.  `event(it, modes)` may
+    return (gradient scale, wipe residual) for an iteration.  Returns, per iteration, the
+    carry modes BEFORE the call (2 = that call skipped sampling), the candidate counts the
+    pass left, the list capacity and what `event` asked for."""
+    from paper_1901_04359_amd import binding as B
+    P, m, k = cfg.P, cfg.m, cfg.k
+    dev = Device(P, m, k)
+    res = np.zeros((P, m), dtype=np.float32)
+    dev.set_res(res)
+    trace = []
+    for it in range(iters):
+        modes = dev.carry_modes()
+        scale, wipe = event(it, modes) if event else (1.0, False)
+        g = W.gradients(cfg, it)
+        if scale != 1.0:
+            g = (g * np.float32(scale)).astype(np.float32)
+        if wipe:
+            res = np.zeros_like(res)
+            dev.set_res(res)
+        dev.set_grad(g)
+        say(f"step_carry {label} it={it} P={P} m={m} k={k} modes={modes} scale={scale} wipe={wipe}")
+        gi, gv = dev.step_carry()
+        counts, cap = B.gtopk_debug_candidate_counts(dev.ws, m, k, P)
+        exp = orc.step(res, g, k)
+        li, lv = idx_np(dev.loc_idx), val_np(dev.loc_val)
+        assert np.array_equal(li, exp["loc_idx"]), f"it={it} loc_idx {first_diff(li, exp['loc_idx'])}"
+        assert bits_equal(lv, exp["loc_val"]), f"it={it} loc_val {first_diff(lv, exp['loc_val'])}"
+        assert np.array_equal(gi, exp["g_idx"]), f"it={it} g_idx {first_diff(gi, exp['g_idx'])}"
+        assert bits_equal(gv, exp["g_val"]), f"it={it} g_val {first_diff(gv, exp['g_val'])}"
+        out = dev.residual()
+        assert bits_equal(out, exp["residual"]), f"it={it} residual {first_diff(out, exp['residual'])}"
+        res = exp["residual"]
+        trace.append((modes, counts, cap, (scale, wipe)))
+    return trace
+
+
+@pytest.mark.parametrize("base,m,P", [("C4a", 1_000_000, 8), ("C4b", 600_000, 4), ("C5", 800_001, 4)])
+def test_step_carry_matches_oracle_and_skips_sampling(base, m, P):
+    """Thresholds carried from call to call: every iteration bit-exact, and once the k-th
+    magnitudes move predictably the calls stop sampling while the pass still keeps between
+    k and the list's capacity of candidates."""
+    cfg = W.scaled(W.CONFIGS[base], m, P=P)
+    trace = check_carry_steps(cfg, 14, cfg.name)
+    assert trace[0][0] == [0] * P                       # the first call samples
+    skipped = [it for it, t in enumerate(trace) if all(md == 2 for md in t[0])]
+    assert len(skipped) >= 3, [t[0] for t in trace]     # the later calls do not
+    for it in skipped:
+        _, counts, cap, _ = trace[it]
+        assert all(cfg.k <= c <= cap for c in counts), (it, counts, cap, cfg.k)
+
+
+def test_step_carry_survives_jumps_of_the_magnitudes():
+    """A carried threshold that has become worthless costs time, never correctness.  Once the
+    calls have stopped sampling, the residual is wiped and the gradients shrunk (the k-th
+    magnitude drops by far: the pass comes back with fewer than k candidates); later the
+    gradients grow a thousand-fold (more candidates than the list holds).  The results stay
+    the oracle's and the call after each jump samples again."""
+    cfg = W.scaled(W.CONFIGS["C4a"], 700_001, P=4)
+    k = cfg.k
+    done = {"down": None, "up": None}
+
+    def event(it, modes):
+        trusted = all(md == 2 for md in modes)
+        if done["down"] is None and it >= 4 and trusted:
+            done["down"] = it
+            return 0.02, True
+        if done["down"] is not None and done["up"] is None and it >= done["down"] + 3 and trusted:
+            done["up"] = it
+            return 1000.0, False
+        return 1.0, False
+
+    trace = check_carry_steps(cfg, 24, "jumps", event)
+    assert done["down"] is not None and done["up"] is not None, (done, [t[0] for t in trace])
+    d, u = done["down"], done["up"]
+    assert all(c < k for c in trace[d][1]), (trace[d][1], k)            # came back short
+    assert all(md != 2 for md in trace[d + 1][0])                        # so the next call sampled
+    assert all(c > trace[u][2] for c in trace[u][1]), (trace[u][1], trace[u][2])   # overflowed
+    if u + 1 < len(trace):
+        assert all(md != 2 for md in trace[u + 1][0])
+
+
 def test_step_is_deterministic():
     cfg = W.scaled(W.CONFIGS["C4a"], 700_001, P=8)
     g = W.gradients(cfg, 0)
