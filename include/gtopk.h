@@ -126,6 +126,9 @@ int gtopk_residual_restore(float* residual, int64_t m, int64_t stride, int32_t P
  * One whole iteration of the hot path: gtopk_local_select, gtopk_tree and
  * gtopk_residual_restore in sequence, with bit-identical results.
  * loc_idx / loc_val may be NULL (then the local k-sets stay in the workspace).
+ * Small problems (P <= 64, k <= 512, P*k <= 4096, m <= 2^20 - 3) run as six kernels: the
+ * exact local selection of a worker in one block, the whole tree with the average and the
+ * extra residual in one block.
  */
 int gtopk_step(const float* grad, float* residual, int64_t m, int64_t stride,
                int32_t P, int32_t k, uint32_t* g_idx, float* g_val,
@@ -280,7 +283,9 @@ int gtopk_debug_candidate_counts(const void* ws, int64_t m, int32_t k, int32_t P
  *   plan[5] pass_histogram  1 if the streaming pass counts the first digits of its
  *                        candidates itself (the dense-row fallback then uses a histogram
  *                        of its own), 0 if the select's histogram kernel does
- *   plan[6] small_path   1 if these sizes take the few-launch path for small problems
+ *   plan[6] small_path   1 if gtopk_step takes the few-launch path for small problems at
+ *                        these sizes (gtopk_step_carry, gtopk_step_timed and the stand-alone
+ *                        calls always take the general kernels)
  *   plan[7] reserved (0)
  */
 #define GTOPK_PLAN_WORDS 8

@@ -30,6 +30,7 @@
 #include "merge.hip.h"
 #include "apply.hip.h"
 #include "aggregate.hip.h"
+#include "small.hip.h"
 
 using namespace gtopk;
 
@@ -188,6 +189,13 @@ uint32_t cand_capacity(int64_t m, uint32_t k) {
     return (uint32_t)cap;
 }
 
+// Small problems take the few-launch path: the local selection of a worker in one block,
+// the whole tree with the average and the extra residual in one block.
+static bool small_problem(int64_t m, int64_t k, int64_t P) {
+    return P <= kSmallMaxP && k <= kSmallMaxK && P * k <= kSmallMaxEntries &&
+           m + 3 <= (int64_t)kSmallMaxChunks * kSmallChunk;
+}
+
 struct SamplePlan { uint32_t tile_stride, n_tiles, target; };
 SamplePlan plan_sample(int64_t m, uint32_t k);
 
@@ -213,7 +221,9 @@ StepWs carve_step(void* ws, int64_t m, uint32_t k, uint32_t P) {
     s.tspec = c.take<uint32_t>(P);
     s.cand_idx = c.take<uint32_t>((size_t)P * s.cap);
     s.cand_val = c.take<float>((size_t)P * s.cap);
-    s.run_table = c.take<uint2>((size_t)P * s.nchunks);
+    // (the few-launch path for small problems cuts a row into runs of 4096 elements)
+    const uint32_t nruns_small = small_problem(m, k, P) ? ceil_div((uint64_t)m + 3, kSmallChunk) : 0u;
+    s.run_table = c.take<uint2>((size_t)P * (s.nchunks > nruns_small ? s.nchunks : nruns_small));
     s.run_off = c.take<uint32_t>((size_t)P * s.nchunks);
     s.ord_idx = c.take<uint32_t>((size_t)P * s.cap);
     s.ord_val = c.take<float>((size_t)P * s.cap);
@@ -625,6 +635,29 @@ static int step_impl(const float* grad, float* residual, int64_t m, int64_t stri
     hipStream_t st = (hipStream_t)stream;
     uint32_t* li = loc_idx ? loc_idx : w.loc_idx;
     float* lv = loc_val ? loc_val : w.loc_val;
+    if (!events && !thr_state && small_problem(m, k, P)) {
+        zero_async(st, zero_job(w.samp_hist, (size_t)(w.tspec - w.samp_hist)));
+        const SamplePlan sp = plan_sample(m, (uint32_t)k);
+        uint32_t sblocks = ceil_div(sp.n_tiles, (kSampleBlock / kSampleTile) * 8);
+        const uint32_t sb_max = P >= 64 ? 4u : (P <= 16 ? 16u : 256u / (uint32_t)P);
+        sblocks = sblocks > sb_max ? sb_max : (sblocks < 1 ? 1 : sblocks);
+        hipLaunchKernelGGL(k_sample, dim3(sblocks, P), dim3(kSampleBlock), 0, st, grad, residual,
+                           (uint32_t)m, stride, sp.tile_stride, sp.n_tiles, w.samp_hist,
+                           (const uint4*)nullptr);
+        hipLaunchKernelGGL(k_sample_pick, dim3(P), dim3(kSampleBlock), 0, st, w.samp_hist, sp.target,
+                           w.tspec, (const uint4*)nullptr);
+        // small blocks: one run per 4096 elements (the run table was carved for that many)
+        const uint32_t nruns = ceil_div((uint64_t)m + 3, kSmallChunk);
+        hipLaunchKernelGGL((k_accum_filter<false, kSmallIters>), dim3(nruns, P), dim3(kSBlock), 0, st,
+                           grad, residual, (uint32_t)m, stride, w.tspec, w.cand_idx, w.cand_val, w.cap,
+                           w.cand_count, w.run_table, nruns, w.sel.hist);
+        CandSrc src = cand_source(residual, stride, m, (uint32_t)k, w, false, false);
+        src.nchunks = nruns;
+        hipLaunchKernelGGL(k_small_select, dim3(P), dim3(kSmallBlock), 0, st, src, (uint32_t)k, li, lv);
+        hipLaunchKernelGGL(k_small_tree, dim3(1), dim3(kSmallBlock), 0, st, li, lv, (uint32_t)P,
+                           (uint32_t)k, g_idx, g_val, (float)P, residual, stride);
+        return launch_status();
+    }
     mark_stage(0, events, st);
     // one clear for everything this step needs zeroed: the sampler's histograms and the
     // candidate counters; both selects' histograms and tickets; the global-set bitmap
@@ -823,7 +856,7 @@ int gtopk_debug_plan(int64_t m, int32_t k, int32_t P, uint32_t* plan) {
     plan[3] = sp.target;
     plan[4] = cand_capacity(m, (uint32_t)k);
     plan[5] = pass_histograms(m, (uint32_t)k) ? 1u : 0u;
-    plan[6] = 0u;
+    plan[6] = small_problem(m, k, P) ? 1u : 0u;
     plan[7] = 0u;
     return GTOPK_OK;
 }

@@ -84,6 +84,8 @@ __global__ __launch_bounds__(kSampleBlock) void k_sample_pick(
 //
 // Block (chunk, w) handles virtual positions [chunk*32768, +32768) of worker w; each of
 // its 8 waves a contiguous 4096 of them, 16 float4 per lane, all held in registers.
+// (ITERS float4 per lane in general: 2048 * ITERS positions per block.  Short rows of few
+// workers take small blocks, so that they spread over more than a handful of CUs.)
 // Phase 1 loads, adds, stores and counts the entries whose key reaches the speculative
 // threshold; one atomicAdd per block reserves a contiguous range ("run") of the worker's
 // candidate list; phase 2 writes the block's candidates there in index order.
@@ -93,7 +95,7 @@ __global__ __launch_bounds__(kSampleBlock) void k_sample_pick(
 // (what the select's histogram kernel would read back), through an LDS histogram: one
 // global atomic per non-empty bin.  (One global atomic per candidate is as good where the
 // candidates are spread evenly, and far worse where they crowd into a few blocks.)
-template <bool HIST>
+template <bool HIST, int ITERS = kIters>
 __global__ __launch_bounds__(kSBlock) void k_accum_filter(
         const float* __restrict__ grad, float* __restrict__ res, uint32_t m, int64_t stride,
         const uint32_t* __restrict__ tspec, uint32_t* __restrict__ cand_idx,
@@ -117,20 +119,21 @@ __global__ __launch_bounds__(kSBlock) void k_accum_filter(
     const uint32_t vend = head + m;          // <= 2^31 + 3
     const uint32_t ts = tspec[w];
     // chunk < ceil((m + 3) / 32768), so none of the offsets below wraps
-    const uint32_t wbase = chunk * (uint32_t)kChunk + wave * (uint32_t)kWaveSpan;
+    constexpr uint32_t kSpan = ITERS * 4 * kWave;            // elements per wave
+    const uint32_t wbase = chunk * (kSpan * (uint32_t)kWaves) + wave * kSpan;
 
-    float a[kIters][4];
-    const bool whole = wbase >= head && wbase + (uint32_t)kWaveSpan <= vend;   // wave-uniform
+    float a[ITERS][4];
+    const bool whole = wbase >= head && wbase + kSpan <= vend;   // wave-uniform
     if (whole) {
-        floatx4 gv[kIters], rv[kIters];
+        floatx4 gv[ITERS], rv[ITERS];
 #pragma unroll
-        for (int i = 0; i < kIters; ++i) {
+        for (int i = 0; i < ITERS; ++i) {
             const uint32_t v = wbase + i * 256 + lane * 4;
             gv[i] = __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(g + v));
             rv[i] = __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(r + v));
         }
 #pragma unroll
-        for (int i = 0; i < kIters; ++i) {
+        for (int i = 0; i < ITERS; ++i) {
             const uint32_t v = wbase + i * 256 + lane * 4;
             const floatx4 s = rv[i] + gv[i];          // four independent fp32 adds
             __builtin_nontemporal_store(s, reinterpret_cast<floatx4*>(r + v));
@@ -138,7 +141,7 @@ __global__ __launch_bounds__(kSBlock) void k_accum_filter(
         }
     } else {
 #pragma unroll
-        for (int i = 0; i < kIters; ++i) {
+        for (int i = 0; i < ITERS; ++i) {
             const uint32_t v = wbase + i * 256 + lane * 4;
             if (v >= head && v + 4 <= vend) {
                 const floatx4 s = *reinterpret_cast<const floatx4*>(r + v) +
@@ -161,7 +164,7 @@ __global__ __launch_bounds__(kSBlock) void k_accum_filter(
 
     uint32_t cnt = 0;   // wave-uniform
 #pragma unroll
-    for (int i = 0; i < kIters; ++i) {
+    for (int i = 0; i < ITERS; ++i) {
         const uint32_t v = wbase + i * 256 + lane * 4;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -189,7 +192,7 @@ __global__ __launch_bounds__(kSBlock) void k_accum_filter(
     uint32_t* ci = cand_idx + (size_t)w * cap;
     float* cv = cand_val + (size_t)w * cap;
 #pragma unroll
-    for (int i = 0; i < kIters; ++i) {
+    for (int i = 0; i < ITERS; ++i) {
         const uint32_t v = wbase + i * 256 + lane * 4;
         bool c[4];
         uint64_t b[4];

@@ -197,6 +197,13 @@ def test_debug_plan_describes_the_sampler():
     assert small["tile_stride"] == small["tile_len"] and small["target"] == 50
     with pytest.raises(B.GtopkError):
         B.gtopk_debug_plan(100, 0, 2)
+    # which sizes gtopk_step runs as its few-launch path for small problems
+    assert B.gtopk_debug_plan(65_536, 66, 4)["small_path"] == 1
+    assert B.gtopk_debug_plan(269_722, 270, 8)["small_path"] == 1
+    assert B.gtopk_debug_plan(14_728_266, 14_728, 16)["small_path"] == 0
+    assert B.gtopk_debug_plan(100_000, 513, 2)["small_path"] == 0
+    assert B.gtopk_debug_plan(100_000, 100, 128)["small_path"] == 0
+    assert B.gtopk_debug_plan(1_048_574, 10, 2)["small_path"] == 0
 
 
 def test_argument_errors_step_static():

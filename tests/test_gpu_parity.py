@@ -215,7 +215,9 @@ def test_restore_parity(P, m, k):
         assert bits_equal(out[w], exp), f"w={w}: {first_diff(out[w], exp)}"
 
 
-def check_steps(cfg, grads_of_iter, iters, label, want_loc=True):
+def check_steps(cfg, grads_of_iter, iters, label, want_loc=True, general=False):
+    """`general`: go through gtopk_step_carry, which always takes the general kernels (small
+    problems otherwise take gtopk_step's few-launch path)."""
     P, m, k = cfg.P, cfg.m, cfg.k
     dev = Device(P, m, k)
     res = np.zeros((P, m), dtype=np.float32)
@@ -223,8 +225,8 @@ def check_steps(cfg, grads_of_iter, iters, label, want_loc=True):
     for it in range(iters):
         g = grads_of_iter(it)
         dev.set_grad(g)
-        say(f"step {label} it={it} P={P} m={m} k={k}")
-        gi, gv = dev.step(want_loc=want_loc)
+        say(f"step {label} it={it} P={P} m={m} k={k} general={general}")
+        gi, gv = dev.step_carry(want_loc=want_loc) if general else dev.step(want_loc=want_loc)
         exp = orc.step(res, g, k)
         if want_loc:
             li, lv = idx_np(dev.loc_idx), val_np(dev.loc_val)
@@ -237,10 +239,13 @@ def check_steps(cfg, grads_of_iter, iters, label, want_loc=True):
         res = exp["residual"]
 
 
+@pytest.mark.parametrize("general", [False, True])
 @pytest.mark.parametrize("name", ["C1", "C2"])
-def test_step_configs_all_iterations(name):
+def test_step_configs_all_iterations(name, general):
+    from paper_1901_04359_amd import binding as B
     cfg = W.CONFIGS[name]
-    check_steps(cfg, lambda it: W.gradients(cfg, it), cfg.iters, name)
+    assert B.gtopk_debug_plan(cfg.m, cfg.k, cfg.P)["small_path"] == 1     # the two small configs
+    check_steps(cfg, lambda it: W.gradients(cfg, it), cfg.iters, name, general=general)
 
 
 @pytest.mark.parametrize("base,m,P", [("C3", 500_009, 16), ("C4a", 1_000_000, 32),
@@ -428,7 +433,8 @@ def test_step_density_schedule(rho, m):
     (256, 5_000, 50, None),           # eight rounds, 128 pairs in the first
     (4, 300_001, 3_000, 300_005),     # padded rows, odd stride
 ])
-def test_step_shapes(P, m, k, stride):
+@pytest.mark.parametrize("general", [False, True])
+def test_step_shapes(P, m, k, stride, general):
     rng = np.random.default_rng(P * 7 + m + k)
     dev = Device(P, m, k, stride=stride)
     res = np.zeros((P, m), dtype=np.float32)
@@ -436,8 +442,8 @@ def test_step_shapes(P, m, k, stride):
     for it in range(2):
         g = (rng.standard_normal((P, m)) * 1e-3).astype(np.float32)
         dev.set_grad(g)
-        say(f"step shapes P={P} m={m} k={k} stride={stride} it={it}")
-        gi, gv = dev.step()
+        say(f"step shapes P={P} m={m} k={k} stride={stride} it={it} general={general}")
+        gi, gv = dev.step_carry() if general else dev.step()
         exp = orc.step(res, g, k)
         assert np.array_equal(idx_np(dev.loc_idx), exp["loc_idx"])
         assert bits_equal(val_np(dev.loc_val), exp["loc_val"])
@@ -448,6 +454,56 @@ def test_step_shapes(P, m, k, stride):
     if stride is not None:      # the padding between rows must be untouched
         pad = dev.res_buf[: P * stride].view(P, stride)[:, m:].cpu().numpy()
         assert not pad.any()
+
+
+@pytest.mark.parametrize("kind", ["all_equal", "all_zero", "special", "few_levels", "one_spike", "under"])
+@pytest.mark.parametrize("P,m,k", [(4, 65_536, 66), (8, 300_000, 300), (64, 9_000, 64),
+                                   (8, 1_048_573, 512), (2, 700, 512)])
+def test_small_path_degenerate_rows_and_limits(kind, P, m, k):
+    """gtopk_step's few-launch path (one block per worker, one block for the tree) at the
+    limits of the sizes it takes, on rows that make a worker fall back to its dense row
+    inside that block, next to ordinary workers."""
+    from paper_1901_04359_amd import binding as B
+    plan = B.gtopk_debug_plan(m, k, P)
+    assert plan["small_path"] == 1
+    rng = np.random.default_rng(P + m + k)
+    g = (rng.standard_normal((P, m)) * 1e-3).astype(np.float32)
+    for w in range(0, P, 2):                  # every other worker is a special row
+        if kind == "all_equal":
+            g[w] = np.where(rng.random(m) < 0.5, -1, 1).astype(np.float32) * np.float32(0.125)
+        elif kind == "all_zero":
+            g[w] = 0.0
+            g[w, ::3] = -0.0
+        elif kind == "special":
+            g[w] = W.special_values(m, seed=w)
+        elif kind == "few_levels":
+            g[w] = rng.integers(-1, 2, m).astype(np.float32) * np.float32(0.5)
+        elif kind == "one_spike":
+            g[w] = 0.0
+            g[w, m // 3] = 7.0
+        else:                                  # large magnitudes only where the sampler looks
+            t = np.arange(plan["n_tiles"], dtype=np.int64)[:, None] * plan["tile_stride"]
+            pos = (t + np.arange(plan["tile_len"], dtype=np.int64)[None, :]).ravel()
+            pos = pos[pos < m]
+            if pos.size < m and plan["target"] < k - 1:
+                at = rng.choice(pos, min(pos.size, k - 1), replace=False)
+                g[w, at] = (1.0 + rng.random(at.size)).astype(np.float32)
+    dev = Device(P, m, k)
+    res = np.zeros((P, m), dtype=np.float32)
+    dev.set_res(res)
+    for it in range(2):
+        dev.set_grad(g)
+        say(f"small path kind={kind} P={P} m={m} k={k} it={it}")
+        gi, gv = dev.step()
+        exp = orc.step(res, g, k)
+        assert np.array_equal(idx_np(dev.loc_idx), exp["loc_idx"]), first_diff(idx_np(dev.loc_idx), exp["loc_idx"])
+        assert bits_equal(val_np(dev.loc_val), exp["loc_val"])
+        assert np.array_equal(gi, exp["g_idx"]), first_diff(gi, exp["g_idx"])
+        assert bits_equal(gv, exp["g_val"]), first_diff(gv, exp["g_val"])
+        out = dev.residual()
+        assert bits_equal(out, exp["residual"]), first_diff(out, exp["residual"])
+        res = exp["residual"]
+        g = (rng.standard_normal((P, m)) * 1e-3).astype(np.float32)     # then ordinary gradients
 
 
 def test_step_matches_the_three_calls():
@@ -630,8 +686,9 @@ def _random_shape_cases(n, seed):
     return cases
 
 
+@pytest.mark.parametrize("general", [False, True])
 @pytest.mark.parametrize("P,m,k,kind,pad", _random_shape_cases(48, 20260427))
-def test_step_random_shapes(P, m, k, kind, pad):
+def test_step_random_shapes(P, m, k, kind, pad, general):
     """Seeded random problem shapes (tiny rows, k = m, k = 1, odd strides) and value kinds,
     two iterations each with the residual carried."""
     rng = np.random.default_rng(P * 1_000_003 + m * 31 + k)
@@ -648,8 +705,8 @@ def test_step_random_shapes(P, m, k, kind, pad):
         else:
             g = np.where(rng.random((P, m)) < 0.02, rng.standard_normal((P, m)), 0.0).astype(np.float32)
         dev.set_grad(g)
-        say(f"random shape P={P} m={m} k={k} kind={kind} pad={pad} it={it}")
-        gi, gv = dev.step()
+        say(f"random shape P={P} m={m} k={k} kind={kind} pad={pad} it={it} general={general}")
+        gi, gv = dev.step_carry() if general else dev.step()
         exp = orc.step(res, g, k)
         assert np.array_equal(idx_np(dev.loc_idx), exp["loc_idx"])
         assert bits_equal(val_np(dev.loc_val), exp["loc_val"])
