@@ -380,12 +380,21 @@ def main() -> int:
                         "note": "per step of the second pass, first to last HIP event of the step"},
         "roofline": {"kernel": "k_accum_filter", "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": traffic, "launch_ms": kern_ms,
+                     "traffic": traffic,
+                     "traffic_source": ("profiles/k_accum_filter_traffic.txt: rocprofv3 --pmc FETCH_SIZE / "
+                                        "WRITE_SIZE per dispatch, scaled by a 1 GiB copy's readings; a "
+                                        "committed summary, not measured in this run"
+                                        if traffic else None),
+                     "launch_ms": kern_ms,
                      "measured": "HIP events around the kernel in a second pass over the same K steps",
                      "algorithmic_bytes_per_launch": alg_bytes},
         "input_generation_s": round(t_gen, 1),
         "entry_point": "gtopk_step" if thr_state is None else "gtopk_step_carry",
     }
+    if thr_state is None and B.gtopk_debug_plan(m, k, P)["small_path"]:
+        out["stages_note"] = ("this problem is small enough for gtopk_step's few-launch path, which `value` "
+                              "and ms_per_step time; the second pass (gtopk_step_timed) runs the general "
+                              "kernels, so stages_ms and roofline describe those")
     if thr_state is not None:
         out["carried_thresholds"] = {
             "workers_not_sampling_after_timed_steps": sum(1 for md in modes_after_timed if md == 2),
