@@ -50,9 +50,12 @@ extern "C" {
 typedef enum {
     GTOPK_OK = 0,
     GTOPK_EINVAL = -1,     /* null pointer; m < 1 or m > 2^31; k < 1 or k > m; k > 2^30 where
-                              sets are merged; P < 1 or not a power of two (the paper assumes
-                              a power of two, Section III); stride < m; batch < 1 or
-                              batch > 32767; k-set stride < k                                 */
+                              sets are merged (gtopk_merge, gtopk_tree, and the step calls
+                              with P > 1: a merged pair has 2k slots); P < 1, P > 32768 or not
+                              a power of two (the paper assumes a power of two, Section III);
+                              stride < m; batch < 1 or batch > 32767; k-set stride < k;
+                              copies < 1 or > 65535 (gtopk_apply_update); P > 1024
+                              (gtopk_topk_allreduce, which takes any P from 1 on)            */
     GTOPK_EWORKSPACE = -2, /* ws_bytes smaller than the matching *_workspace_bytes query   */
     GTOPK_EALIGN = -3,     /* a pointer is not 16-byte aligned                              */
     GTOPK_EHIP = -4        /* a kernel launch failed (hipGetLastError)                      */
@@ -78,6 +81,8 @@ size_t gtopk_merge_workspace_bytes(int32_t k, int32_t batch);
  *   m, stride             : elements per worker and distance between rows (>= m)
  *   out_idx   [P][k] out  : indices of the k selected entries of each worker, ascending
  *   out_val   [P][k] out  : acc at those indices, bit for bit (line 7)
+ *   m : 1 .. 2^31;  k : 1 .. m;  P : a power of two, 1 .. 32768 (the limit of the step
+ *   calls, whose workspace this call shares);  ws : gtopk_workspace_bytes(m, k, P) bytes
  */
 int gtopk_local_select(const float* grad, float* residual, int64_t m, int64_t stride,
                        int32_t P, int32_t k, uint32_t* out_idx, float* out_val,
@@ -108,6 +113,8 @@ int gtopk_merge(const uint32_t* a_idx, const float* a_val,
  *
  *   loc_idx, loc_val [P][k] in : the workers' local k-sets (not modified)
  *   g_idx, g_val     [k]   out : the global k-set; values are the tree's sums / P
+ *   P : a power of two, 1 .. 32768;  k : 1 .. 2^30;  ws : gtopk_workspace_bytes(k, k, P) bytes
+ *       or more (any m >= k gives enough)
  */
 int gtopk_tree(const uint32_t* loc_idx, const float* loc_val, int32_t P, int32_t k,
                uint32_t* g_idx, float* g_val, void* ws, size_t ws_bytes, void* stream);
@@ -129,6 +136,8 @@ int gtopk_residual_restore(float* residual, int64_t m, int64_t stride, int32_t P
  * Small problems (P <= 64, k <= 512, P*k <= 4096, m <= 2^20 - 3) run as six kernels: the
  * exact local selection of a worker in one block, the whole tree with the average and the
  * extra residual in one block.
+ *   m : 1 .. 2^31;  k : 1 .. m (and <= 2^30 if P > 1);  P : a power of two, 1 .. 32768;
+ *   stride >= m;  ws : gtopk_workspace_bytes(m, k, P) bytes
  */
 int gtopk_step(const float* grad, float* residual, int64_t m, int64_t stride,
                int32_t P, int32_t k, uint32_t* g_idx, float* g_val,
