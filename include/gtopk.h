@@ -133,9 +133,10 @@ int gtopk_residual_restore(float* residual, int64_t m, int64_t stride, int32_t P
  * One whole iteration of the hot path: gtopk_local_select, gtopk_tree and
  * gtopk_residual_restore in sequence, with bit-identical results.
  * loc_idx / loc_val may be NULL (then the local k-sets stay in the workspace).
- * Small problems (P <= 64, k <= 512, P*k <= 4096, m <= 2^20 - 3) run as six kernels: the
- * exact local selection of a worker in one block, the whole tree with the average and the
- * extra residual in one block.
+ * Small problems (P <= 64, k <= 512, P*k <= 4096, m <= 2^20 - 3) run as four kernels: the
+ * speculative threshold of a worker in one block, the streaming pass, the exact local
+ * selection of a worker in one block, the whole tree with the average and the extra
+ * residual in one block.
  *   m : 1 .. 2^31;  k : 1 .. m (and <= 2^30 if P > 1);  P : a power of two, 1 .. 32768;
  *   stride >= m;  ws : gtopk_workspace_bytes(m, k, P) bytes
  */
@@ -296,8 +297,11 @@ int gtopk_debug_candidate_counts(const void* ws, int64_t m, int32_t k, int32_t P
  *                        these sizes (gtopk_step_carry, gtopk_step_timed and the stand-alone
  *                        calls always take the general kernels)
  *   plan[7] reserved (0)
+ *   plan[8] small_tile_stride, plan[9] small_n_tiles, plan[10] small_target: the sampler of
+ *                        the few-launch path (same tile_len; all 0 where plan[6] is 0)
+ *   plan[11] reserved (0)
  */
-#define GTOPK_PLAN_WORDS 8
+#define GTOPK_PLAN_WORDS 12
 int gtopk_debug_plan(int64_t m, int32_t k, int32_t P, uint32_t* plan);
 
 #ifdef __cplusplus

@@ -197,7 +197,11 @@ static bool small_problem(int64_t m, int64_t k, int64_t P) {
 }
 
 struct SamplePlan { uint32_t tile_stride, n_tiles, target; };
-SamplePlan plan_sample(int64_t m, uint32_t k);
+// (the few-launch path takes a smaller sample: one block per worker reads it)
+constexpr double kSampleMean = 256.0, kSampleMinTiles = 4096.0;
+constexpr double kSmallSampleMean = 16.0, kSmallSampleMinTiles = 128.0;
+SamplePlan plan_sample(int64_t m, uint32_t k, double sample_mean = kSampleMean,
+                       double min_tiles = kSampleMinTiles);
 
 StepWs carve_step(void* ws, int64_t m, uint32_t k, uint32_t P) {
     Carver c{reinterpret_cast<char*>(ws)};
@@ -316,12 +320,12 @@ void run_select(const Src& src, const SelState& ss, const SelGrid& gr, uint32_t 
 // expected sample rank of the k-th key plus 5.5 standard deviations, so that the
 // candidate list holds at least k entries except with probability ~1e-8 per worker
 // (and then that worker is merely selected from its dense row).
-SamplePlan plan_sample(int64_t m, uint32_t k) {
-    const double kSampleMean = 256.0;        // expected sample rank of the k-th key, at least
-    const double kMinTiles = 4096.0;         // spread: a layer of 1 % of the row still gets ~40 tiles
+// sample_mean: expected sample rank of the k-th key, at least.  min_tiles: spread (with
+// 4096, a layer of 1 % of the row still gets ~40 tiles).
+SamplePlan plan_sample(int64_t m, uint32_t k, double sample_mean, double min_tiles) {
     SamplePlan p;
-    double want = kSampleMean * (double)m / (double)k;
-    if (want < kMinTiles * kSampleTile) want = kMinTiles * kSampleTile;
+    double want = sample_mean * (double)m / (double)k;
+    if (want < min_tiles * kSampleTile) want = min_tiles * kSampleTile;
     if (want >= (double)m) {
         p.tile_stride = kSampleTile;
     } else {
@@ -636,16 +640,11 @@ static int step_impl(const float* grad, float* residual, int64_t m, int64_t stri
     uint32_t* li = loc_idx ? loc_idx : w.loc_idx;
     float* lv = loc_val ? loc_val : w.loc_val;
     if (!events && !thr_state && small_problem(m, k, P)) {
-        zero_async(st, zero_job(w.samp_hist, (size_t)(w.tspec - w.samp_hist)));
-        const SamplePlan sp = plan_sample(m, (uint32_t)k);
-        uint32_t sblocks = ceil_div(sp.n_tiles, (kSampleBlock / kSampleTile) * 8);
-        const uint32_t sb_max = P >= 64 ? 4u : (P <= 16 ? 16u : 256u / (uint32_t)P);
-        sblocks = sblocks > sb_max ? sb_max : (sblocks < 1 ? 1 : sblocks);
-        hipLaunchKernelGGL(k_sample, dim3(sblocks, P), dim3(kSampleBlock), 0, st, grad, residual,
-                           (uint32_t)m, stride, sp.tile_stride, sp.n_tiles, w.samp_hist,
-                           (const uint4*)nullptr);
-        hipLaunchKernelGGL(k_sample_pick, dim3(P), dim3(kSampleBlock), 0, st, w.samp_hist, sp.target,
-                           w.tspec, (const uint4*)nullptr);
+        // one block per worker samples, picks the threshold and clears the candidate counter
+        const SamplePlan sp = plan_sample(m, (uint32_t)k, kSmallSampleMean, kSmallSampleMinTiles);
+        hipLaunchKernelGGL(k_small_sample, dim3(P), dim3(kSmallBlock), 0, st, grad, residual,
+                           (uint32_t)m, stride, sp.tile_stride, sp.n_tiles, sp.target, w.tspec,
+                           w.cand_count);
         // small blocks: one run per 4096 elements (the run table was carved for that many)
         const uint32_t nruns = ceil_div((uint64_t)m + 3, kSmallChunk);
         hipLaunchKernelGGL((k_accum_filter<false, kSmallIters>), dim3(nruns, P), dim3(kSBlock), 0, st,
@@ -858,6 +857,13 @@ int gtopk_debug_plan(int64_t m, int32_t k, int32_t P, uint32_t* plan) {
     plan[5] = pass_histograms(m, (uint32_t)k) ? 1u : 0u;
     plan[6] = small_problem(m, k, P) ? 1u : 0u;
     plan[7] = 0u;
+    plan[8] = plan[9] = plan[10] = plan[11] = 0u;
+    if (plan[6]) {
+        const SamplePlan ss = plan_sample(m, (uint32_t)k, kSmallSampleMean, kSmallSampleMinTiles);
+        plan[8] = ss.tile_stride;
+        plan[9] = ss.n_tiles;
+        plan[10] = ss.target;
+    }
     return GTOPK_OK;
 }
 

@@ -198,7 +198,12 @@ def test_debug_plan_describes_the_sampler():
     with pytest.raises(B.GtopkError):
         B.gtopk_debug_plan(100, 0, 2)
     # which sizes gtopk_step runs as its few-launch path for small problems
-    assert B.gtopk_debug_plan(65_536, 66, 4)["small_path"] == 1
+    c1 = B.gtopk_debug_plan(65_536, 66, 4)
+    assert c1["small_path"] == 1
+    # the few-launch path samples less: one block per worker reads it
+    assert 0 < c1["small_n_tiles"] * c1["tile_len"] <= c1["n_tiles"] * c1["tile_len"]
+    assert c1["small_target"] >= 1 and c1["small_tile_stride"] >= c1["tile_len"]
+    assert B.gtopk_debug_plan(14_728_266, 14_728, 16)["small_n_tiles"] == 0
     assert B.gtopk_debug_plan(269_722, 270, 8)["small_path"] == 1
     assert B.gtopk_debug_plan(14_728_266, 14_728, 16)["small_path"] == 0
     assert B.gtopk_debug_plan(100_000, 513, 2)["small_path"] == 0

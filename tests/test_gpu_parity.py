@@ -482,10 +482,10 @@ def test_small_path_degenerate_rows_and_limits(kind, P, m, k):
             g[w] = 0.0
             g[w, m // 3] = 7.0
         else:                                  # large magnitudes only where the sampler looks
-            t = np.arange(plan["n_tiles"], dtype=np.int64)[:, None] * plan["tile_stride"]
+            t = np.arange(plan["small_n_tiles"], dtype=np.int64)[:, None] * plan["small_tile_stride"]
             pos = (t + np.arange(plan["tile_len"], dtype=np.int64)[None, :]).ravel()
             pos = pos[pos < m]
-            if pos.size < m and plan["target"] < k - 1:
+            if pos.size < m and plan["small_target"] < k - 1:
                 at = rng.choice(pos, min(pos.size, k - 1), replace=False)
                 g[w, at] = (1.0 + rng.random(at.size)).astype(np.float32)
     dev = Device(P, m, k)
