@@ -166,7 +166,7 @@ __global__ __launch_bounds__(BLOCK) void k_union(
         mv[x + pa[j]] = sum;
         const bool dup = pb[j] > 0 && A_idx(pb[j] - 1) == ib[j];
         mi[x + pb[j]] = dup ? kTomb : ib[j];
-        mv[x + pb[j]] = fb[j];
+        mv[x + pb[j]] = dup ? 0.0f : fb[j];         // a tombstone's value is +0.0 (see MergedSrc)
         if (HIST) {
             // the first digit of the keys this block has just produced (what k_hist would
             // read back): LDS counts now, one global add per bin and block below
@@ -357,7 +357,7 @@ __global__ __launch_bounds__(BLOCK) void k_union_path(
                 a = sa[x];
             } else {
                 oi[j] = b == aprev ? kTomb : b;
-                ov[j] = sbv[y];
+                ov[j] = b == aprev ? 0.0f : sbv[y];  // a tombstone's value is +0.0 (see MergedSrc)
                 ++y;
                 b = sb[y];
             }

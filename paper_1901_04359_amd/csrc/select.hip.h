@@ -62,6 +62,9 @@ struct SelState {
 // counts (run_off[w][chunk] = first logical position of the run), and k_bucket's walk
 // copies the candidates into index order on the side.
 struct CandSrc {
+    static constexpr bool kValueOnlyWalk = false;
+    __device__ uint32_t fetch_bits(int, uint32_t) const { return 0u; }
+    __device__ bool is_tomb(int, uint32_t) const { return false; }
     static constexpr bool kIdentity = false;
     static constexpr bool kRunScan = true;
     const float* res;
@@ -213,6 +216,12 @@ struct CandSrc {
 struct MergedSrc {
     static constexpr bool kIdentity = true;
     static constexpr bool kRunScan = false;
+    // A tombstone's value is +0.0: its key falls into the lowest bin of either digit layout, so
+    // a walk that only counts keys ABOVE a bin, and looks closer only at keys INSIDE it, can
+    // read the values alone and ask is_tomb() for the few slots inside the bin.
+    static constexpr bool kValueOnlyWalk = true;
+    __device__ uint32_t fetch_bits(int s, uint32_t p) const { return __float_as_uint(val[(size_t)s * stride + p]); }
+    __device__ bool is_tomb(int s, uint32_t p) const { return idx[(size_t)s * stride + p] == kTomb; }
     const uint32_t* idx;
     const float* val;
     uint32_t n, stride, L;       // L slots per group
@@ -355,7 +364,12 @@ __device__ __forceinline__ void bucket_fast(const Src& src, const SelState& st, 
         for (int j = 0; j < kBatch; ++j) {
             const uint32_t p = i0 + j * kBlock + threadIdx.x;
             idx[j] = 0; bits[j] = 0;
-            ok[j] = p < end && src.fetch_phys(s, dn, p, idx[j], bits[j]);
+            if (Src::kValueOnlyWalk) {
+                ok[j] = p < end;
+                if (ok[j]) bits[j] = src.fetch_bits(s, p);
+            } else {
+                ok[j] = p < end && src.fetch_phys(s, dn, p, idx[j], bits[j]);
+            }
         }
 #pragma unroll
         for (int j = 0; j < kBatch; ++j) {
@@ -391,7 +405,8 @@ __device__ __forceinline__ void bucket_fast(const Src& src, const SelState& st, 
             const uint32_t key = bits[j] & kAbs;
             const uint32_t d = dg.bin(key);
             const bool above = ok[j] && d > d1;
-            const bool inside = ok[j] && d == d1;
+            bool inside = ok[j] && d == d1;
+            if (Src::kValueOnlyWalk && inside) inside = !src.is_tomb(s, p);
             const uint32_t lg = Src::kIdentity ? g : lp[j] / L;
             if (Src::kIdentity) gt += (uint32_t)__popcll(__ballot(above));
             else add_grouped(above, lg, ggt);
@@ -435,7 +450,8 @@ __device__ __forceinline__ void bucket_fast(const Src& src, const SelState& st, 
 #pragma unroll
         for (int j = 0; j < kBatch; ++j) {
             const uint32_t key = bits[j] & kAbs;
-            const bool inside = ok[j] && dg.bin(key) == d1;
+            bool inside = ok[j] && dg.bin(key) == d1;
+            if (Src::kValueOnlyWalk && inside) inside = !src.is_tomb(s, i0 + j * kBlock + threadIdx.x);
             const uint64_t inm = __ballot(inside);
             if (inside) {
                 const uint32_t pos = off + rank_in(inm);
