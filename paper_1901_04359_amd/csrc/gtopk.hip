@@ -197,6 +197,14 @@ static bool small_problem(int64_t m, int64_t k, int64_t P) {
 }
 
 struct SamplePlan { uint32_t tile_stride, n_tiles, target; };
+
+// Long candidate lists are selected where the streaming pass left them, one group per run
+// (RunSrc): from about 2048 expected candidates per chunk of the row on, and while the runs
+// of a row are no more than the select's group tables hold.
+static bool run_groups(int64_t m, uint32_t k) {
+    const double per_chunk = 1.4 * (double)k * (double)kChunk / (double)m;
+    return per_chunk >= 2048.0 && ceil_div((uint64_t)m + 3, kChunk) <= (uint64_t)kMaxGroups;
+}
 // (the few-launch path takes a smaller sample: one block per worker reads it)
 constexpr double kSampleMean = 256.0, kSampleMinTiles = 4096.0;
 constexpr double kSmallSampleMean = 16.0, kSmallSampleMinTiles = 128.0;
@@ -231,7 +239,11 @@ StepWs carve_step(void* ws, int64_t m, uint32_t k, uint32_t P) {
     s.run_off = c.take<uint32_t>((size_t)P * s.nchunks);
     s.ord_idx = c.take<uint32_t>((size_t)P * s.cap);
     s.ord_val = c.take<float>((size_t)P * s.cap);
-    s.sel = carve_select(c, P, s.cap, s.gcand > s.gdense ? s.gcand : s.gdense, /*with_dense_hist=*/true);
+    {
+        uint32_t g = s.gcand > s.gdense ? s.gcand : s.gdense;
+        if (run_groups(m, k) && s.nchunks > g) g = s.nchunks;      // one group per run
+        s.sel = carve_select(c, P, s.cap, g, /*with_dense_hist=*/true);
+    }
     const size_t pairs = P > 1 ? P / 2 : 1;
     s.mrg = carve_merge(c, k, pairs);
     s.x_idx = c.take<uint32_t>(pairs * k);
@@ -421,8 +433,16 @@ int do_local_select(const float* grad, float* residual, int64_t m, int64_t strid
     const CandSrc src = cand_source(residual, stride, m, k, w, producer_hist, false, thr_state);
     // the histogram kernel always runs: where the pass has counted its candidates it serves
     // only the workers that came back with fewer than k of them
-    run_select<CandSrc, false>(src, w.sel, local_grid(w, P), k, out_idx, out_val, (int64_t)k, 1.0f,
-                               nullptr, st);
+    if (run_groups(m, k)) {
+        SelGrid gr = local_grid(w, P);
+        if (gr.groups < w.nchunks) gr.groups = gr.walk_blocks = w.nchunks;
+        RunSrc rs;
+        static_cast<CandSrc&>(rs) = src;
+        run_select<RunSrc, false>(rs, w.sel, gr, k, out_idx, out_val, (int64_t)k, 1.0f, nullptr, st);
+    } else {
+        run_select<CandSrc, false>(src, w.sel, local_grid(w, P), k, out_idx, out_val, (int64_t)k, 1.0f,
+                                   nullptr, st);
+    }
     // a kernel of its own: while the select runs, a dense row may still be read as a whole
     if (zero_rows)
         hipLaunchKernelGGL(k_zero_selected, dim3(ceil_div(k, kBlock), P), dim3(kBlock), 0, st, out_idx,

@@ -62,6 +62,7 @@ struct SelState {
 // counts (run_off[w][chunk] = first logical position of the run), and k_bucket's walk
 // copies the candidates into index order on the side.
 struct CandSrc {
+    static constexpr bool kRunGroups = false;
     static constexpr bool kValueOnlyWalk = false;
     __device__ uint32_t fetch_bits(int, uint32_t) const { return 0u; }
     __device__ bool is_tomb(int, uint32_t) const { return false; }
@@ -145,6 +146,21 @@ struct CandSrc {
     }
     __device__ uint32_t nphys(int s, bool dn) const { return dn ? m : cand_count[s]; }
     __device__ uint32_t group_slots(bool dn) const { return dn ? Ld : Lc; }
+    // slots [first, end) that a block walks for group g of a set that is not a dense row
+    // (false: none); and the group of the item at physical slot p
+    __device__ bool group_range(int s, uint32_t g, uint32_t& first, uint32_t& end) const {
+        const uint32_t n = cand_count[s];
+        const uint64_t f = (uint64_t)g * Lc;
+        if (f >= n) return false;
+        first = (uint32_t)f;
+        end = (uint32_t)(f + Lc < n ? f + Lc : n);
+        return true;
+    }
+    __device__ uint32_t group_of(int s, bool dn, uint32_t p, uint32_t idx) const {
+        return logical(s, dn, p, idx) / group_slots(dn);
+    }
+    // ... and of the item that fetch_ord() reads at position lp
+    __device__ uint32_t group_of_ord(int, bool dn, uint32_t lp, uint32_t) const { return lp / group_slots(dn); }
     // Lower bound of the k-th key: the speculative threshold while at least k entries
     // reached it; for a worker with fewer the k-th key lies below it, and nothing bounds
     // it from below: plain coarse bins.
@@ -206,6 +222,38 @@ struct CandSrc {
     }
 };
 
+// The local select of LONG candidate lists (thousands of candidates per chunk of the row):
+// the groups are the runs themselves - group g of worker s is the run of chunk g, where the
+// streaming pass left it - so nothing is copied into index order: the walk of k_bucket
+// reads a run's values only, the emit reads the run's indices and values in place.  Runs
+// differ in length (0 .. 32768 entries); with hundreds of runs per worker the blocks even
+// out.  A worker that falls back to its dense row is handled as in CandSrc.
+struct RunSrc : CandSrc {
+    static constexpr bool kRunGroups = true;
+    static constexpr bool kValueOnlyWalk = true;
+    static constexpr bool kRunScan = false;
+    __device__ uint32_t fetch_bits(int s, uint32_t p) const { return __float_as_uint(cand_val[(size_t)s * cap + p]); }
+    __device__ bool is_tomb(int, uint32_t) const { return false; }
+    __device__ bool group_range(int s, uint32_t g, uint32_t& first, uint32_t& end) const {
+        if (g >= nchunks) return false;
+        const uint2 run = run_table[(size_t)s * nchunks + g];
+        if (run.y == 0u || run.x >= cap) return false;
+        first = run.x;
+        end = run.y < cap - run.x ? run.x + run.y : cap;        // never cut for a list the pass wrote
+        return true;
+    }
+    __device__ uint32_t group_of(int s, bool dn, uint32_t p, uint32_t idx) const {
+        if (dn) return p / Ld;
+        const uint32_t head = (uint32_t)(((int64_t)s * stride) & 3);
+        const uint32_t chunk = (idx + head) >> kChunkLog2;
+        return chunk < nchunks ? chunk : nchunks - 1;          // likewise
+    }
+    __device__ bool fetch_ord(int s, bool dn, uint32_t p, uint32_t& idx, uint32_t& bits) const {
+        return fetch_phys(s, dn, p, idx, bits);
+    }
+    __device__ uint32_t group_of_ord(int s, bool dn, uint32_t p, uint32_t idx) const { return group_of(s, dn, p, idx); }
+};
+
 // Merge: n = 2k slots per pair (rows `stride` slots apart), index-ascending, a slot with
 // index kTomb holds nothing.
 // Every key of the union that is a plain copy of an operand's entry is at least that
@@ -214,6 +262,7 @@ struct CandSrc {
 // in_min[2s], in_min[2s+1] are those smallest keys (NULL: not known; inverted: stored as
 // 0x7fffffff - key, the form in which k_set_min_key's atomic maximum leaves them).
 struct MergedSrc {
+    static constexpr bool kRunGroups = false;
     static constexpr bool kIdentity = true;
     static constexpr bool kRunScan = false;
     // A tombstone's value is +0.0: its key falls into the lowest bin of either digit layout, so
@@ -236,6 +285,15 @@ struct MergedSrc {
     }
     __device__ uint32_t nphys(int, bool) const { return n; }
     __device__ uint32_t group_slots(bool) const { return L; }
+    __device__ bool group_range(int, uint32_t g, uint32_t& first, uint32_t& end) const {
+        const uint64_t f = (uint64_t)g * L;
+        if (f >= n) return false;
+        first = (uint32_t)f;
+        end = (uint32_t)(f + L < n ? f + L : n);
+        return true;
+    }
+    __device__ uint32_t group_of(int, bool, uint32_t p, uint32_t) const { return p / L; }
+    __device__ uint32_t group_of_ord(int, bool, uint32_t lp, uint32_t) const { return lp / L; }
     __device__ Digit digit(int s, bool, const SelState&) const {
         if (!in_min) return Digit{0u, (uint32_t)kCoarseShift};
         uint32_t ma = in_min[2 * s], mb = in_min[2 * s + 1];
@@ -350,11 +408,10 @@ __device__ __forceinline__ void bucket_fast(const Src& src, const SelState& st, 
     const uint32_t g = blockIdx.x;
     if (threadIdx.x == 0) s_nstash = 0u;       // visible after the barrier inside the pick
     constexpr bool dn = false;
-    const uint32_t n = src.nphys(s, dn);
+    constexpr bool kOwnGroup = Src::kIdentity || Src::kRunGroups;     // every slot of the walk is of group g
     const uint32_t L = src.group_slots(dn);
-    const uint64_t first = (uint64_t)g * L;
-    if (first >= n) return;
-    const uint32_t end = (uint32_t)(first + L < n ? first + L : n);
+    uint32_t first, end;
+    if (!src.group_range(s, g, first, end)) return;
     const Digit dg = src.digit(s, dn, st);
     // one round of the walk: the block's next kBlock * kBatch slots, their items and logical positions
     uint32_t idx[kBatch], bits[kBatch], lp[kBatch];
@@ -374,7 +431,7 @@ __device__ __forceinline__ void bucket_fast(const Src& src, const SelState& st, 
 #pragma unroll
         for (int j = 0; j < kBatch; ++j) {
             const uint32_t p = i0 + j * kBlock + threadIdx.x;
-            lp[j] = p < end ? src.logical(s, dn, p, idx[j]) : 0u;
+            lp[j] = (!kOwnGroup && p < end) ? src.logical(s, dn, p, idx[j]) : 0u;
         }
     };
     // the first round is fetched before the pick, so that its latency overlaps with it
@@ -401,14 +458,14 @@ __device__ __forceinline__ void bucket_fast(const Src& src, const SelState& st, 
 #pragma unroll
         for (int j = 0; j < kBatch; ++j) {
             const uint32_t p = i0 + j * kBlock + threadIdx.x;
-            if (p < end) src.store_ordered(s, dn, lp[j], idx[j], bits[j]);
+            if (!kOwnGroup && p < end) src.store_ordered(s, dn, lp[j], idx[j], bits[j]);
             const uint32_t key = bits[j] & kAbs;
             const uint32_t d = dg.bin(key);
             const bool above = ok[j] && d > d1;
             bool inside = ok[j] && d == d1;
             if (Src::kValueOnlyWalk && inside) inside = !src.is_tomb(s, p);
-            const uint32_t lg = Src::kIdentity ? g : lp[j] / L;
-            if (Src::kIdentity) gt += (uint32_t)__popcll(__ballot(above));
+            const uint32_t lg = kOwnGroup ? g : lp[j] / L;
+            if (kOwnGroup) gt += (uint32_t)__popcll(__ballot(above));
             else add_grouped(above, lg, ggt);
             // in-bin entries are parked in LDS (in any order) as long as they fit
             const uint64_t inm = __ballot(inside);
@@ -428,7 +485,7 @@ __device__ __forceinline__ void bucket_fast(const Src& src, const SelState& st, 
     if (threadIdx.x == 0) {
         uint32_t tg = 0, ti = 0;
         for (int v = 0; v < kBlock / kWave; ++v) { tg += s_gt[v]; ti += s_in[v]; }
-        if (Src::kIdentity) ggt[g] = tg;
+        if (kOwnGroup) ggt[g] = tg;
         s_base = ti ? atomicAdd(&st.list_cnt[s], ti) : 0u;     // one reservation per block
     }
     __syncthreads();
@@ -455,7 +512,7 @@ __device__ __forceinline__ void bucket_fast(const Src& src, const SelState& st, 
             const uint64_t inm = __ballot(inside);
             if (inside) {
                 const uint32_t pos = off + rank_in(inm);
-                if (pos < st.list_cap) list[pos] = make_uint2(key, Src::kIdentity ? g : lp[j] / L);
+                if (pos < st.list_cap) list[pos] = make_uint2(key, kOwnGroup ? g : lp[j] / L);
             }
             off += (uint32_t)__popcll(inm);
         }
@@ -662,7 +719,7 @@ __device__ __forceinline__ void for_each_in_bin(const Src& src, int s, bool dn, 
                 const bool ok = p < nphys && src.fetch_phys(s, dn, (uint32_t)p, idx, bits) &&
                                 (bits & kAbs) >= fl;
                 key[j] = (ok && dg.bin(bits & kAbs) == d1) ? (bits & kAbs) : kNoKey;
-                grp[j] = ok ? src.logical(s, dn, (uint32_t)p, idx) / src.group_slots(dn) : 0u;
+                grp[j] = ok ? src.group_of(s, dn, (uint32_t)p, idx) : 0u;
             }
 #pragma unroll
             for (int j = 0; j < kWide; ++j) f(key[j], grp[j]);
@@ -826,10 +883,8 @@ __device__ __forceinline__ void emit_fast(
     const uint32_t t = threadIdx.x;
     constexpr bool dn = false;
     const uint32_t n = src.nphys(s, dn);
-    const uint32_t L = src.group_slots(dn);
-    const uint64_t first = (uint64_t)g * L;
-    if (first >= n) return;
-    const uint32_t end = (uint32_t)(first + L < n ? first + L : n);
+    uint32_t first, end;
+    if (!src.group_range(s, g, first, end)) return;
     const uint32_t wave = t / kWave;
 
     // the block's first round of items is fetched up front: its latency overlaps the finish
@@ -897,10 +952,10 @@ __device__ __forceinline__ void emit_fast(
 #pragma unroll
                     for (int j = 0; j < kBatch; ++j) {
                         const uint64_t p = p0 + (uint64_t)j * kT + t;
-                        uint32_t i2, b2 = 0;
+                        uint32_t i2 = 0, b2 = 0;
                         const bool live = p < n && src.fetch_ord(s, dn, (uint32_t)p, i2, b2);
                         key[j] = (live && dg.bin(b2 & kAbs) == d1) ? (b2 & kAbs) : kNone;
-                        grp[j] = (uint32_t)(p / L);
+                        grp[j] = live ? src.group_of_ord(s, dn, (uint32_t)p, i2) : 0u;
                     }
 #pragma unroll
                     for (int j = 0; j < kBatch; ++j) f(key[j], grp[j]);

@@ -21,7 +21,7 @@ pytestmark = pytest.mark.gpu
 
 # expected path of a row kind: "cand" (served from the candidate list), "over" (more
 # candidates than the list holds), "under" (fewer than k candidates)
-KINDS = ["gauss", "all_equal", "under", "few_levels", "all_zero", "one_spike", "gauss", "under"]
+KINDS = ["gauss", "all_equal", "under", "few_levels", "all_zero", "one_spike", "plateau", "under"]
 
 
 def sampled_positions(plan, m):
@@ -48,6 +48,15 @@ def make_row(kind, m, k, plan, rng, base):
         # one magnitude held by two thirds of the row: more than any list holds, and the
         # k-th key ties with hundreds of thousands of others
         return rng.integers(-1, 2, m).astype(np.float32) * np.float32(0.5), "over"
+    if kind == "plateau":
+        # three tenths of the row share one magnitude far above the rest: where the list holds
+        # them they are candidates, the k-th key ties with all of them (more than the select's
+        # list of in-bin keys holds), and the ties run across the whole row
+        n_plat = (3 * m) // 10
+        g = (rng.standard_normal(m) * 1e-3).astype(np.float32)
+        at = rng.choice(m, n_plat, replace=False)
+        g[at] = np.where(rng.random(n_plat) < 0.5, -1, 1).astype(np.float32) * np.float32(0.5)
+        return g, ("cand" if k <= n_plat <= plan["capacity"] else "over")
     if kind == "under":
         # large magnitudes ONLY where the sampler looks: the sample sees the same number of
         # them as the whole row holds and puts the threshold among them, so the pass keeps
