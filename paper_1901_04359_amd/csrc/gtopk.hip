@@ -199,11 +199,11 @@ static bool small_problem(int64_t m, int64_t k, int64_t P) {
 struct SamplePlan { uint32_t tile_stride, n_tiles, target; };
 
 // Long candidate lists are selected where the streaming pass left them, one group per run
-// (RunSrc): from about 2048 expected candidates per chunk of the row on, and while the runs
+// (RunSrc): from about 256 expected candidates per chunk of the row on, and while the runs
 // of a row are no more than the select's group tables hold.
 static bool run_groups(int64_t m, uint32_t k) {
     const double per_chunk = 1.4 * (double)k * (double)kChunk / (double)m;
-    return per_chunk >= 2048.0 && ceil_div((uint64_t)m + 3, kChunk) <= (uint64_t)kMaxGroups;
+    return per_chunk >= 256.0 && ceil_div((uint64_t)m + 3, kChunk) <= (uint64_t)kMaxGroups;
 }
 // (the few-launch path takes a smaller sample: one block per worker reads it)
 constexpr double kSampleMean = 256.0, kSampleMinTiles = 4096.0;
@@ -434,10 +434,10 @@ int do_local_select(const float* grad, float* residual, int64_t m, int64_t strid
     // the histogram kernel always runs: where the pass has counted its candidates it serves
     // only the workers that came back with fewer than k of them
     if (run_groups(m, k)) {
-        SelGrid gr = local_grid(w, P);
-        if (gr.groups < w.nchunks) gr.groups = gr.walk_blocks = w.nchunks;
         RunSrc rs;
         static_cast<CandSrc&>(rs) = src;
+        SelGrid gr = local_grid(w, P);
+        if (gr.groups < w.nchunks) gr.groups = gr.walk_blocks = w.nchunks;
         run_select<RunSrc, false>(rs, w.sel, gr, k, out_idx, out_val, (int64_t)k, 1.0f, nullptr, st);
     } else {
         run_select<CandSrc, false>(src, w.sel, local_grid(w, P), k, out_idx, out_val, (int64_t)k, 1.0f,

@@ -222,7 +222,7 @@ struct CandSrc {
     }
 };
 
-// The local select of LONG candidate lists (thousands of candidates per chunk of the row):
+// The local select of LONG candidate lists (hundreds of candidates or more per chunk of the row):
 // the groups are the runs themselves - group g of worker s is the run of chunk g, where the
 // streaming pass left it - so nothing is copied into index order: the walk of k_bucket
 // reads a run's values only, the emit reads the run's indices and values in place.  Runs
@@ -410,8 +410,12 @@ __device__ __forceinline__ void bucket_fast(const Src& src, const SelState& st, 
     constexpr bool dn = false;
     constexpr bool kOwnGroup = Src::kIdentity || Src::kRunGroups;     // every slot of the walk is of group g
     const uint32_t L = src.group_slots(dn);
-    uint32_t first, end;
-    if (!src.group_range(s, g, first, end)) return;
+    // (block 0 stays even when its group holds nothing: it records the bin)
+    uint32_t first = 0, end = 0;
+    if (!src.group_range(s, g, first, end)) {
+        if (g != 0) return;
+        first = end = 0;
+    }
     const Digit dg = src.digit(s, dn, st);
     // one round of the walk: the block's next kBlock * kBatch slots, their items and logical positions
     uint32_t idx[kBatch], bits[kBatch], lp[kBatch];
@@ -883,8 +887,12 @@ __device__ __forceinline__ void emit_fast(
     const uint32_t t = threadIdx.x;
     constexpr bool dn = false;
     const uint32_t n = src.nphys(s, dn);
-    uint32_t first, end;
-    if (!src.group_range(s, g, first, end)) return;
+    // (block 0 stays even when its group holds nothing: it records T)
+    uint32_t first = 0, end = 0;
+    if (!src.group_range(s, g, first, end)) {
+        if (g != 0) return;
+        first = end = 0;
+    }
     const uint32_t wave = t / kWave;
 
     // the block's first round of items is fetched up front: its latency overlaps the finish

@@ -21,7 +21,7 @@ pytestmark = pytest.mark.gpu
 
 # expected path of a row kind: "cand" (served from the candidate list), "over" (more
 # candidates than the list holds), "under" (fewer than k candidates)
-KINDS = ["gauss", "all_equal", "under", "few_levels", "all_zero", "one_spike", "plateau", "under"]
+KINDS = ["gauss", "all_equal", "under", "few_levels", "all_zero", "one_spike", "plateau", "gap"]
 
 
 def sampled_positions(plan, m):
@@ -48,6 +48,13 @@ def make_row(kind, m, k, plan, rng, base):
         # one magnitude held by two thirds of the row: more than any list holds, and the
         # k-th key ties with hundreds of thousands of others
         return rng.integers(-1, 2, m).astype(np.float32) * np.float32(0.5), "over"
+    if kind == "gap":
+        # an ordinary row whose first 70,000 elements and a stretch in the middle are zero: the
+        # chunks there leave no candidates at all
+        g = base.copy()
+        g[:70_000] = 0.0
+        g[m // 2: m // 2 + 40_000] = 0.0
+        return g, "cand"
     if kind == "plateau":
         # three tenths of the row share one magnitude far above the rest: where the list holds
         # them they are candidates, the k-th key ties with all of them (more than the select's
