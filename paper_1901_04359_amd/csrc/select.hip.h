@@ -146,6 +146,9 @@ struct CandSrc {
     }
     __device__ uint32_t nphys(int s, bool dn) const { return dn ? m : cand_count[s]; }
     __device__ uint32_t group_slots(bool dn) const { return dn ? Ld : Lc; }
+    __device__ uint32_t ngroups(int s, bool dn) const {
+        return (uint32_t)(((uint64_t)nphys(s, dn) + group_slots(dn) - 1) / group_slots(dn));
+    }
     // slots [first, end) that a block walks for group g of a set that is not a dense row
     // (false: none); and the group of the item at physical slot p
     __device__ bool group_range(int s, uint32_t g, uint32_t& first, uint32_t& end) const {
@@ -234,6 +237,7 @@ struct RunSrc : CandSrc {
     static constexpr bool kRunScan = false;
     __device__ uint32_t fetch_bits(int s, uint32_t p) const { return __float_as_uint(cand_val[(size_t)s * cap + p]); }
     __device__ bool is_tomb(int, uint32_t) const { return false; }
+    __device__ uint32_t ngroups(int s, bool dn) const { return dn ? CandSrc::ngroups(s, dn) : nchunks; }
     __device__ bool group_range(int s, uint32_t g, uint32_t& first, uint32_t& end) const {
         if (g >= nchunks) return false;
         const uint2 run = run_table[(size_t)s * nchunks + g];
@@ -285,6 +289,7 @@ struct MergedSrc {
     }
     __device__ uint32_t nphys(int, bool) const { return n; }
     __device__ uint32_t group_slots(bool) const { return L; }
+    __device__ uint32_t ngroups(int, bool) const { return (uint32_t)(((uint64_t)n + L - 1) / L); }
     __device__ bool group_range(int, uint32_t g, uint32_t& first, uint32_t& end) const {
         const uint64_t f = (uint64_t)g * L;
         if (f >= n) return false;
@@ -750,7 +755,7 @@ __global__ __launch_bounds__(1024) void k_finish(Src src, SelState st) {
     const uint32_t t = threadIdx.x;
     const bool dn = src.dense(s);
     const uint32_t nphys = src.nphys(s, dn);
-    const uint32_t ng = (uint32_t)(((uint64_t)nphys + src.group_slots(dn) - 1) / src.group_slots(dn));   // <= kMaxGroups
+    const uint32_t ng = src.ngroups(s, dn);          // <= kMaxGroups
     const Digit dg = src.digit(s, dn, st);
     const uint32_t fl = src.floor_key(s, dn);
     const uint32_t d1 = st.d1[s];

@@ -106,6 +106,7 @@ CASES = [
     (1_000_003, 125_000, 8, 1),       # rho = 1/8: the pass histograms (very many per block)
     (1_000_003, 15_000, 8, 0),        # rho = 0.015: the select's histogram kernel does
     (700_001, 700, 4, 1),             # a second shape, P = 4
+    (3_000_017, 30_000, 32, 0),       # rho = 0.01, 32 workers: one group per run of the pass
 ]
 
 
