@@ -296,7 +296,9 @@ int gtopk_debug_candidate_counts(const void* ws, int64_t m, int32_t k, int32_t P
  *   plan[6] small_path   1 if gtopk_step takes the few-launch path for small problems at
  *                        these sizes (gtopk_step_carry, gtopk_step_timed and the stand-alone
  *                        calls always take the general kernels)
- *   plan[7] reserved (0)
+ *   plan[7] run_groups   1 if the local selection of the general kernels selects the candidates
+ *                        where the streaming pass left them, one group per run (long runs),
+ *                        0 if it first copies them into index order (short runs)
  *   plan[8] small_tile_stride, plan[9] small_n_tiles, plan[10] small_target: the sampler of
  *                        the few-launch path (same tile_len; all 0 where plan[6] is 0)
  *   plan[11] reserved (0)

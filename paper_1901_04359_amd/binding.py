@@ -348,7 +348,7 @@ def gtopk_probe_stream(a, b, n: int, mode: int, sink=None) -> None:
 
 
 PLAN_FIELDS = ("tile_stride", "n_tiles", "tile_len", "target", "capacity", "pass_histogram",
-               "small_path", "reserved", "small_tile_stride", "small_n_tiles", "small_target",
+               "small_path", "run_groups", "small_tile_stride", "small_n_tiles", "small_target",
                "reserved2")
 
 

@@ -876,7 +876,7 @@ int gtopk_debug_plan(int64_t m, int32_t k, int32_t P, uint32_t* plan) {
     plan[4] = cand_capacity(m, (uint32_t)k);
     plan[5] = pass_histograms(m, (uint32_t)k) ? 1u : 0u;
     plan[6] = small_problem(m, k, P) ? 1u : 0u;
-    plan[7] = 0u;
+    plan[7] = run_groups(m, (uint32_t)k) ? 1u : 0u;
     plan[8] = plan[9] = plan[10] = plan[11] = 0u;
     if (plan[6]) {
         const SamplePlan ss = plan_sample(m, (uint32_t)k, kSmallSampleMean, kSmallSampleMinTiles);

@@ -100,7 +100,8 @@ def check_paths(counts, cap, k, paths, label):
         assert got == path, f"{label}: worker {w} count {c} (k={k}, cap={cap}) took '{got}', wanted '{path}'"
 
 
-# (m, k, P, histogram regime of the streaming pass)
+# (m, k, P, histogram regime of the streaming pass); the first case copies its candidates into
+# index order, the others select them run by run where the pass left them
 CASES = [
     (1_000_003, 1000, 8, 1),          # rho = 0.001: the pass histograms (few candidates per block)
     (1_000_003, 125_000, 8, 1),       # rho = 1/8: the pass histograms (very many per block)
@@ -116,6 +117,7 @@ def test_fallback_step_mixed_workers(m, k, P, pass_hist):
     cfg, plan, g0, paths = build_case(m, k, P, seed=m + k)
     if not plan["small_path"]:
         assert plan["pass_histogram"] == pass_hist, plan
+        assert plan["run_groups"] == (1 if k * 1000 >= 6 * m else 0), plan
     assert plan["n_tiles"] * plan["tile_len"] < m, "the sampler must not see the whole row"
     dev = Device(P, m, k)
     res = np.zeros((P, m), dtype=np.float32)
