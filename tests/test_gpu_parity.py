@@ -715,6 +715,100 @@ def test_step_random_shapes(P, m, k, kind, pad, general):
         res = exp["residual"]
 
 
+def _fill(kind, P, m, rng):
+    """One batch of gradients of a value kind of the seeded sweeps below."""
+    if kind == "gauss":
+        return (rng.standard_normal((P, m)) * 1e-3).astype(np.float32)
+    if kind == "ties":
+        return rng.integers(-3, 4, (P, m)).astype(np.float32) * np.float32(0.5)
+    if kind == "special":
+        return np.stack([W.special_values(m, seed=int(rng.integers(0, 10_000))) for _ in range(P)])
+    if kind == "sparse":
+        return np.where(rng.random((P, m)) < 0.02, rng.standard_normal((P, m)), 0.0).astype(np.float32)
+    g = (rng.standard_normal((P, m)) * 1e-3).astype(np.float32)
+    if kind == "gaps":                 # stretches of zeros: chunks of the row without any candidate
+        for w in range(P):
+            a = int(rng.integers(0, m))
+            g[w, a:min(m, a + int(rng.integers(1, max(2, m // 3))))] = 0.0
+            if rng.random() < 0.5:
+                g[w, :min(m, 40_000)] = 0.0
+    elif kind == "plateau":            # a large share of the row at one magnitude: ties at the k-th key
+        for w in range(P):
+            n = int(m * rng.uniform(0.05, 0.6))
+            at = rng.choice(m, n, replace=False)
+            g[w, at] = np.where(rng.random(n) < 0.5, -1, 1).astype(np.float32) * np.float32(0.25)
+    elif kind == "shared":             # the workers' large entries coincide: merges of overlapping sets
+        base = (rng.standard_normal(m) * 1e-3).astype(np.float32)
+        g = (base[None, :] * rng.uniform(0.5, 1.5, (P, 1)) + rng.standard_normal((P, m)) * 1e-5).astype(np.float32)
+    return g
+
+
+_SWEEP_KINDS = ["gauss", "ties", "special", "sparse", "gaps", "plateau", "shared"]
+
+
+def _small_path_cases(n, seed):
+    """Shapes inside the few-launch path's limits (P <= 64, k <= 512, P * k <= 4096, m < 2^20)."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        P = int(rng.choice([1, 2, 4, 8, 16, 32, 64]))
+        kmax = min(512, 4096 // P)
+        k = int(rng.choice([1, 2, kmax, int(rng.integers(1, kmax + 1)), int(rng.integers(1, kmax + 1))]))
+        m = int(rng.choice([rng.integers(k, k + 50), rng.integers(k, 5000 + k), rng.integers(5000, 200_000),
+                            rng.integers(200_000, 1_048_573)]))
+        cases.append((P, max(m, k), k, str(rng.choice(_SWEEP_KINDS)), int(rng.choice([0, 0, 1, 2, 3, 7]))))
+    return cases
+
+
+def _long_run_cases(n, seed):
+    """Densities at which the candidates are selected run by run where the pass left them."""
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        P = int(rng.choice([1, 2, 4, 8]))
+        m = int(rng.choice([rng.integers(40_000, 200_000), rng.integers(200_000, 1_500_000)]))
+        rho = float(rng.choice([0.006, 0.01, 0.03, 0.1, 0.25, 0.5, 0.9]))
+        cases.append((P, m, min(m, max(513, int(m * rho))), str(rng.choice(_SWEEP_KINDS)), int(rng.choice([0, 0, 1, 3]))))
+    return cases
+
+
+def _check_two_iterations(P, m, k, kind, pad, label):
+    rng = np.random.default_rng(P * 1_000_003 + m * 31 + k)
+    dev = Device(P, m, k, stride=m + pad if pad else None)
+    res = np.zeros((P, m), dtype=np.float32)
+    dev.set_res(res)
+    for it in range(2):
+        g = _fill(kind, P, m, rng)
+        dev.set_grad(g)
+        say(f"{label} P={P} m={m} k={k} kind={kind} pad={pad} it={it}")
+        gi, gv = dev.step()
+        exp = orc.step(res, g, k)
+        assert np.array_equal(idx_np(dev.loc_idx), exp["loc_idx"]), first_diff(idx_np(dev.loc_idx), exp["loc_idx"])
+        assert bits_equal(val_np(dev.loc_val), exp["loc_val"])
+        assert np.array_equal(gi, exp["g_idx"]), first_diff(gi, exp["g_idx"])
+        assert bits_equal(gv, exp["g_val"])
+        out = dev.residual()
+        assert bits_equal(out, exp["residual"]), first_diff(out, exp["residual"])
+        res = exp["residual"]
+
+
+@pytest.mark.parametrize("P,m,k,kind,pad", _small_path_cases(60, 20261127))
+def test_step_random_shapes_few_launch_path(P, m, k, kind, pad):
+    """Seeded shapes and value kinds inside the limits of gtopk_step's few-launch path."""
+    from paper_1901_04359_amd import binding as B
+    assert B.gtopk_debug_plan(m, k, P)["small_path"] == 1
+    _check_two_iterations(P, m, k, kind, pad, "few-launch sweep")
+
+
+@pytest.mark.parametrize("P,m,k,kind,pad", _long_run_cases(30, 20261128))
+def test_step_random_shapes_long_runs(P, m, k, kind, pad):
+    """Seeded shapes and value kinds at the densities where the candidates are selected in place."""
+    from paper_1901_04359_amd import binding as B
+    plan = B.gtopk_debug_plan(m, k, P)
+    assert plan["small_path"] == 0 and plan["run_groups"] == 1
+    _check_two_iterations(P, m, k, kind, pad, "long-run sweep")
+
+
 def _random_aggregation_cases(n, seed):
     rng = np.random.default_rng(seed)
     cases = []
