@@ -282,6 +282,16 @@ int gtopk_debug_candidate_counts(const void* ws, int64_t m, int32_t k, int32_t P
                                  uint32_t* host_counts, uint32_t* host_capacity);
 
 /*
+ * Instrumentation for tests (not part of the method): after a gtopk_merge on workspace `ws`
+ * with these sizes has COMPLETED, copy to the host how many slots of each pair's union
+ * reached the pair's speculative threshold (host_kept[batch]).  A pair with fewer than k
+ * was merged and selected once more from its complete union.  GTOPK_EINVAL where merges
+ * of this k do not go through a speculative threshold (gtopk_debug_plan, plan[11]).
+ * Synchronous (blocking device-to-host copy).
+ */
+int gtopk_debug_merge_kept(const void* ws, int32_t k, int32_t batch, uint32_t* host_kept);
+
+/*
  * Instrumentation for tests (not part of the method; host only, touches no GPU): how the
  * local selection of these sizes is laid out, so that a test can build rows that defeat
  * the speculative threshold and can tell which regime it exercises.
@@ -301,9 +311,14 @@ int gtopk_debug_candidate_counts(const void* ws, int64_t m, int32_t k, int32_t P
  *                        0 if it first copies them into index order (short runs)
  *   plan[8] small_tile_stride, plan[9] small_n_tiles, plan[10] small_target: the sampler of
  *                        the few-launch path (same tile_len; all 0 where plan[6] is 0)
- *   plan[11] reserved (0)
+ *   plan[11] merge_filtered  1 if a merge of two k-sets of this k goes through a speculative
+ *                        threshold (a sample of the union; only slots that reach it are kept)
+ *   plan[12] merge_tile_stride, plan[13] merge_n_tiles, plan[14] merge_target: that sample -
+ *                        tile t covers positions [t*merge_tile_stride, +plan[2]) of both
+ *                        operands (all 0 where plan[11] is 0)
+ *   plan[15] reserved (0)
  */
-#define GTOPK_PLAN_WORDS 12
+#define GTOPK_PLAN_WORDS 16
 int gtopk_debug_plan(int64_t m, int32_t k, int32_t P, uint32_t* plan);
 
 #ifdef __cplusplus

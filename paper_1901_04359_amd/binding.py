@@ -23,6 +23,7 @@ EXPORTS = (
     "gtopk_apply_update", "gtopk_dense_mask",
     "gtopk_allreduce_workspace_bytes", "gtopk_topk_allreduce", "gtopk_dense_topk",
     "gtopk_step_timed", "gtopk_probe_stream", "gtopk_debug_candidate_counts", "gtopk_debug_plan",
+    "gtopk_debug_merge_kept",
 )
 
 GTOPK_OK, GTOPK_EINVAL, GTOPK_EWORKSPACE, GTOPK_EALIGN, GTOPK_EHIP = 0, -1, -2, -3, -4
@@ -87,6 +88,8 @@ def load() -> ctypes.CDLL:
     lib.gtopk_probe_stream.argtypes = [vp, vp, i64, i32, vp, vp]
     lib.gtopk_debug_plan.restype = c.c_int
     lib.gtopk_debug_plan.argtypes = [i64, i32, i32, c.POINTER(c.c_uint32)]
+    lib.gtopk_debug_merge_kept.restype = c.c_int
+    lib.gtopk_debug_merge_kept.argtypes = [vp, i32, i32, c.POINTER(c.c_uint32)]
     lib.gtopk_debug_candidate_counts.restype = c.c_int
     lib.gtopk_debug_candidate_counts.argtypes = [vp, i64, i32, i32, c.POINTER(c.c_uint32),
                                                  c.POINTER(c.c_uint32)]
@@ -349,7 +352,7 @@ def gtopk_probe_stream(a, b, n: int, mode: int, sink=None) -> None:
 
 PLAN_FIELDS = ("tile_stride", "n_tiles", "tile_len", "target", "capacity", "pass_histogram",
                "small_path", "run_groups", "small_tile_stride", "small_n_tiles", "small_target",
-               "reserved2")
+               "merge_filtered", "merge_tile_stride", "merge_n_tiles", "merge_target", "reserved")
 
 
 def gtopk_debug_plan(m: int, k: int, P: int) -> dict:
@@ -357,6 +360,16 @@ def gtopk_debug_plan(m: int, k: int, P: int) -> dict:
     plan = (ctypes.c_uint32 * len(PLAN_FIELDS))()
     _check(load().gtopk_debug_plan(m, k, P, plan), "gtopk_debug_plan")
     return dict(zip(PLAN_FIELDS, (int(x) for x in plan)))
+
+
+def gtopk_debug_merge_kept(ws, k: int, batch: int):
+    """Slots of each pair's union that reached its speculative threshold in the last completed
+    gtopk_merge on `ws` (large k only; see gtopk.h)."""
+    torch = _torch()
+    torch.cuda.synchronize()
+    kept = (ctypes.c_uint32 * batch)()
+    _check(load().gtopk_debug_merge_kept(_ptr(ws, torch.uint8, "ws"), k, batch, kept), "gtopk_debug_merge_kept")
+    return list(kept)
 
 
 def gtopk_debug_candidate_counts(ws, m: int, k: int, P: int):

@@ -132,9 +132,27 @@ struct MergeWs {
     uint32_t* tmin[2]; // [pairs] smallest key of each output set, alternating between rounds
     uint32_t* inv_min; // [2*pairs] 0x7fffffff - smallest key of each caller-supplied operand
     uint32_t* cuts;    // [pairs][tiles + 1] cut points of k_union_path's blocks (large sets)
+    // the largest sets are merged through a speculative threshold (FiltSrc); all NULL otherwise
+    uint32_t* f_samp_hist;  // [pairs][16384]  } cleared together at the start of every round
+    uint32_t* f_set_cnt;    // [pairs]         }
+    size_t f_clear_words;
+    uint32_t* f_tspec;      // [pairs]
+    uint32_t* f_tile_cnt;   // [pairs][tiles]
+    SelState sel_rep;       // select state of the pairs that fall back to their complete union
+    size_t rep_clear_words;
     uint32_t L;
     size_t bytes;
 };
+
+// Sets of more than 2^22 entries whose 8192-slot union tiles fit the select's group tables
+// are merged through a speculative threshold.  Measured at C4 size: at k = 6.4 M the rounds of
+// the tree take 3.4 instead of 3.6 ms; at k = 1.85 M the sample and the stand-by launches for a
+// threshold that misses (about 65 us per round) cost more than the smaller select saves.
+constexpr uint32_t kMergeFilterMinK = 1u << 22;
+inline bool merge_filtered(uint32_t k) {
+    return k > kMergeFilterMinK &&
+           ceil_div(2ull * k, (uint64_t)kUnionHistBlock * kUnionPathEpt) <= (uint32_t)kMaxGroups;
+}
 
 MergeWs carve_merge(Carver& c, uint32_t k, size_t pairs) {
     MergeWs w;
@@ -150,6 +168,19 @@ MergeWs carve_merge(Carver& c, uint32_t k, size_t pairs) {
     w.cuts = c.take<uint32_t>(k > kUnionCutsMinK
                                   ? pairs * ((size_t)ceil_div(2ull * k, kUnionHistBlock * kUnionPathEpt) + 1)
                                   : 0);
+    w.f_samp_hist = w.f_set_cnt = w.f_tspec = w.f_tile_cnt = nullptr;
+    w.f_clear_words = w.rep_clear_words = 0;
+    w.sel_rep = w.sel;
+    if (merge_filtered(k)) {
+        const size_t ntiles = ceil_div(2ull * k, kUnionHistBlock * kUnionPathEpt);
+        w.f_samp_hist = c.take<uint32_t>(pairs * kSampleBins);
+        w.f_set_cnt = c.take<uint32_t>(pairs);
+        uint32_t* end = c.take<uint32_t>(1);
+        w.f_clear_words = w.f_samp_hist ? (size_t)(end - w.f_samp_hist) : 0;
+        w.f_tspec = c.take<uint32_t>(pairs);
+        w.f_tile_cnt = c.take<uint32_t>(pairs * ntiles);
+        w.sel_rep = carve_select_alt(c, w.sel, pairs, &w.rep_clear_words);
+    }
     w.bytes = c.off;
     return w;
 }
@@ -450,6 +481,28 @@ int do_local_select(const float* grad, float* residual, int64_t m, int64_t strid
     return launch_status();
 }
 
+// Sample of a union for its speculative threshold: 256 tiles of 64 positions of either
+// operand.  Every slot of the union is sampled with probability f = sampled / k, so the
+// k-th key of the union has expected sample rank `sampled`; the target adds 5.5 standard
+// deviations and 3 % for the tiles' placement error, as for a row (plan_sample).
+struct MergeSamplePlan { uint32_t tile_stride, n_tiles, target, blocks; };
+inline MergeSamplePlan plan_merge_sample(uint32_t k) {
+    MergeSamplePlan p;
+    const uint32_t want_tiles = 256;
+    p.tile_stride = k / want_tiles;                          // k > 2^19: at least 2048
+    if (p.tile_stride < (uint32_t)kSampleTile) p.tile_stride = kSampleTile;
+    p.n_tiles = ceil_div(k, p.tile_stride);
+    const uint64_t last = (uint64_t)k - (uint64_t)(p.n_tiles - 1) * p.tile_stride;
+    const double sampled = (double)(p.n_tiles - 1) * kSampleTile + (double)(last < (uint64_t)kSampleTile ? last : kSampleTile);
+    double t = 1.03 * sampled + 5.5 * __builtin_sqrt(sampled) + 2.0;
+    if (t > 2.0 * sampled) t = 2.0 * sampled;
+    p.target = (uint32_t)t;
+    p.blocks = ceil_div(p.n_tiles, kSampleBlock / kSampleTile);
+    if (p.blocks > 16) p.blocks = 16;
+    if (p.blocks < 1) p.blocks = 1;
+    return p;
+}
+
 inline uint32_t min_key_blocks(uint32_t k) {
     const uint32_t b = ceil_div(k, 8192);
     return b < 1 ? 1 : (b > 64 ? 64 : b);
@@ -489,13 +542,49 @@ void do_merge_batch(const uint32_t* a_idx, const float* a_val, const uint32_t* b
                            dim3(ceil_div(2 * k, kUnionHistBlock * kUnionPathEpt), batch),
                            dim3(kUnionHistBlock), 0, st, a_idx, a_val, b_idx, b_val, k, in_stride, w.m_idx,
                            w.m_val, w.m_stride, (const uint32_t*)nullptr, zp, zw, src, ss);
-    else {
+    else if (!w.f_samp_hist) {
         const uint32_t tile = kUnionHistBlock * kUnionPathEpt, ntiles = ceil_div(2 * k, tile);
         hipLaunchKernelGGL(k_union_cuts, dim3(ceil_div(ntiles + 1, kBlock), batch), dim3(kBlock), 0, st,
                            a_idx, b_idx, k, in_stride, tile, ntiles, w.cuts);
         hipLaunchKernelGGL((k_union_path<kUnionPathEpt, true, kUnionHistBlock, true>), dim3(ntiles, batch),
                            dim3(kUnionHistBlock), 0, st, a_idx, a_val, b_idx, b_val, k, in_stride, w.m_idx,
                            w.m_val, w.m_stride, (const uint32_t*)w.cuts, zp, zw, src, ss);
+    } else {
+        // The largest sets.  A sample of the union gives a threshold that a little more than k
+        // of its slots are expected to reach; the union keeps only those, tile by tile, and the
+        // select works on what is left (FiltSrc).  A pair whose union kept fewer than k slots is
+        // then merged and selected once more, from its complete union; for every other pair
+        // those launches return at once.
+        const uint32_t tile = kUnionHistBlock * kUnionPathEpt, ntiles = ceil_div(2 * k, tile);
+        zero_async(st, zero_job(w.f_samp_hist, w.f_clear_words, w.sel_rep.hist, w.rep_clear_words));
+        const MergeSamplePlan mp = plan_merge_sample(k);
+        hipLaunchKernelGGL(k_merge_sample, dim3(mp.blocks, batch), dim3(kSampleBlock), 0, st, a_idx, a_val,
+                           b_idx, b_val, k, in_stride, mp.tile_stride, mp.n_tiles, w.f_samp_hist);
+        hipLaunchKernelGGL(k_sample_pick, dim3(batch), dim3(kSampleBlock), 0, st,
+                           (const uint32_t*)w.f_samp_hist, mp.target, w.f_tspec, (const uint4*)nullptr);
+        hipLaunchKernelGGL(k_union_cuts, dim3(ceil_div(ntiles + 1, kBlock), batch), dim3(kBlock), 0, st,
+                           a_idx, b_idx, k, in_stride, tile, ntiles, w.cuts);
+        hipLaunchKernelGGL((k_union_path<kUnionPathEpt, true, kUnionHistBlock, true, true>), dim3(ntiles, batch),
+                           dim3(kUnionHistBlock), 0, st, a_idx, a_val, b_idx, b_val, k, in_stride, w.m_idx,
+                           w.m_val, w.m_stride, (const uint32_t*)w.cuts, zp, zw, src, ss,
+                           UnionFilter{w.f_tspec, w.f_tile_cnt, w.f_set_cnt}, (const uint32_t*)nullptr);
+        static_assert(kUnionHistBlock * kUnionPathEpt == 8192, "FiltSrc's tiles are the union's: 2^13 slots");
+        const FiltSrc fs{w.m_idx, w.m_val, k, w.m_stride, 13u, ntiles, w.f_tile_cnt, w.f_set_cnt, w.f_tspec};
+        run_select<FiltSrc, DIVIDE>(fs, ss, SelGrid{batch, ntiles, ntiles, 2ull * k, true}, k, out_idx, out_val,
+                                    out_stride, divisor, gbits, st, /*with_hist=*/false);
+        // the pairs that came out short
+        MergedSrc rsrc = src;
+        rsrc.gate_cnt = w.f_set_cnt;
+        rsrc.gate_k = k;
+        SelState rs = w.sel_rep;
+        rs.T_out = out_min;
+        hipLaunchKernelGGL((k_union_path<kUnionPathEpt, true, kUnionHistBlock, true>), dim3(ntiles, batch),
+                           dim3(kUnionHistBlock), 0, st, a_idx, a_val, b_idx, b_val, k, in_stride, w.m_idx,
+                           w.m_val, w.m_stride, (const uint32_t*)w.cuts, (uint32_t*)nullptr, 0u, rsrc, rs,
+                           UnionFilter{nullptr, nullptr, nullptr}, (const uint32_t*)w.f_set_cnt);
+        run_select<MergedSrc, DIVIDE>(rsrc, rs, SelGrid{batch, groups, groups, 2ull * k, true}, k, out_idx,
+                                      out_val, out_stride, divisor, gbits, st, /*with_hist=*/false);
+        return;
     }
     run_select<MergedSrc, DIVIDE>(src, ss, SelGrid{batch, groups, groups, 2ull * k, 2ull * k > kInlineFinishMax},
                                   k, out_idx, out_val, out_stride, divisor, gbits, st,
@@ -850,6 +939,17 @@ int gtopk_debug_candidate_counts(const void* ws, int64_t m, int32_t k, int32_t P
     return GTOPK_OK;
 }
 
+int gtopk_debug_merge_kept(const void* ws, int32_t k, int32_t batch, uint32_t* host_kept) {
+    if (!ws || !host_kept || k < 1 || k > kMaxMergeK || batch < 1 || batch > 32767) return GTOPK_EINVAL;
+    Carver c{reinterpret_cast<char*>(const_cast<void*>(ws))};
+    const MergeWs w = carve_merge(c, (uint32_t)k, (size_t)batch);
+    if (!w.f_set_cnt) return GTOPK_EINVAL;               // merges of this k are not filtered
+    if (hipMemcpy(host_kept, w.f_set_cnt, sizeof(uint32_t) * (size_t)batch, hipMemcpyDeviceToHost) !=
+        hipSuccess)
+        return GTOPK_EHIP;
+    return GTOPK_OK;
+}
+
 int gtopk_probe_stream(const float* a, float* b, int64_t n, int32_t mode, float* sink,
                        void* stream) {
     if (!a || !b || n < 1 || n % kChunk != 0 || n / kChunk > 0x7fffffff) return GTOPK_EINVAL;
@@ -877,7 +977,14 @@ int gtopk_debug_plan(int64_t m, int32_t k, int32_t P, uint32_t* plan) {
     plan[5] = pass_histograms(m, (uint32_t)k) ? 1u : 0u;
     plan[6] = small_problem(m, k, P) ? 1u : 0u;
     plan[7] = run_groups(m, (uint32_t)k) ? 1u : 0u;
-    plan[8] = plan[9] = plan[10] = plan[11] = 0u;
+    for (int i = 8; i < GTOPK_PLAN_WORDS; ++i) plan[i] = 0u;
+    if (P > 1 && merge_filtered((uint32_t)k)) {
+        const MergeSamplePlan mp = plan_merge_sample((uint32_t)k);
+        plan[11] = 1u;
+        plan[12] = mp.tile_stride;
+        plan[13] = mp.n_tiles;
+        plan[14] = mp.target;
+    }
     if (plan[6]) {
         const SamplePlan ss = plan_sample(m, (uint32_t)k, kSmallSampleMean, kSmallSampleMinTiles);
         plan[8] = ss.tile_stride;

@@ -242,14 +242,29 @@ __global__ __launch_bounds__(kBlock) void k_union_cuts(
     cuts[(size_t)s * (ntiles + 1) + c] = lo;
 }
 
-template <int EPT, bool CUTS, int BLOCK, bool HIST>
+// FILTER (with HIST): of its tile the block keeps only the slots whose key reaches
+// filt.tspec[s] (no tombstones either), packed at the start of the tile in index order;
+// filt.tile_cnt[s][tile] = their number, which is also added to filt.set_cnt[s]; the first
+// digits counted are those of the kept slots, in bins relative to the threshold (FiltSrc).
+// gate_cnt != NULL: pair s is merged only if gate_cnt[s] < k (the complete union of a pair
+// whose filtered union came out short).
+struct UnionFilter {
+    const uint32_t* tspec;
+    uint32_t* tile_cnt;
+    uint32_t* set_cnt;
+};
+
+template <int EPT, bool CUTS, int BLOCK, bool HIST, bool FILTER = false>
 __global__ __launch_bounds__(BLOCK) void k_union_path(
         const uint32_t* __restrict__ a_idx, const float* __restrict__ a_val,
         const uint32_t* __restrict__ b_idx, const float* __restrict__ b_val, uint32_t k,
         int64_t in_stride, uint32_t* __restrict__ m_idx, float* __restrict__ m_val,
         uint32_t m_stride, const uint32_t* __restrict__ cuts, uint32_t* __restrict__ zero_ptr,
-        uint32_t zero_words, MergedSrc hsrc, SelState hst) {
+        uint32_t zero_words, MergedSrc hsrc, SelState hst, UnionFilter filt = UnionFilter{nullptr, nullptr, nullptr},
+        const uint32_t* __restrict__ gate_cnt = nullptr) {
     static_assert(EPT % 4 == 0, "whole 16-byte vectors per thread");
+    static_assert(!FILTER || HIST, "the filtered union counts its own first digits");
+    if (gate_cnt && gate_cnt[blockIdx.y] >= k) return;       // block-uniform
     constexpr uint32_t kTile = BLOCK * EPT;
     constexpr uint32_t kStage = kTile + 3;         // A: previous + entries + sentinel; B: entries + next
     // EPT spare slots: with operands that are not sorted (unspecified results) a thread's
@@ -258,6 +273,7 @@ __global__ __launch_bounds__(BLOCK) void k_union_path(
     __shared__ float s_v[kStage + EPT];
     __shared__ uint32_t s_split[2];
     __shared__ uint32_t s_hist[HIST ? kHistBins : 1];
+    __shared__ uint32_t s_scan[FILTER ? BLOCK / kWave : 1];
     const int s = blockIdx.y;
     if (HIST)
         for (int b = threadIdx.x; b < kHistBins; b += BLOCK) s_hist[b] = 0u;   // barriers follow
@@ -327,6 +343,10 @@ __global__ __launch_bounds__(BLOCK) void k_union_path(
     const float* sav = s_v + 1;
     const float* sbv = s_v + na + 2;
     const uint32_t d = threadIdx.x * EPT;          // first slot of this thread, relative to p0
+    uint32_t oi[EPT];
+    float ov[EPT];
+#pragma unroll
+    for (int j = 0; j < EPT; ++j) { oi[j] = kTomb; ov[j] = 0.0f; }
     if (d < nout) {                                // nout is a multiple of EPT except in the last block
         // A entries among the tile's first d slots
         uint32_t x = d > nb ? d - nb : 0u;
@@ -338,8 +358,6 @@ __global__ __launch_bounds__(BLOCK) void k_union_path(
             }
         }
         uint32_t y = d - x;
-        uint32_t oi[EPT];
-        float ov[EPT];
         uint32_t a = sa[x], b = sb[y];
         uint32_t aprev = sa[(int)x - 1];
 #pragma unroll
@@ -362,19 +380,57 @@ __global__ __launch_bounds__(BLOCK) void k_union_path(
                 b = sb[y];
             }
         }
-        uint32_t* mi = m_idx + (size_t)s * m_stride + p0 + d;
-        float* mv = m_val + (size_t)s * m_stride + p0 + d;
+    }
+    if (!FILTER) {
+        if (d < nout) {
+            uint32_t* mi = m_idx + (size_t)s * m_stride + p0 + d;
+            float* mv = m_val + (size_t)s * m_stride + p0 + d;
 #pragma unroll
-        for (int j = 0; j < EPT; j += 4) {
-            *reinterpret_cast<uint4*>(mi + j) = make_uint4(oi[j], oi[j + 1], oi[j + 2], oi[j + 3]);
-            *reinterpret_cast<float4*>(mv + j) = make_float4(ov[j], ov[j + 1], ov[j + 2], ov[j + 3]);
+            for (int j = 0; j < EPT; j += 4) {
+                *reinterpret_cast<uint4*>(mi + j) = make_uint4(oi[j], oi[j + 1], oi[j + 2], oi[j + 3]);
+                *reinterpret_cast<float4*>(mv + j) = make_float4(ov[j], ov[j + 1], ov[j + 2], ov[j + 3]);
+            }
+            if (HIST) {
+                // first digits of the keys just produced: what k_hist would read back
+                const Digit dg = hsrc.digit(s, false, hst);
+#pragma unroll
+                for (int j = 0; j < EPT; ++j)
+                    if (oi[j] != kTomb) atomicAdd(&s_hist[dg.bin(__float_as_uint(ov[j]) & kAbs)], 1u);
+            }
         }
-        if (HIST) {
-            // first digits of the keys just produced: what k_hist would read back
-            const Digit dg = hsrc.digit(s, false, hst);
+    } else {
+        // keep what reaches the threshold, packed at the start of the tile in slot order
+        const uint32_t ts = filt.tspec[s];
+        uint32_t keep = 0;
 #pragma unroll
-            for (int j = 0; j < EPT; ++j)
-                if (oi[j] != kTomb) atomicAdd(&s_hist[dg.bin(__float_as_uint(ov[j]) & kAbs)], 1u);
+        for (int j = 0; j < EPT; ++j)
+            if (oi[j] != kTomb && (__float_as_uint(ov[j]) & kAbs) >= ts) keep |= 1u << j;
+        const uint32_t cnt = (uint32_t)__popc(keep);
+        uint32_t total;
+        const uint32_t incl = block_incl_scan(cnt, s_scan, total);      // total <= nout
+        // (the scan's barriers lie behind every thread's merge: the staged operands are dead,
+        // and their LDS collects the kept slots, which then leave in whole coalesced rows)
+        uint32_t pos = incl - cnt;
+        const Digit dg{ts, (uint32_t)kFineShift};
+#pragma unroll
+        for (int j = 0; j < EPT; ++j) {
+            if ((keep >> j) & 1u) {
+                s_i[pos] = oi[j];
+                s_v[pos] = ov[j];
+                ++pos;
+                atomicAdd(&s_hist[dg.bin(__float_as_uint(ov[j]) & kAbs)], 1u);
+            }
+        }
+        __syncthreads();
+        uint32_t* mi = m_idx + (size_t)s * m_stride + p0;
+        float* mv = m_val + (size_t)s * m_stride + p0;
+        for (uint32_t i = threadIdx.x; i < total; i += BLOCK) {
+            mi[i] = s_i[i];
+            mv[i] = s_v[i];
+        }
+        if (threadIdx.x == 0) {
+            filt.tile_cnt[(size_t)s * gridDim.x + blockIdx.x] = total;
+            if (total) atomicAdd(&filt.set_cnt[s], total);
         }
     }
     if (HIST) {
@@ -384,6 +440,49 @@ __global__ __launch_bounds__(BLOCK) void k_union_path(
             const uint32_t c = s_hist[b];
             if (c) atomicAdd(&out[b], c);
         }
+    }
+}
+
+// Sample of the union of pair s for its speculative threshold: tile t covers positions
+// [t * tile_stride, + 64) of BOTH operands (clipped to k), one wave per tile.  A sampled
+// entry of A stands for its slot of the union: its value plus B's value at the same index,
+// if B has one (binary search).  A sampled entry of B stands for its slot unless A holds
+// the index too - that slot is A's.  So every slot of the union is sampled with the same
+// probability, and the histogram of the sampled keys (16384 bins, added to samp_hist[s]
+// with one atomic per non-empty bin and block) is read by k_sample_pick as for a row.
+__global__ __launch_bounds__(kSampleBlock) void k_merge_sample(
+        const uint32_t* __restrict__ a_idx, const float* __restrict__ a_val,
+        const uint32_t* __restrict__ b_idx, const float* __restrict__ b_val, uint32_t k,
+        int64_t in_stride, uint32_t tile_stride, uint32_t n_tiles, uint32_t* __restrict__ samp_hist) {
+    __shared__ uint32_t h[kSampleBins];
+    const int s = blockIdx.y;
+    for (int b = threadIdx.x; b < kSampleBins; b += kSampleBlock) h[b] = 0u;
+    __syncthreads();
+    const uint32_t* ai = a_idx + (int64_t)s * in_stride;
+    const float* av = a_val + (int64_t)s * in_stride;
+    const uint32_t* bi = b_idx + (int64_t)s * in_stride;
+    const float* bv = b_val + (int64_t)s * in_stride;
+    const uint32_t sub = threadIdx.x / kSampleTile, el = threadIdx.x % kSampleTile;
+    const uint32_t tiles_per_round = (kSampleBlock / kSampleTile) * gridDim.x;
+    for (uint64_t t = (uint64_t)blockIdx.x * (kSampleBlock / kSampleTile) + sub; t < n_tiles; t += tiles_per_round) {
+        const uint64_t q = t * tile_stride + el;
+        if (q >= k) continue;
+        const uint32_t ia = ai[q], ib = bi[q];
+        const float va = av[q], vb = bv[q];
+        uint32_t lo = 0, hi = k;                      // first B entry with index >= ia
+        while (lo < hi) { const uint32_t mid = (lo + hi) >> 1; if (bi[mid] < ia) lo = mid + 1; else hi = mid; }
+        float v = va;
+        if (lo < k && bi[lo] == ia) v = v + bv[lo];
+        atomicAdd(&h[(__float_as_uint(v) & kAbs) >> kSampleShift], 1u);
+        lo = 0; hi = k;                               // first A entry with index >= ib
+        while (lo < hi) { const uint32_t mid = (lo + hi) >> 1; if (ai[mid] < ib) lo = mid + 1; else hi = mid; }
+        if (!(lo < k && ai[lo] == ib)) atomicAdd(&h[(__float_as_uint(vb) & kAbs) >> kSampleShift], 1u);
+    }
+    __syncthreads();
+    uint32_t* out = samp_hist + (size_t)s * kSampleBins;
+    for (int b = threadIdx.x; b < kSampleBins; b += kSampleBlock) {
+        const uint32_t c = h[b];
+        if (c) atomicAdd(&out[b], c);
     }
 }
 

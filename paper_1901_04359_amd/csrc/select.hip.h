@@ -62,6 +62,7 @@ struct SelState {
 // counts (run_off[w][chunk] = first logical position of the run), and k_bucket's walk
 // copies the candidates into index order on the side.
 struct CandSrc {
+    __device__ bool skip(int) const { return false; }     // every set of the launch is selected
     static constexpr bool kRunGroups = false;
     static constexpr bool kValueOnlyWalk = false;
     __device__ uint32_t fetch_bits(int, uint32_t) const { return 0u; }
@@ -162,6 +163,10 @@ struct CandSrc {
     __device__ uint32_t group_of(int s, bool dn, uint32_t p, uint32_t idx) const {
         return logical(s, dn, p, idx) / group_slots(dn);
     }
+    // fetch_ord() for a position inside a range that group_range() has handed out
+    __device__ bool fetch_emit(int s, bool dn, uint32_t lp, uint32_t& idx, uint32_t& bits) const {
+        return fetch_ord(s, dn, lp, idx, bits);
+    }
     // ... and of the item that fetch_ord() reads at position lp
     __device__ uint32_t group_of_ord(int, bool dn, uint32_t lp, uint32_t) const { return lp / group_slots(dn); }
     // Lower bound of the k-th key: the speculative threshold while at least k entries
@@ -256,6 +261,9 @@ struct RunSrc : CandSrc {
         return fetch_phys(s, dn, p, idx, bits);
     }
     __device__ uint32_t group_of_ord(int s, bool dn, uint32_t p, uint32_t idx) const { return group_of(s, dn, p, idx); }
+    __device__ bool fetch_emit(int s, bool dn, uint32_t p, uint32_t& idx, uint32_t& bits) const {
+        return fetch_phys(s, dn, p, idx, bits);
+    }
 };
 
 // Merge: n = 2k slots per pair (rows `stride` slots apart), index-ascending, a slot with
@@ -280,6 +288,11 @@ struct MergedSrc {
     uint32_t n, stride, L;       // L slots per group
     const uint32_t* in_min;
     bool inverted;
+    // optional gate: set s is selected only if gate_cnt[s] < gate_k (the sets whose filtered
+    // union came out short, see FiltSrc); NULL: every set
+    const uint32_t* gate_cnt;
+    uint32_t gate_k;
+    __device__ bool skip(int s) const { return gate_cnt && gate_cnt[s] >= gate_k; }
     __device__ bool dense(int) const { return false; }
     __device__ void carry(int, uint32_t) const {}
     __device__ uint32_t floor_key(int, bool) const { return 0u; }
@@ -299,6 +312,9 @@ struct MergedSrc {
     }
     __device__ uint32_t group_of(int, bool, uint32_t p, uint32_t) const { return p / L; }
     __device__ uint32_t group_of_ord(int, bool, uint32_t lp, uint32_t) const { return lp / L; }
+    __device__ bool fetch_emit(int s, bool dn, uint32_t lp, uint32_t& i, uint32_t& bits) const {
+        return fetch_phys(s, dn, lp, i, bits);
+    }
     __device__ Digit digit(int s, bool, const SelState&) const {
         if (!in_min) return Digit{0u, (uint32_t)kCoarseShift};
         uint32_t ma = in_min[2 * s], mb = in_min[2 * s + 1];
@@ -319,6 +335,77 @@ struct MergedSrc {
     __device__ bool fetch_ord(int s, bool dn, uint32_t lp, uint32_t& i, uint32_t& bits) const {
         return fetch_phys(s, dn, lp, i, bits);
     }
+    __device__ void scan_runs(int, uint32_t*) const {}
+};
+
+// Merge of LARGE sets through a speculative threshold: the union kernel has kept, of every
+// tile of 8192 slots of the union, only the slots whose key reaches tspec[s] - a bucket
+// edge taken from a sample of the union such that a little more than k slots are
+// expected to reach it - packed at the start of the tile, in index order.  Group g of
+// pair s is what is left of tile g: tile_cnt[s][g] slots from slot g * tile on.  A pair
+// whose union kept fewer than k slots (set_cnt[s] < k: the sample misled) is skipped here
+// and selected from its complete union instead (MergedSrc with the gate).
+struct FiltSrc {
+    static constexpr bool kRunGroups = true;
+    static constexpr bool kIdentity = false;
+    static constexpr bool kRunScan = false;
+    static constexpr bool kValueOnlyWalk = true;
+    const uint32_t* idx;
+    const float* val;
+    uint32_t k, stride, tile_log2, ntiles;      // tiles of 2^tile_log2 slots
+    const uint32_t* tile_cnt;     // [pairs][ntiles]
+    const uint32_t* set_cnt;      // [pairs]
+    const uint32_t* tspec;        // [pairs]
+    __device__ bool skip(int s) const { return set_cnt[s] < k; }
+    __device__ bool dense(int) const { return false; }
+    __device__ void carry(int, uint32_t) const {}
+    __device__ uint32_t floor_key(int, bool) const { return 0u; }
+    __device__ bool wants_hist(int, bool) const { return true; }
+    __device__ uint32_t* hist_of(int s, bool, const SelState& st) const { return st.hist + (size_t)s * kHistBins; }
+    __device__ uint32_t nphys(int, bool) const { return ntiles << tile_log2; }      // <= 2^31 + 8192
+    __device__ uint32_t group_slots(bool) const { return 1u << tile_log2; }
+    __device__ uint32_t ngroups(int, bool) const { return ntiles; }
+    __device__ Digit digit(int s, bool, const SelState&) const { return Digit{tspec[s], (uint32_t)kFineShift}; }
+    __device__ uint32_t kept(int s, uint32_t g) const {
+        const uint32_t c = tile_cnt[(size_t)s * ntiles + g];
+        return c < (1u << tile_log2) ? c : (1u << tile_log2);
+    }
+    __device__ bool group_range(int s, uint32_t g, uint32_t& first, uint32_t& end) const {
+        if (g >= ntiles) return false;
+        const uint32_t c = kept(s, g);
+        if (c == 0u) return false;
+        first = g << tile_log2;
+        end = first + c;
+        return true;
+    }
+    __device__ uint32_t fetch_bits(int s, uint32_t p) const { return __float_as_uint(val[(size_t)s * stride + p]); }
+    __device__ bool is_tomb(int, uint32_t) const { return false; }
+    __device__ bool fetch_phys(int s, bool, uint32_t p, uint32_t& i, uint32_t& bits) const {
+        const uint32_t g = p >> tile_log2;
+        if (g >= ntiles || p - (g << tile_log2) >= kept(s, g)) return false;
+        i = idx[(size_t)s * stride + p];
+        bits = __float_as_uint(val[(size_t)s * stride + p]);
+        return true;
+    }
+    __device__ bool fetch_key_phys(int s, bool dn, uint32_t p, uint32_t& key) const {
+        uint32_t i, bits = 0;
+        const bool ok = fetch_phys(s, dn, p, i, bits);
+        key = bits & kAbs;
+        return ok;
+    }
+    __device__ uint32_t logical(int, bool, uint32_t p, uint32_t) const { return p; }
+    __device__ void store_ordered(int, bool, uint32_t, uint32_t, uint32_t) const {}
+    __device__ bool fetch_ord(int s, bool dn, uint32_t lp, uint32_t& i, uint32_t& bits) const {
+        return fetch_phys(s, dn, lp, i, bits);
+    }
+    // (inside a range from group_range() every slot is a kept one)
+    __device__ bool fetch_emit(int s, bool, uint32_t p, uint32_t& i, uint32_t& bits) const {
+        i = idx[(size_t)s * stride + p];
+        bits = __float_as_uint(val[(size_t)s * stride + p]);
+        return true;
+    }
+    __device__ uint32_t group_of(int, bool, uint32_t p, uint32_t) const { return p >> tile_log2; }
+    __device__ uint32_t group_of_ord(int, bool, uint32_t lp, uint32_t) const { return lp >> tile_log2; }
     __device__ void scan_runs(int, uint32_t*) const {}
 };
 
@@ -687,6 +774,7 @@ __device__ __forceinline__ void bucket_general(const Src& src, const SelState& s
 // bookkeeping for an overflowing list); every other set the plain one.
 template <class Src>
 __global__ __launch_bounds__(kBlock) void k_bucket(Src src, SelState st, uint32_t k) {
+    if (src.skip(blockIdx.y)) return;
     if (src.dense(blockIdx.y)) bucket_general(src, st, k);
     else bucket_fast(src, st, k);
 }
@@ -753,6 +841,7 @@ __global__ __launch_bounds__(1024) void k_finish(Src src, SelState st) {
     __shared__ uint32_t s_out[3];
     const int s = blockIdx.x;
     const uint32_t t = threadIdx.x;
+    if (src.skip(s)) return;
     const bool dn = src.dense(s);
     const uint32_t nphys = src.nphys(s, dn);
     const uint32_t ng = src.ngroups(s, dn);          // <= kMaxGroups
@@ -908,7 +997,7 @@ __device__ __forceinline__ void emit_fast(
         for (int j = 0; j < kBatch; ++j) {
             const uint32_t p = i0 + j * kBlock + t;
             idx[j] = 0; vb[j] = 0;
-            ok[j] = p < end && src.fetch_ord(s, dn, p, idx[j], vb[j]);
+            ok[j] = p < end && src.fetch_emit(s, dn, p, idx[j], vb[j]);
         }
     };
     load_round((uint32_t)first);
@@ -1355,6 +1444,7 @@ __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(7, 8))) 
         Src src, SelState st, uint32_t k, uint32_t* __restrict__ out_idx,
         float* __restrict__ out_val, int64_t out_stride, float divisor,
         uint32_t* __restrict__ gbits) {
+    if (src.skip(blockIdx.y)) return;
     if (src.dense(blockIdx.y))
         emit_general<Src, DIVIDE, INLINE, kBlock>(src, st, k, out_idx, out_val, out_stride, divisor, gbits);
     else

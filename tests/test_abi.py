@@ -204,6 +204,11 @@ def test_debug_plan_describes_the_sampler():
     assert 0 < c1["small_n_tiles"] * c1["tile_len"] <= c1["n_tiles"] * c1["tile_len"]
     assert c1["small_target"] >= 1 and c1["small_tile_stride"] >= c1["tile_len"]
     assert B.gtopk_debug_plan(14_728_266, 14_728, 16)["small_n_tiles"] == 0
+    # merges of very large sets go through a speculative threshold
+    assert B.gtopk_debug_plan(25_557_032, 255_570, 32)["merge_filtered"] == 0
+    big = B.gtopk_debug_plan(25_557_032, 6_389_258, 32)
+    assert big["merge_filtered"] == 1 and big["merge_n_tiles"] * big["tile_len"] < 6_389_258
+    assert B.gtopk_debug_plan(25_557_032, 6_389_258, 1)["merge_filtered"] == 0      # P = 1: no merge
     # long runs of candidates (C4b and the warm-up densities) are selected in place
     assert B.gtopk_debug_plan(25_557_032, 25_557, 32)["run_groups"] == 0
     assert B.gtopk_debug_plan(25_557_032, 255_570, 32)["run_groups"] == 1

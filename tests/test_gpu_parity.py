@@ -121,6 +121,61 @@ def test_merge_parity(kind, k, m):
         assert bits_equal(gv[b], ov), f"b={b} val: {first_diff(gv[b], ov)}"
 
 
+def _gap_ksets(n_sets, k, m, seed):
+    """Index sets for very large k without a permutation of [0, m): ascending random gaps."""
+    rng = np.random.default_rng(seed)
+    idx = np.empty((n_sets, k), dtype=np.uint32)
+    val = np.empty((n_sets, k), dtype=np.float32)
+    for s in range(n_sets):
+        gaps = rng.integers(1, 2 * (m // k), k, dtype=np.int64)       # mean m / k
+        pos = np.cumsum(gaps) - 1
+        assert pos[-1] < m
+        idx[s] = pos.astype(np.uint32)
+        val[s] = rng.standard_normal(k).astype(np.float32)
+    return idx, val
+
+
+def test_merge_speculative_threshold_hits_and_misses():
+    """Merges of more than 2^22 entries keep only the slots of the union that reach a threshold
+    taken from a sample.  Pair 0 is ordinary; pair 1 has its large values exactly where the
+    sample looks in both operands, so the threshold lands among them and fewer than k slots are
+    kept: that pair is merged once more from its complete union; pair 2 is all ties (and the
+    operands cancel at every shared index).  All in one launch, bit for bit against the oracle."""
+    import torch
+    from paper_1901_04359_amd import binding as B
+    k, m, batch = 4_200_003, 33_554_432, 3
+    plan = B.gtopk_debug_plan(m, k, 2)
+    assert plan["merge_filtered"] == 1
+    idx, val = _gap_ksets(2 * batch, k, m, seed=77)
+    a_idx, a_val = idx[0::2].copy(), val[0::2].copy()
+    b_idx, b_val = idx[1::2].copy(), val[1::2].copy()
+    assert np.isin(b_idx[0][:100_000], a_idx[0]).sum() > 1000          # the operands do share indices
+    rng = np.random.default_rng(5)
+    t = np.arange(plan["merge_n_tiles"], dtype=np.int64)[:, None] * plan["merge_tile_stride"]
+    pos = (t + np.arange(plan["tile_len"], dtype=np.int64)[None, :]).ravel()
+    pos = pos[pos < k]
+    assert 2 * pos.size < k
+    a_val[1] *= np.float32(1e-3)
+    b_val[1] *= np.float32(1e-3)
+    a_val[1, pos] = (1.0 + rng.random(pos.size)).astype(np.float32)
+    b_val[1, pos] = -(1.0 + rng.random(pos.size)).astype(np.float32)
+    a_val[2] = np.float32(0.25)
+    b_val[2] = np.float32(-0.25)
+    say(f"merge through a speculative threshold k={k} batch={batch}")
+    ws = B.alloc_merge_workspace(k, batch)
+    ws.fill_(0x5A)
+    out_idx = torch.zeros((batch, k), dtype=torch.int32, device="cuda")
+    out_val = torch.zeros((batch, k), dtype=torch.float32, device="cuda")
+    B.gtopk_merge(to_dev(a_idx), to_dev(a_val), to_dev(b_idx), to_dev(b_val), k, batch, k, out_idx, out_val, k, ws)
+    kept = B.gtopk_debug_merge_kept(ws, k, batch)
+    assert kept[0] >= k and kept[1] < k, kept
+    gi, gv = idx_np(out_idx), val_np(out_val)
+    for b in range(batch):
+        oi, ov = orc.merge(a_idx[b], a_val[b], b_idx[b], b_val[b], k)
+        assert np.array_equal(gi[b], oi), f"b={b} (kept {kept[b]}) idx: {first_diff(gi[b], oi)}"
+        assert bits_equal(gv[b], ov), f"b={b} (kept {kept[b]}) val: {first_diff(gv[b], ov)}"
+
+
 @pytest.mark.parametrize("layout", ["a_below_b", "b_below_a", "identical", "interleaved",
                                     "blocks", "one_shared"])
 @pytest.mark.parametrize("k", [300, 66_000, 100_003])
