@@ -272,11 +272,15 @@ __global__ __launch_bounds__(BLOCK) void k_union_path(
     __shared__ uint32_t s_i[kStage + EPT];
     __shared__ float s_v[kStage + EPT];
     __shared__ uint32_t s_split[2];
-    __shared__ uint32_t s_hist[HIST ? kHistBins : 1];
+    // two 16-bit counters per word: a tile holds kTile <= 65535 slots, so no count overflows, and
+    // with the histogram at 8 KB two blocks fit the CU's LDS
+    static_assert(kTile < 65536u, "16-bit counters");
+    __shared__ uint32_t s_hist[HIST ? kHistBins / 2 : 1];
+    auto count_bin = [&](uint32_t b) { atomicAdd(&s_hist[b >> 1], (b & 1u) ? 0x10000u : 1u); };
     __shared__ uint32_t s_scan[FILTER ? BLOCK / kWave : 1];
     const int s = blockIdx.y;
     if (HIST)
-        for (int b = threadIdx.x; b < kHistBins; b += BLOCK) s_hist[b] = 0u;   // barriers follow
+        for (int b = threadIdx.x; b < kHistBins / 2; b += BLOCK) s_hist[b] = 0u;   // barriers follow
     {
         const uint32_t nthreads = gridDim.x * gridDim.y * BLOCK;
         for (uint32_t i = (blockIdx.y * gridDim.x + blockIdx.x) * BLOCK + threadIdx.x; i < zero_words;
@@ -395,7 +399,7 @@ __global__ __launch_bounds__(BLOCK) void k_union_path(
                 const Digit dg = hsrc.digit(s, false, hst);
 #pragma unroll
                 for (int j = 0; j < EPT; ++j)
-                    if (oi[j] != kTomb) atomicAdd(&s_hist[dg.bin(__float_as_uint(ov[j]) & kAbs)], 1u);
+                    if (oi[j] != kTomb) count_bin(dg.bin(__float_as_uint(ov[j]) & kAbs));
             }
         }
     } else {
@@ -418,7 +422,7 @@ __global__ __launch_bounds__(BLOCK) void k_union_path(
                 s_i[pos] = oi[j];
                 s_v[pos] = ov[j];
                 ++pos;
-                atomicAdd(&s_hist[dg.bin(__float_as_uint(ov[j]) & kAbs)], 1u);
+                count_bin(dg.bin(__float_as_uint(ov[j]) & kAbs));
             }
         }
         __syncthreads();
@@ -437,7 +441,7 @@ __global__ __launch_bounds__(BLOCK) void k_union_path(
         __syncthreads();
         uint32_t* out = hst.hist + (size_t)s * kHistBins;
         for (int b = threadIdx.x; b < kHistBins; b += BLOCK) {
-            const uint32_t c = s_hist[b];
+            const uint32_t c = (s_hist[b >> 1] >> ((b & 1) * 16)) & 0xFFFFu;
             if (c) atomicAdd(&out[b], c);
         }
     }
