@@ -405,9 +405,7 @@ bool pass_histograms(int64_t m, uint32_t k) {
     return per_block <= 128.0 || per_block >= 4096.0;
 }
 
-// `zero_rows`: store +0.0 at the selected entries (the stand-alone call); gtopk_step
-// passes false and settles the rows in k_restore_fused.  `pre_cleared`: the caller has
-// already cleared this call's counters and histograms.
+// the candidate lists (or dense rows) of the P workers as the select kernels' source
 CandSrc cand_source(const float* rows, int64_t stride, int64_t m, uint32_t k, const StepWs& w,
                     bool producer_hist, bool no_bounds, uint32_t* thr_state = nullptr) {
     return CandSrc{rows, stride, (uint32_t)m, k, w.cap, w.nchunks, w.Lc, w.Ld,
@@ -780,7 +778,7 @@ static int step_impl(const float* grad, float* residual, int64_t m, int64_t stri
     if (rc != GTOPK_OK) return rc;
     mark_stage(4, events, st);
     hipLaunchKernelGGL(k_restore_fused, dim3(ceil_div((uint32_t)k, kBlock), (uint32_t)P), dim3(kBlock),
-                       0, st, residual, stride, (uint32_t)k, li, lv, w.gbits);
+                       0, st, residual, stride, (uint32_t)k, li, lv, w.gbits, (const uint32_t*)w.sel.T);
     rc = launch_status();
     mark_stage(5, events, st);
     return rc;

@@ -563,15 +563,18 @@ __global__ __launch_bounds__(kBlock) void k_restore(
 // (the row still holds acc there).  Zero-then-add-back leaves acc unchanged except that
 // +0.0 + (-0.0) = +0.0, so: an entry whose index is in the global set becomes +0.0, an
 // entry that is -0.0 becomes +0.0, every other entry is already what the literal form
-// produces.  gbits is the one-bit-per-element mask of the global set.
+// produces.  gbits is the one-bit-per-element mask of the global set.  loc_min[w] is the
+// smallest key of worker w's set: only a set that reaches down to key 0 can hold a -0.0, so
+// the values of every other set are not read at all.
 __global__ __launch_bounds__(kBlock) void k_restore_fused(
         float* __restrict__ res, int64_t stride, uint32_t k, const uint32_t* __restrict__ loc_idx,
-        const float* __restrict__ loc_val, const uint32_t* __restrict__ gbits) {
+        const float* __restrict__ loc_val, const uint32_t* __restrict__ gbits,
+        const uint32_t* __restrict__ loc_min) {
     const int w = blockIdx.y;
     const uint32_t t = blockIdx.x * kBlock + threadIdx.x;
     if (t >= k) return;
     const uint32_t i = loc_idx[(size_t)w * k + t];
-    const uint32_t vb = __float_as_uint(loc_val[(size_t)w * k + t]);
+    const uint32_t vb = loc_min[w] == 0u ? __float_as_uint(loc_val[(size_t)w * k + t]) : 0u;   // block-uniform
     const bool in_g = (gbits[i >> 5] >> (i & 31)) & 1u;
     if (in_g || vb == 0x80000000u) res[(int64_t)w * stride + i] = 0.0f;
 }
