@@ -13,7 +13,10 @@
 //                  instead (same kernels, decided on the device).
 //   tree           per round: index-ordered union of the two k-sets of each pair
 //                  (values at shared indices added) -> the same exact select
-//                  -> ordered emit; the last round divides by P.
+//                  -> ordered emit; the last round divides by P.  Very large sets are
+//                  merged through a speculative threshold of their own (a sample of
+//                  the union; only the slots that reach it are kept), with the
+//                  complete union standing by for a pair whose threshold misses.
 //   restore        membership test of each local entry in the global index set.
 //
 // Nothing here is a dense contraction, so there is no MFMA; the streaming pass is

@@ -7,8 +7,9 @@
 //   k_bucket  every block picks, from that histogram, the bin d1 that holds the k-th
 //             key; then, per group of slots: count of keys above the bin; keys inside
 //             the bin are appended (with their group) to a short list.  For the local
-//             selection this walk also copies the candidates, which the streaming pass
-//             left as runs in arbitrary order, into index order.
+//             selection of short runs this walk also copies the candidates, which the
+//             streaming pass left as runs in arbitrary order, into index order (CandSrc);
+//             long runs are selected where they lie, one group per run (RunSrc).
 //   k_emit    every block: LDS radix passes over the list give the exact key T and the
 //             number of ties to take, and the block's output offsets; then, per group:
 //             ordered compaction of the selected entries
@@ -52,7 +53,10 @@ struct SelState {
 // positions.  k_hist and k_bucket walk the physical slots; logical() maps a physical slot
 // to its logical position; kIdentity says the two orders coincide.  fetch_ord() reads an
 // item by logical position (for the ordered emit).  fetch_*() return false for a slot that
-// holds nothing.
+// holds nothing.  group_range() hands a block the slots of a group of a set that is not
+// read as a dense row; sources whose groups are not equal cuts of the logical order
+// (kRunGroups: the runs of the streaming pass, the tiles of a filtered union) answer it
+// from their own tables.  skip() takes a set out of a launch altogether.
 
 // Local select: the candidate list of worker s, or - when the speculative threshold
 // left fewer than k candidates or more than the list holds - the worker's dense row.
