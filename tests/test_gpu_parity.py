@@ -959,7 +959,7 @@ def test_non_finite_inputs_keep_the_structure():
     assert np.isin(gi, np.unique(li)).all()
 
 
-@pytest.mark.parametrize("k", [300, 70_000, 600_000])
+@pytest.mark.parametrize("k", [300, 70_000, 600_000, 4_300_000])      # one size per union kernel
 def test_merge_of_unsorted_sets_stays_in_bounds(k):
     """Unsorted or duplicate indices in caller-supplied sets give unspecified results, but the
     call must complete and leave neighbouring memory alone (guard words around the output)."""
