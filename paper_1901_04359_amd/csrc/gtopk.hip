@@ -468,8 +468,12 @@ int do_local_select(const float* grad, float* residual, int64_t m, int64_t strid
     if (run_groups(m, k)) {
         RunSrc rs;
         static_cast<CandSrc&>(rs) = src;
+        // k_bucket: every wave of a block takes a run; k_emit: a block per run; a worker on its
+        // dense row uses the blocks there are
         SelGrid gr = local_grid(w, P);
-        if (gr.groups < w.nchunks) gr.groups = gr.walk_blocks = w.nchunks;
+        const uint32_t rb = ceil_div(w.nchunks, kBlock / kWave);
+        if (gr.walk_blocks < rb) gr.walk_blocks = rb;
+        if (gr.groups < w.nchunks) gr.groups = w.nchunks;
         run_select<RunSrc, false>(rs, w.sel, gr, k, out_idx, out_val, (int64_t)k, 1.0f, nullptr, st);
     } else {
         run_select<CandSrc, false>(src, w.sel, local_grid(w, P), k, out_idx, out_val, (int64_t)k, 1.0f,
