@@ -9,18 +9,18 @@ wherever something is selected, no blocking, no approximation), and the steps
 are composed in the order the paper gives them, so that each can be checked
 against its passage by eye:
 
-  * Algorithm 4 (the S-SGD iteration built on gTopKAllReduce), lines 4-8:
+  * Algorithm 4 (the S-SGD iteration built on gTopKAllReduce), its local part:
     accumulate, threshold, mask, extract, keep residual  -> `local_select`
   * Definition 1 (the Top-k operation between two sparse vectors) -> `merge`
-  * Algorithm 3 (gTopKAllReduce), lines 1-18: the binary tree    -> `tree`
+  * Algorithm 3 (gTopKAllReduce), the rounds of the binary tree  -> `tree`
   * Eq. 3 (S-SGD averages over the P workers)                  -> the /P in `tree`
-  * Algorithm 3 lines 19-23 (broadcast, gMask) and Algorithm 4 line 10
-    (extra residual)                                            -> `residual_restore`
-  * Algorithm 4 line 11 (model update) and the dense gMask      -> `apply_update`, `dense_mask`
+  * Algorithm 3's broadcast and gMask, Algorithm 4's extra-residual
+    step                                                        -> `residual_restore`
+  * Algorithm 4's model update and the dense gMask              -> `apply_update`, `dense_mask`
   * The two aggregations the paper compares against, as comparison workloads:
     Algorithm 1, procedure TopKAllReduce (gather, scatter-add, average)
                                                                  -> `topk_allreduce`
-    Algorithm 2 (naive gTop-k), lines 11-13: top-k of that dense average
+    Algorithm 2 (naive gTop-k): the top-k of that dense average
                                                                  -> `dense_topk`
 
 Precision: the paper trains in 32-bit floating point (note under Table III), so
@@ -30,9 +30,9 @@ comparison decides anything.
 
 Readings taken where the paper is silent or inconsistent:
 
-  R1  Algorithm 4 lines 5-6 compare `|G| > thr` with thr the k-th largest
-      magnitude, which taken literally selects k-1 entries, while the comment
-      on line 6 says the mask has k of them.  The comment wins: exactly k
+  R1  Algorithm 4's threshold and mask steps compare `|G| > thr` with thr the
+      k-th largest magnitude, which taken literally selects k-1 entries, while
+      the listing's own remark gives the mask k of them.  The remark wins: exactly k
       entries are selected, the first k under the total order (|v| descending,
       index ascending).
   R2  |v| is compared as the unsigned integer `bits(v) & 0x7fffffff`
@@ -114,24 +114,24 @@ def first_k_by_magnitude(keys: np.ndarray, index: np.ndarray, k: int) -> np.ndar
 
 
 def accumulate(residual: np.ndarray, grad: np.ndarray) -> np.ndarray:
-    """Algorithm 4 line 4: G_i = G_{i-1} + gradient, one fp32 add per element."""
+    """Algorithm 4, accumulation: G_i = G_{i-1} + gradient, one fp32 add per element."""
     assert residual.dtype == np.float32 and grad.dtype == np.float32
     return (residual + grad).astype(np.float32)
 
 
 def local_select(residual: np.ndarray, grad: np.ndarray, k: int
                  ) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
-    """Algorithm 4 lines 4-8 for one worker.
+    """The local part of Algorithm 4 for one worker.
 
     Returns (loc_idx uint32[k] ascending, loc_val float32[k], new residual).
     """
-    acc = accumulate(residual, grad)                                 # line 4
+    acc = accumulate(residual, grad)                                 # accumulate
     m = acc.shape[0]
     keys = magnitude_keys(acc)
-    loc_idx = first_k_by_magnitude(keys, np.arange(m, dtype=np.uint64), k)  # lines 5-6 (R1)
-    loc_val = acc[loc_idx].copy()                                     # line 7
+    loc_idx = first_k_by_magnitude(keys, np.arange(m, dtype=np.uint64), k)  # threshold + mask (R1)
+    loc_val = acc[loc_idx].copy()                                     # extract
     new_res = acc.copy()
-    new_res[loc_idx] = np.float32(0.0)                                # line 8
+    new_res[loc_idx] = np.float32(0.0)                                # keep the rest as residual
     return loc_idx, loc_val, new_res
 
 
@@ -165,7 +165,7 @@ def merge(a_idx: np.ndarray, a_val: np.ndarray, b_idx: np.ndarray, b_val: np.nda
 
 def tree_rounds(loc_idx: Sequence[np.ndarray], loc_val: Sequence[np.ndarray], k: int,
                 map_fn=map) -> List[List[Optional[Tuple[np.ndarray, np.ndarray]]]]:
-    """Algorithm 3 lines 1-18 under R5.  Returns, for each round, the list of
+    """The rounds of Algorithm 3 under R5.  Returns, for each round, the list of
     per-rank current sets after that round (None for ranks that have sent their
     set away and gone idle).  Element [-1][0] is the undivided result.
     The merges of one round are independent and go through `map_fn`."""
@@ -208,7 +208,7 @@ def tree(loc_idx: Sequence[np.ndarray], loc_val: Sequence[np.ndarray], k: int,
 
 def residual_restore(residual: np.ndarray, loc_idx: np.ndarray, loc_val: np.ndarray,
                      g_idx: np.ndarray) -> np.ndarray:
-    """Algorithm 4 line 10 for one worker: locally selected entries whose index
+    """Algorithm 4, extra residual, for one worker: locally selected entries whose index
     is not in the global set are added back to the residual (R8, R10)."""
     out = residual.copy()
     globally_kept = np.isin(loc_idx, g_idx)           # gMask at the local indices
@@ -218,7 +218,7 @@ def residual_restore(residual: np.ndarray, loc_idx: np.ndarray, loc_val: np.ndar
 
 
 def apply_update(weights: np.ndarray, g_idx: np.ndarray, g_val: np.ndarray, lr) -> np.ndarray:
-    """Algorithm 4 line 11: W_i = W_{i-1} - eta * G~_i.  G~_i is zero outside g_idx, so
+    """Algorithm 4, model update: W_i = W_{i-1} - eta * G~_i.  G~_i is zero outside g_idx, so
     only those k weights move: one fp32 multiply, then one fp32 subtract."""
     out = weights.copy()
     prod = (np.float32(lr) * g_val.astype(np.float32)).astype(np.float32)
@@ -227,7 +227,7 @@ def apply_update(weights: np.ndarray, g_idx: np.ndarray, g_val: np.ndarray, lr) 
 
 
 def dense_mask(g_idx: np.ndarray, m: int) -> np.ndarray:
-    """Algorithm 3 lines 20-22: gMask has m entries, 1 at the global indices, 0 elsewhere."""
+    """Algorithm 3, after the broadcast: gMask has m entries, 1 at the global indices, 0 elsewhere."""
     mask = np.zeros(m, dtype=np.uint8)
     mask[g_idx] = 1
     return mask
@@ -247,7 +247,7 @@ def topk_allreduce(loc_idx: Sequence[np.ndarray], loc_val: Sequence[np.ndarray],
 
 
 def dense_topk(dense: np.ndarray, k: int) -> Tuple[np.ndarray, np.ndarray]:
-    """Algorithm 2 lines 11-13: the k entries of a dense vector with the largest |v|
+    """Algorithm 2, global selection: the k entries of a dense vector with the largest |v|
     (same R1/R2 rule as the local selection), as an index-ascending sparse k-set."""
     m = dense.shape[0]
     idx = first_k_by_magnitude(magnitude_keys(dense), np.arange(m, dtype=np.uint32), k)
