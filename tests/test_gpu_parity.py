@@ -121,6 +121,24 @@ def test_merge_parity(kind, k, m):
         assert bits_equal(gv[b], ov), f"b={b} val: {first_diff(gv[b], ov)}"
 
 
+@pytest.mark.parametrize("kind", ["gauss", "ties", "cancel"])
+@pytest.mark.parametrize("k,batch", [(300_001, 16), (260_000, 8)])
+def test_merge_long_groups(kind, k, batch):
+    """Batches whose merged sets are cut into groups of 4096 and 8192 slots, which the select
+    walks four slots per load (a batch of three, as above, gets shorter groups); "ties" fills
+    the bin of the k-th key far beyond what a block parks in LDS."""
+    m = 6_000_000
+    idx, val = W.ksets(2 * batch, k, m, seed=k + batch, overlap=0.4, value_kind=kind)
+    a_idx, a_val = idx[0::2].copy(), val[0::2].copy()
+    b_idx, b_val = idx[1::2].copy(), val[1::2].copy()
+    say(f"merge, long groups: kind={kind} k={k} m={m} batch={batch}")
+    gi, gv = run_merge(a_idx, a_val, b_idx, b_val, k)
+    for b in range(batch):
+        oi, ov = orc.merge(a_idx[b], a_val[b], b_idx[b], b_val[b], k)
+        assert np.array_equal(gi[b], oi), f"b={b} idx: {first_diff(gi[b], oi)}"
+        assert bits_equal(gv[b], ov), f"b={b} val: {first_diff(gv[b], ov)}"
+
+
 def _gap_ksets(n_sets, k, m, seed):
     """Index sets for very large k without a permutation of [0, m): ascending random gaps."""
     rng = np.random.default_rng(seed)
