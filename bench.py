@@ -258,6 +258,11 @@ def main() -> int:
                     help="replace the gradient rows of this many workers by rows of equal "
                          "magnitudes, which overflow the candidate list and are selected from "
                          "the dense row (cost of the exact fallback)")
+    ap.add_argument("--short-workers", type=int, default=0,
+                    help="replace the gradient rows of this many workers by rows whose large "
+                         "magnitudes sit only where the sampler looks, so that the speculative "
+                         "threshold comes out too high, the pass keeps fewer than k candidates "
+                         "and the worker is selected from its dense row (cost of a sampling miss)")
     ap.add_argument("--carry", action="store_true",
                     help="call gtopk_step_carry (speculative thresholds carried from step to step) "
                          "instead of gtopk_step (a fresh sample of every row on every step)")
@@ -302,6 +307,18 @@ def main() -> int:
         for w in range(min(args.degenerate_workers, P)):
             sign = np.random.default_rng(1000 * b + w).integers(0, 2, m).astype(np.float32) * 2 - 1
             host[(w * 7) % P] = sign * np.float32(0.125)
+        if args.short_workers:
+            plan = B.gtopk_debug_plan(m, k, P)
+            t = np.arange(plan["n_tiles"], dtype=np.int64)[:, None] * plan["tile_stride"]
+            pos = (t + np.arange(plan["tile_len"], dtype=np.int64)[None, :]).ravel()
+            pos = pos[pos < m]
+            n_big = min(pos.size, max(plan["target"] + plan["target"] // 3, min(k - 1, 2 * plan["target"])))
+            for w in range(min(args.short_workers, P)):
+                rng = np.random.default_rng(5000 * b + w)
+                row = (rng.standard_normal(m) * 1e-3).astype(np.float32)
+                at = rng.choice(pos, n_big, replace=False)
+                row[at] = ((1.0 + rng.random(n_big)) * rng.choice([-1.0, 1.0], n_big)).astype(np.float32)
+                host[(w * 7 + 3) % P] = row
         grads.append(torch.from_numpy(host).cuda())
         del host
     t_gen = time.perf_counter() - t_gen
@@ -407,6 +424,11 @@ def main() -> int:
         out["degenerate_workers"] = {
             "requested": args.degenerate_workers,
             "served_from_dense_row_in_last_step": sum(1 for c in counts if c < k or c > cap)}
+    if args.short_workers:
+        counts, cap = B.gtopk_debug_candidate_counts(ws, m, k, P)
+        out["short_workers"] = {
+            "requested": args.short_workers,
+            "with_fewer_than_k_candidates_in_last_step": sum(1 for c in counts if c < k)}
     if not args.no_ceiling:
         out["hbm_ceiling"] = hbm_ceiling(B, torch, grads[0], res)
         res.zero_()
