@@ -9,7 +9,9 @@
 //             the bin are appended (with their group) to a short list.  For the local
 //             selection of short runs this walk also copies the candidates, which the
 //             streaming pass left as runs in arbitrary order, into index order (CandSrc);
-//             long runs are selected where they lie, one group per run (RunSrc).
+//             long runs are selected where they lie, one group per run (RunSrc), a run per
+//             wave of the walk's blocks.  Long groups of a merged set are walked four slots
+//             per load.
 //   k_emit    every block: LDS radix passes over the list give the exact key T and the
 //             number of ties to take, and the block's output offsets; then, per group:
 //             ordered compaction of the selected entries
