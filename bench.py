@@ -120,14 +120,22 @@ def hbm_ceiling(B, torch, a, b, reps: int = 20):
     t_read = timed(lambda: B.gtopk_probe_stream(av, bv, n, 1, sink))
     t_torch = timed(lambda: bv.add_(av))
     gbs = lambda nbytes, ms: round(nbytes / (ms * 1e-3) / 1e9, 1)
+    # the add form with one of the pass's choices changed at a time (cache policy, block shape)
+    variants = {"temporal_loads": 2, "temporal_stores": 3, "temporal_loads_and_stores": 4,
+                "256_threads_x_32": 5, "1024_threads_x_8": 6, "8192_element_blocks": 7}
+    sweep = {name: gbs(12.0 * n, timed(lambda md=md: B.gtopk_probe_stream(av, bv, n, md, None)))
+             for name, md in variants.items()}
     return {
         "elements": n,
         "probe_add_GBs": gbs(12.0 * n, t_add), "probe_add_ms": round(t_add, 4),
         "probe_read_GBs": gbs(8.0 * n, t_read), "probe_read_ms": round(t_read, 4),
         "torch_add_GBs": gbs(12.0 * a.numel(), t_torch), "torch_add_ms": round(t_torch, 4),
+        "probe_add_variants_GBs": sweep,
         "note": ("probe = k_probe_stream, the streaming pass's block shape and cache policy with "
                  "only the memory traffic left; add: 12 B per element, read: 8 B per element; "
-                 "torch_add = torch's b.add_(a) on the same buffers"),
+                 "torch_add = torch's b.add_(a) on the same buffers; probe_add_variants = the add "
+                 "form with one choice changed: ordinary instead of non-temporal loads / stores, "
+                 "other block shapes (the pass: 512 threads x 16 accesses, 32768 elements per block)"),
     }
 
 

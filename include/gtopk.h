@@ -264,9 +264,16 @@ int gtopk_step_timed(const float* grad, float* residual, int64_t m, int64_t stri
  * memory system gives to that access pattern.
  *   mode 0: b[i] = b[i] + a[i] for i < n  (8 bytes read and 4 written per element, as the pass)
  *   mode 1: a and b are only read; one float per 32768 elements is written to sink
- *           (sink holds n / 32768 floats; it may be NULL in mode 0)
+ *           (sink holds n / 32768 floats; it may be NULL in every other mode)
+ * Modes 2 to 7 are mode 0 with ONE of the pass's choices changed, so that the choice is
+ * measured rather than asserted:
+ *   mode 2: ordinary (temporal) loads      mode 3: ordinary stores      mode 4: both ordinary
+ *   mode 5: 256 threads x 32 accesses per lane and array   mode 6: 1024 threads x 8
+ *           (the pass: 512 x 16; all three cover 32768 elements per block)
+ *   mode 7: 512 threads x 4: blocks of 8192 elements
  * n must be a positive multiple of 32768.
  */
+#define GTOPK_PROBE_MODES 8
 int gtopk_probe_stream(const float* a, float* b, int64_t n, int32_t mode, float* sink,
                        void* stream);
 

@@ -958,16 +958,23 @@ int gtopk_debug_merge_kept(const void* ws, int32_t k, int32_t batch, uint32_t* h
 int gtopk_probe_stream(const float* a, float* b, int64_t n, int32_t mode, float* sink,
                        void* stream) {
     if (!a || !b || n < 1 || n % kChunk != 0 || n / kChunk > 0x7fffffff) return GTOPK_EINVAL;
-    if (mode != 0 && mode != 1) return GTOPK_EINVAL;
+    if (mode < 0 || mode >= GTOPK_PROBE_MODES) return GTOPK_EINVAL;
     if (mode == 1 && !sink) return GTOPK_EINVAL;
     if (!aligned16(a) || !aligned16(b) || !aligned16(sink)) return GTOPK_EALIGN;
-    const uint32_t blocks = (uint32_t)(n / kChunk);
-    if (mode == 0)
-        hipLaunchKernelGGL(k_probe_stream<true>, dim3(blocks), dim3(kSBlock), 0, (hipStream_t)stream, a, b,
-                           sink);
-    else
-        hipLaunchKernelGGL(k_probe_stream<false>, dim3(blocks), dim3(kSBlock), 0, (hipStream_t)stream, a,
-                           b, sink);
+    const uint32_t blocks = (uint32_t)(n / kChunk);      // of the pass's shape: 32768 elements each
+    hipStream_t st = (hipStream_t)stream;
+    switch (mode) {
+        case 0: hipLaunchKernelGGL(k_probe_stream<true>, dim3(blocks), dim3(kSBlock), 0, st, a, b, sink); break;
+        case 1: hipLaunchKernelGGL(k_probe_stream<false>, dim3(blocks), dim3(kSBlock), 0, st, a, b, sink); break;
+        // cache policy
+        case 2: hipLaunchKernelGGL((k_probe_stream<true, false, true>), dim3(blocks), dim3(kSBlock), 0, st, a, b, sink); break;
+        case 3: hipLaunchKernelGGL((k_probe_stream<true, true, false>), dim3(blocks), dim3(kSBlock), 0, st, a, b, sink); break;
+        case 4: hipLaunchKernelGGL((k_probe_stream<true, false, false>), dim3(blocks), dim3(kSBlock), 0, st, a, b, sink); break;
+        // block shape (elements per block: 32768, 32768, 8192)
+        case 5: hipLaunchKernelGGL((k_probe_stream<true, true, true, 256, 32>), dim3(blocks), dim3(256), 0, st, a, b, sink); break;
+        case 6: hipLaunchKernelGGL((k_probe_stream<true, true, true, 1024, 8>), dim3(blocks), dim3(1024), 0, st, a, b, sink); break;
+        default: hipLaunchKernelGGL((k_probe_stream<true, true, true, 512, 4>), dim3(blocks * 4), dim3(512), 0, st, a, b, sink); break;
+    }
     return launch_status();
 }
 

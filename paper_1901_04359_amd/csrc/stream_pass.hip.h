@@ -232,29 +232,39 @@ __global__ __launch_bounds__(kSBlock) void k_accum_filter(
 //   ADD:  b[i] = b[i] + a[i]          (8 bytes read, 4 written per element, as the pass)
 //   !ADD: both arrays read, one float per block written to `sink` (read-only ceiling)
 // n is a multiple of kChunk (the caller checks).
-template <bool ADD>
-__global__ __launch_bounds__(kSBlock) void k_probe_stream(
+// The other template arguments vary what the pass fixed, so that the choice stays on
+// record: NTL / NTS = non-temporal loads / stores; THREADS x ITERS = threads per block x
+// float4 per lane and array (a block covers THREADS * ITERS * 4 elements).
+template <bool ADD, bool NTL = true, bool NTS = true, int THREADS = kSBlock, int ITERS = kIters>
+__global__ __launch_bounds__(THREADS) void k_probe_stream(
         const float* __restrict__ a, float* __restrict__ b, float* __restrict__ sink) {
+    constexpr int kSpan = ITERS * 4 * kWave;                 // elements per wave
     const uint32_t lane = lane_id();
     const uint32_t wave = threadIdx.x / kWave;
-    const size_t base = (size_t)blockIdx.x * kChunk + (size_t)wave * kWaveSpan;
-    floatx4 av[kIters], bv[kIters];
+    const size_t base = (size_t)blockIdx.x * ((size_t)kSpan * (THREADS / kWave)) + (size_t)wave * kSpan;
+    floatx4 av[ITERS], bv[ITERS];
 #pragma unroll
-    for (int i = 0; i < kIters; ++i) {
+    for (int i = 0; i < ITERS; ++i) {
         const size_t v = base + i * 256 + lane * 4;
-        av[i] = __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(a + v));
-        bv[i] = __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(b + v));
+        if (NTL) {
+            av[i] = __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(a + v));
+            bv[i] = __builtin_nontemporal_load(reinterpret_cast<const floatx4*>(b + v));
+        } else {
+            av[i] = *reinterpret_cast<const floatx4*>(a + v);
+            bv[i] = *reinterpret_cast<const floatx4*>(b + v);
+        }
     }
     if (ADD) {
 #pragma unroll
-        for (int i = 0; i < kIters; ++i) {
+        for (int i = 0; i < ITERS; ++i) {
             const size_t v = base + i * 256 + lane * 4;
-            __builtin_nontemporal_store(bv[i] + av[i], reinterpret_cast<floatx4*>(b + v));
+            if (NTS) __builtin_nontemporal_store(bv[i] + av[i], reinterpret_cast<floatx4*>(b + v));
+            else *reinterpret_cast<floatx4*>(b + v) = bv[i] + av[i];
         }
     } else {
         floatx4 acc = av[0] + bv[0];
 #pragma unroll
-        for (int i = 1; i < kIters; ++i) acc = acc + av[i] + bv[i];
+        for (int i = 1; i < ITERS; ++i) acc = acc + av[i] + bv[i];
         float s = acc.x + acc.y + acc.z + acc.w;
 #pragma unroll
         for (int d = 32; d >= 1; d >>= 1) s += __shfl_xor(s, d);

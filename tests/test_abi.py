@@ -180,7 +180,7 @@ def test_argument_errors_timed_probe():
                                              kw.get("mode", 0), kw.get("sink", FAKE), None)
     assert pr(a=None) == B.GTOPK_EINVAL
     assert pr(n=1000) == B.GTOPK_EINVAL                         # not a multiple of 32768
-    assert pr(mode=2) == B.GTOPK_EINVAL
+    assert pr(mode=8) == B.GTOPK_EINVAL and pr(mode=-1) == B.GTOPK_EINVAL
     assert pr(mode=1, sink=None) == B.GTOPK_EINVAL
     assert pr(a=ODD) == B.GTOPK_EALIGN
 

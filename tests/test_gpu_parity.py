@@ -1017,3 +1017,29 @@ def test_allreduce_of_unsorted_sets_stays_in_bounds():
     torch.cuda.synchronize()
     assert bool((buf[:guard] == 7.0).all()) and bool((buf[-guard:] == 7.0).all())
     assert bool(torch.isfinite(buf[guard:guard + m]).all())
+
+
+def test_probe_stream_modes():
+    """The bandwidth probe (instrumentation of the benchmark): every add form leaves b + a in b,
+    one IEEE add per element, whatever its cache policy and block shape; the read-only form
+    leaves both arrays alone and writes one finite float per 32768 elements."""
+    import torch
+    from paper_1901_04359_amd import binding as B
+    n = 5 * 32768
+    rng = np.random.default_rng(3)
+    a = rng.standard_normal(n).astype(np.float32)
+    b0 = rng.standard_normal(n).astype(np.float32)
+    da = to_dev(a)
+    for mode in (0, 2, 3, 4, 5, 6, 7):
+        db = to_dev(b0)
+        say(f"probe mode {mode}")
+        B.gtopk_probe_stream(da, db, n, mode, None)
+        torch.cuda.synchronize()
+        assert bits_equal(val_np(db), b0 + a), f"mode {mode}: {first_diff(val_np(db), b0 + a)}"
+        assert bits_equal(val_np(da), a)
+    db = to_dev(b0)
+    sink = torch.full((n // 32768,), float("nan"), dtype=torch.float32, device="cuda")
+    B.gtopk_probe_stream(da, db, n, 1, sink)
+    torch.cuda.synchronize()
+    assert bits_equal(val_np(db), b0) and bits_equal(val_np(da), a)
+    assert np.isfinite(val_np(sink)).all()
