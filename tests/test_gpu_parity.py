@@ -243,6 +243,23 @@ def test_tree_parity(P, k, m, kind):
     assert bits_equal(gv, ov), first_diff(gv, ov)
 
 
+@pytest.mark.parametrize("kind", ["gauss", "ties"])
+def test_tree_large_sets(kind):
+    """A tree of 16 sets of 300,000 entries: unions cut by output position, and rounds whose
+    merged sets are cut into groups of 4864, 2560, 1280 and 768 slots (the select walks the
+    first round's four slots per load, the others slot by slot)."""
+    P, k, m = 16, 300_000, 6_000_000
+    idx, val = W.ksets(P, k, m, seed=P + k, overlap=0.5, value_kind=kind)
+    dev = Device(P, k, k)
+    dev.loc_idx.copy_(to_dev(idx))
+    dev.loc_val.copy_(to_dev(val))
+    say(f"tree of large sets P={P} k={k} m={m} kind={kind}")
+    gi, gv = dev.tree()
+    oi, ov = orc.tree(list(idx), list(val), k)
+    assert np.array_equal(gi, oi), first_diff(gi, oi)
+    assert bits_equal(gv, ov), first_diff(gv, ov)
+
+
 def test_tree_every_round_matches_oracle():
     """Intermediate sets of every round, through gtopk_merge, in the tree's pairing."""
     P, k, m = 8, 500, 20_000
