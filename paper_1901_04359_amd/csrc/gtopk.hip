@@ -79,6 +79,7 @@ SelState carve_select(Carver& c, size_t sets, uint32_t list_cap, uint32_t maxgro
     s.off_eq = c.take<uint32_t>(sets * maxgroups);
     s.list_cap = list_cap;
     s.maxgroups = maxgroups;
+    s.seg_list = 0u;
     return s;
 }
 // words from s.hist to the end of s.bin_lo_inv / s.hist_dense (padding included)
@@ -332,9 +333,12 @@ struct SelGrid {
 
 // histogram + bucket + emit
 template <class Src, bool DIVIDE>
-void run_select(const Src& src, const SelState& ss, const SelGrid& gr, uint32_t k, uint32_t* out_idx,
+void run_select(const Src& src, const SelState& ss0, const SelGrid& gr, uint32_t k, uint32_t* out_idx,
                 float* out_val, int64_t out_stride, float divisor, uint32_t* gbits, hipStream_t st,
                 bool with_hist = true) {
+    // large merged sets, finished once per set: the in-bin keys stay with their groups (no shared counter)
+    SelState ss = ss0;
+    ss.seg_list = (Src::kSegList && gr.own_finish) ? 1u : 0u;
     // few blocks per set (a popular bin takes one same-address atomic per block): 4 slots per
     // thread up to 32 blocks, then 32 blocks with more slots per thread, then 32 slots per
     // thread up to 256 blocks (swept at k = 255,570 .. 6.4 M)

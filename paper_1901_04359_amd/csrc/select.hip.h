@@ -45,6 +45,12 @@ struct SelState {
     uint32_t* off_gt;     // [sets][maxgroups] written by k_finish only: selected entries with
     uint32_t* off_eq;     //   key > T / entries with key == T in the groups before this one
     uint32_t list_cap, maxgroups;
+    // seg_list != 0 (large merged sets, finished by k_finish): the in-bin keys of group g are not
+    // appended to one list through a shared counter but stored from position (first slot of
+    // group g) of `list` on, grp_in[g] of them - a block of k_bucket then waits for no atomic
+    // (all blocks of a set reserving on one counter cost the walk a quarter of its time);
+    // list_cnt stays 0
+    uint32_t seg_list;
 };
 
 // ---------------------------------------------------------------------------------
@@ -72,6 +78,7 @@ struct CandSrc {
     static constexpr bool kRunGroups = false;
     static constexpr bool kWaveGroups = false;
     static constexpr bool kVectorWalk = false;
+    static constexpr bool kSegList = false;
     static constexpr bool kValueOnlyWalk = false;
     __device__ uint32_t fetch_bits(int, uint32_t) const { return 0u; }
     __device__ bool is_tomb(int, uint32_t) const { return false; }
@@ -290,6 +297,7 @@ struct MergedSrc {
     // rows of values are 16-byte aligned and padded to whole vectors, groups start at
     // multiples of four slots: k_bucket walks them four slots per load
     static constexpr bool kVectorWalk = true;
+    static constexpr bool kSegList = true;          // no set of this source is ever read as a dense row
     __device__ const uint32_t* value_row(int s) const { return reinterpret_cast<const uint32_t*>(val) + (size_t)s * stride; }
     static constexpr bool kIdentity = true;
     static constexpr bool kRunScan = false;
@@ -365,6 +373,7 @@ struct FiltSrc {
     static constexpr bool kRunGroups = true;
     static constexpr bool kWaveGroups = false;
     static constexpr bool kVectorWalk = true;
+    static constexpr bool kSegList = true;          // no set of this source is ever read as a dense row
     __device__ const uint32_t* value_row(int s) const { return reinterpret_cast<const uint32_t*>(val) + (size_t)s * stride; }
     static constexpr bool kIdentity = false;
     static constexpr bool kRunScan = false;
@@ -601,7 +610,12 @@ __device__ __forceinline__ void bucket_fast(const Src& src, const SelState& st, 
         uint32_t tg = 0, ti = 0;
         for (int v = 0; v < kBlock / kWave; ++v) { tg += s_gt[v]; ti += s_in[v]; }
         if (kOwnGroup) ggt[g] = tg;
-        s_base = ti ? atomicAdd(&st.list_cnt[s], ti) : 0u;     // one reservation per block
+        if (Src::kSegList && st.seg_list) {                    // the group's own range of the list
+            st.grp_in[(size_t)s * st.maxgroups + g] = ti;
+            s_base = (uint32_t)first;
+        } else {
+            s_base = ti ? atomicAdd(&st.list_cnt[s], ti) : 0u;     // one reservation per block
+        }
     }
     __syncthreads();
     const uint32_t total = s_nstash;
@@ -727,7 +741,12 @@ __device__ __forceinline__ void bucket_vec(const Src& src, const SelState& st, u
         uint32_t tg = 0, ti = 0;
         for (int w = 0; w < kWaves; ++w) { tg += s_gt[w]; ti += s_in[w]; }
         st.grp_gt[(size_t)s * st.maxgroups + g] = tg;
-        s_base = ti ? atomicAdd(&st.list_cnt[s], ti) : 0u;     // one reservation per block
+        if (Src::kSegList && st.seg_list) {                    // the group's own range of the list
+            st.grp_in[(size_t)s * st.maxgroups + g] = ti;
+            s_base = (uint32_t)first;
+        } else {
+            s_base = ti ? atomicAdd(&st.list_cnt[s], ti) : 0u;     // one reservation per block
+        }
     }
     __syncthreads();
     const uint32_t total = s_nstash;
@@ -1107,6 +1126,11 @@ __global__ __launch_bounds__(1024) void k_finish(Src src, SelState st) {
     __shared__ uint32_t g_eq[kMaxGroups];
     __shared__ uint32_t s_wave[kT / kWave];
     __shared__ uint32_t s_out[3];
+    // a segmented list (SelState::seg_list): where each group's entries start in the order of
+    // the groups, and the entries themselves, gathered once, if they fit
+    constexpr uint32_t kSegCache = 8192;
+    __shared__ uint32_t g_off[Src::kSegList ? kMaxGroups : 1];
+    __shared__ uint2 s_ent[Src::kSegList ? kSegCache : 1];
     const int s = blockIdx.x;
     const uint32_t t = threadIdx.x;
     if (src.skip(s)) return;
@@ -1130,6 +1154,53 @@ __global__ __launch_bounds__(1024) void k_finish(Src src, SelState st) {
     const bool one_key = overflow && bin_hi == bin_lo;
     const uint32_t gin0 = (one_key && 2 * t < ng) ? st.grp_in[(size_t)s * st.maxgroups + 2 * t] : 0u;
     const uint32_t gin1 = (one_key && 2 * t + 1 < ng) ? st.grp_in[(size_t)s * st.maxgroups + 2 * t + 1] : 0u;
+    const bool seg = Src::kSegList && st.seg_list != 0;      // uniform
+    uint32_t nseg = 0;                                        // entries of a segmented list
+    bool seg_cached = false;
+    // entry i (< nseg) of a segmented list: it belongs to the last group whose entries start at or before i
+    auto seg_fetch = [&](uint32_t i) -> uint2 {
+        uint32_t glo = 0, ghi = ng;
+        while (ghi - glo > 1) {
+            const uint32_t mid = (glo + ghi) >> 1;
+            if (g_off[mid] <= i) glo = mid; else ghi = mid;
+        }
+        uint32_t first = 0, end = 0;
+        src.group_range(s, glo, first, end);
+        const uint32_t p = first + (i - g_off[glo]);
+        return p < st.list_cap ? list[p] : make_uint2(kNoKey, 0u);      // (always inside for a list k_bucket wrote)
+    };
+    if (seg) {
+        const uint32_t c0 = 2 * t < ng ? st.grp_in[(size_t)s * st.maxgroups + 2 * t] : 0u;
+        const uint32_t c1 = 2 * t + 1 < ng ? st.grp_in[(size_t)s * st.maxgroups + 2 * t + 1] : 0u;
+        uint32_t tot;
+        const uint32_t incl = block_incl_scan(c0 + c1, s_wave, tot);
+        g_off[2 * t] = incl - c0 - c1;
+        g_off[2 * t + 1] = incl - c1;
+        __syncthreads();
+        nseg = tot;
+        seg_cached = nseg <= kSegCache;
+        if (seg_cached) {
+            for (uint32_t i = t; i < nseg; i += kT) s_ent[i] = seg_fetch(i);
+            __syncthreads();
+        }
+    }
+    // f(key, group) for every in-bin entry of the set; every thread calls f the same number of times
+    auto each_entry = [&](auto&& f) {
+        if (!seg) {
+            for_each_in_bin<kT>(src, s, dn, dg, d1, list, nlist, overflow, nphys, fl, f);
+        } else {
+            for (uint32_t i0 = 0; i0 < nseg; i0 += kT * kBatch) {
+                uint2 e[kBatch];
+#pragma unroll
+                for (int j = 0; j < kBatch; ++j) {
+                    const uint32_t i = i0 + j * kT + t;
+                    e[j] = i < nseg ? (seg_cached ? s_ent[i] : seg_fetch(i)) : make_uint2(kNoKey, 0u);
+                }
+#pragma unroll
+                for (int j = 0; j < kBatch; ++j) f(e[j].x, e[j].y);
+            }
+        }
+    };
     uint32_t T, need;
     if (one_key) {
         T = bin_hi;
@@ -1150,7 +1221,7 @@ __global__ __launch_bounds__(1024) void k_finish(Src src, SelState st) {
             h[t] = 0u;
             h[t + kT] = 0u;
             __syncthreads();
-            for_each_in_bin<kT>(src, s, dn, dg, d1, list, nlist, overflow, nphys, fl, [&](uint32_t key, uint32_t) {
+            each_entry([&](uint32_t key, uint32_t) {
                 const uint32_t rel = key - lo;
                 const bool mine = key != kNoKey && (rel >> (shift + bits)) == prefix;
                 const uint32_t b = (rel >> shift) & ((1u << bits) - 1u);
@@ -1180,7 +1251,7 @@ __global__ __launch_bounds__(1024) void k_finish(Src src, SelState st) {
         g_eq[2 * t] = 0u;
         g_eq[2 * t + 1] = 0u;
         __syncthreads();
-        for_each_in_bin<kT>(src, s, dn, dg, d1, list, nlist, overflow, nphys, fl, [&](uint32_t key, uint32_t g) {
+        each_entry([&](uint32_t key, uint32_t g) {
             g &= (uint32_t)kMaxGroups - 1;
             add_grouped(key != kNoKey && key > T, g, g_gt);
             add_grouped(key != kNoKey && key == T, g, g_eq);
