@@ -16,7 +16,8 @@
 //             number of ties to take, and the block's output offsets; then, per group:
 //             ordered compaction of the selected entries
 // For large sets (long lists) the first half of k_emit runs once per set in a kernel of
-// its own, k_finish, instead of once per block.  Where the kernel that produces a set's
+// its own, k_finish, instead of once per block; the keys inside the bin then stay with their
+// groups (SelState::seg_list) instead of going through one shared list counter.  Where the kernel that produces a set's
 // entries has counted their first digits itself (the unions of the tree; the streaming
 // pass at most densities), k_hist is not launched or has nothing to do for that set.
 #pragma once
