@@ -153,6 +153,88 @@ def _gap_ksets(n_sets, k, m, seed):
     return idx, val
 
 
+def _shared_ksets(rng, k, m, shared, kind):
+    """One pair of ascending index sets of k entries in [0, m) of which `shared` indices are common,
+    with values of one kind: "gauss"; "ties" (five magnitudes, both signs); "cancel" (opposite
+    values at the shared indices); "plateau" (every magnitude below a random quantile is raised
+    to it, so the k-th key of the merge lies among up to millions of equal keys)."""
+    n = 2 * k - shared
+    cand = np.flatnonzero(rng.random(m) < min(1.0, 1.03 * n / m + 1e-3))
+    while cand.size < n:
+        cand = np.flatnonzero(rng.random(m) < min(1.0, 1.2 * n / m + 1e-2))
+    pool = np.sort(cand[rng.permutation(cand.size)[:n]])
+    who = np.empty(n, dtype=np.int8)
+    perm = rng.permutation(n)
+    who[perm[:k - shared]] = 1
+    who[perm[k - shared:2 * (k - shared)]] = 2
+    who[perm[2 * (k - shared):]] = 3
+    ia, ib = pool[(who & 1) != 0].astype(np.uint32), pool[(who & 2) != 0].astype(np.uint32)
+
+    def values():
+        v = rng.standard_normal(k).astype(np.float32)
+        if kind == "ties":
+            levels = np.array([0.125, 0.25, 0.5, 1.0, 2.0], dtype=np.float32)
+            v = np.copysign(rng.choice(levels, k), v).astype(np.float32)
+        elif kind == "plateau":
+            c = np.float32(np.quantile(np.abs(v), rng.uniform(0.3, 0.8)))
+            v = np.where(np.abs(v) < c, np.copysign(c, v), v).astype(np.float32)
+        return v
+    va, vb = values(), values()
+    if kind == "cancel":
+        vb[np.isin(ib, ia)] = -va[np.isin(ia, ib)]
+    return ia, va, ib, vb
+
+
+@pytest.mark.parametrize("k,spread,batch,kind,shared", [
+    (530_001, 1.3, 3, "plateau", 0.1), (1_048_577, 2.0, 2, "ties", 0.5),
+    (1_700_003, 3.0, 2, "cancel", 0.9), (2_500_000, 1.5, 1, "gauss", 1.0),
+    # either side of the size from which a merge goes through a sampled threshold
+    (4_194_304, 1.2, 1, "plateau", 0.0), (4_194_305, 1.2, 2, "plateau", 0.5),
+    (5_000_001, 2.5, 1, "ties", 0.5), (4_700_000, 4.0, 2, "cancel", 0.1)])
+def test_merge_very_large_sets(k, spread, batch, kind, shared):
+    """Merged sets of more than 2^20 slots: their select keeps the keys of the k-th key's bin
+    with their groups and finishes once per set; with more than 2^22 entries per operand the
+    union is filtered first.  Ties and plateaus fill that bin far beyond what the finish holds
+    in LDS."""
+    import torch
+    from paper_1901_04359_amd import binding as B
+    m = int(2 * k * spread)
+    rng = np.random.default_rng(k + batch)
+    sets = [_shared_ksets(rng, k, m, int(round(shared * k)), kind) for _ in range(batch)]
+    a_idx, a_val, b_idx, b_val = (np.stack([s[j] for s in sets]) for j in range(4))
+    assert B.gtopk_debug_plan(m, k, 2)["merge_filtered"] == (1 if k > 1 << 22 else 0)
+    say(f"merge, very large sets: k={k} m={m} batch={batch} kind={kind} shared={shared}")
+    ws = B.alloc_merge_workspace(k, batch)
+    ws.fill_(0x5A)
+    out_idx = torch.zeros((batch, k), dtype=torch.int32, device="cuda")
+    out_val = torch.zeros((batch, k), dtype=torch.float32, device="cuda")
+    B.gtopk_merge(to_dev(a_idx), to_dev(a_val), to_dev(b_idx), to_dev(b_val), k, batch, k, out_idx, out_val, k, ws)
+    gi, gv = idx_np(out_idx), val_np(out_val)
+    for b in range(batch):
+        oi, ov = orc.merge(a_idx[b], a_val[b], b_idx[b], b_val[b], k)
+        assert np.array_equal(gi[b], oi), f"b={b} idx: {first_diff(gi[b], oi)}"
+        assert bits_equal(gv[b], ov), f"b={b} val: {first_diff(gv[b], ov)}"
+
+
+@pytest.mark.parametrize("P,k,kind,shared", [(8, 700_001, "plateau", 0.3), (4, 1_300_000, "ties", 0.9)])
+def test_tree_very_large_sets(P, k, kind, shared):
+    """Every round of these trees selects from merged sets of more than 2^20 slots."""
+    m = 5 * k
+    rng = np.random.default_rng(P + k)
+    idx = np.empty((P, k), dtype=np.uint32)
+    val = np.empty((P, k), dtype=np.float32)
+    for p in range(0, P, 2):
+        idx[p], val[p], idx[p + 1], val[p + 1] = _shared_ksets(rng, k, m, int(round(shared * k)), kind)
+    dev = Device(P, k, k)
+    dev.loc_idx.copy_(to_dev(idx))
+    dev.loc_val.copy_(to_dev(val))
+    say(f"tree of very large sets P={P} k={k} m={m} kind={kind}")
+    gi, gv = dev.tree()
+    oi, ov = orc.tree(list(idx), list(val), k)
+    assert np.array_equal(gi, oi), first_diff(gi, oi)
+    assert bits_equal(gv, ov), first_diff(gv, ov)
+
+
 def test_merge_speculative_threshold_hits_and_misses():
     """Merges of more than 2^22 entries keep only the slots of the union that reach a threshold
     taken from a sample.  Pair 0 is ordinary; pair 1 has its large values exactly where the
