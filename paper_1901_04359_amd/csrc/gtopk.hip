@@ -517,6 +517,24 @@ inline uint32_t min_key_blocks(uint32_t k) {
     return b < 1 ? 1 : (b > 64 ? 64 : b);
 }
 
+// Lanes per cut point by the number of cut points of the launch (see k_union_cuts).  Measured
+// for sets of 1.9 M and 6.4 M entries, in us for (25 k, 12.5 k, 6.2 k, 3.1 k, 1.6 k) and
+// (7.3 k, 3.6 k, 1.8 k, 0.9 k, 0.45 k) cut points:
+//    2 lanes: 35 31 24 21 14 | 26 22 18 13 16      4 lanes: 41 22 16 13  9 | 17 13 11  8  7
+//   16 lanes: 79 40 20 10  7 | 21 10  8  6  5     64 lanes: 131 73 36 18 9 | 41 19 11  6  5
+inline void launch_union_cuts(const uint32_t* a_idx, const uint32_t* b_idx, uint32_t k, int64_t in_stride,
+                              uint32_t tile, uint32_t ntiles, uint32_t batch, uint32_t* cuts, hipStream_t st) {
+    const uint64_t total = (uint64_t)(ntiles + 1) * batch;
+    const uint32_t L = total > 20000 ? 2u : (total > 5000 ? 4u : 16u);
+    const dim3 grid(ceil_div((ntiles + 1) * L, kBlock), batch);
+    if (L == 2)
+        hipLaunchKernelGGL(k_union_cuts<2>, grid, dim3(kBlock), 0, st, a_idx, b_idx, k, in_stride, tile, ntiles, cuts);
+    else if (L == 4)
+        hipLaunchKernelGGL(k_union_cuts<4>, grid, dim3(kBlock), 0, st, a_idx, b_idx, k, in_stride, tile, ntiles, cuts);
+    else
+        hipLaunchKernelGGL(k_union_cuts<16>, grid, dim3(kBlock), 0, st, a_idx, b_idx, k, in_stride, tile, ntiles, cuts);
+}
+
 // one batch of merges: union + exact select + ordered emit.  `round` picks which of the
 // two select states is used (it must be clear on entry); the other one is cleared on the
 // side for the next round.
@@ -553,8 +571,7 @@ void do_merge_batch(const uint32_t* a_idx, const float* a_val, const uint32_t* b
                            w.m_val, w.m_stride, (const uint32_t*)nullptr, zp, zw, src, ss);
     else if (!w.f_samp_hist) {
         const uint32_t tile = kUnionHistBlock * kUnionPathEpt, ntiles = ceil_div(2 * k, tile);
-        hipLaunchKernelGGL(k_union_cuts, dim3(ceil_div(ntiles + 1, kBlock), batch), dim3(kBlock), 0, st,
-                           a_idx, b_idx, k, in_stride, tile, ntiles, w.cuts);
+        launch_union_cuts(a_idx, b_idx, k, in_stride, tile, ntiles, batch, w.cuts, st);
         hipLaunchKernelGGL((k_union_path<kUnionPathEpt, true, kUnionHistBlock, true>), dim3(ntiles, batch),
                            dim3(kUnionHistBlock), 0, st, a_idx, a_val, b_idx, b_val, k, in_stride, w.m_idx,
                            w.m_val, w.m_stride, (const uint32_t*)w.cuts, zp, zw, src, ss);
@@ -571,8 +588,7 @@ void do_merge_batch(const uint32_t* a_idx, const float* a_val, const uint32_t* b
                            b_idx, b_val, k, in_stride, mp.tile_stride, mp.n_tiles, w.f_samp_hist);
         hipLaunchKernelGGL(k_sample_pick, dim3(batch), dim3(kSampleBlock), 0, st,
                            (const uint32_t*)w.f_samp_hist, mp.target, w.f_tspec, (const uint4*)nullptr);
-        hipLaunchKernelGGL(k_union_cuts, dim3(ceil_div(ntiles + 1, kBlock), batch), dim3(kBlock), 0, st,
-                           a_idx, b_idx, k, in_stride, tile, ntiles, w.cuts);
+        launch_union_cuts(a_idx, b_idx, k, in_stride, tile, ntiles, batch, w.cuts, st);
         hipLaunchKernelGGL((k_union_path<kUnionPathEpt, true, kUnionHistBlock, true, true>), dim3(ntiles, batch),
                            dim3(kUnionHistBlock), 0, st, a_idx, a_val, b_idx, b_val, k, in_stride, w.m_idx,
                            w.m_val, w.m_stride, (const uint32_t*)w.cuts, zp, zw, src, ss,

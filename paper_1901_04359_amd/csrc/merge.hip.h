@@ -208,6 +208,36 @@ __device__ inline uint32_t wave_first_false(uint32_t lo, uint32_t hi, Pred pred)
     return lo;
 }
 
+// The same search by groups of L consecutive lanes (L a power of two), every group with a
+// range and a predicate of its own (pred(x) may depend on the lane's group; the lanes of a
+// group pass the same lo and hi, a group without work passes lo == hi): log_L rounds of one
+// load per lane.  Fewer lanes per search mean more rounds but fewer loads per search, which
+// is what counts once thousands of searches run side by side.  All 64 lanes must call it.
+template <int L, class Pred>
+__device__ inline uint32_t group_first_false(uint32_t lo, uint32_t hi, Pred pred) {
+    static_assert(L >= 2 && L <= kWave && (L & (L - 1)) == 0, "a power of two, at most a wave");
+    const uint32_t lane = lane_id(), gl = lane % L;
+    const uint64_t gmask = (L == kWave ? ~0ull : ((1ull << (L % 64)) - 1ull)) << (lane - gl);
+    while (__any(lo < hi)) {
+        const bool busy = lo < hi;
+        const uint32_t len = hi - lo;
+        const uint32_t step = (len + L - 1) / L;
+        const uint32_t start = lo + gl * step;
+        const bool active = busy && start < hi;
+        const uint32_t last = (start + step < hi ? start + step : hi) - 1;
+        const bool t = active && pred(last);
+        const uint32_t c = (uint32_t)__popcll(__ballot(t) & gmask);
+        if (busy) {
+            const uint32_t cstart = lo + c * step;
+            uint32_t nhi = hi;
+            if (c < (uint32_t)L && cstart < hi) nhi = (cstart + step < hi ? cstart + step : hi) - 1;
+            lo = cstart < hi ? cstart : hi;
+            hi = nhi;
+        }
+    }
+    return lo;
+}
+
 // The same union, cut by OUTPUT position ("merge path"): for large sets.
 // The 2k slots of a pair are the stable merge of A and B by index, A first among equals;
 // the slot of an A entry that has an equal B entry right after it carries the sum, and
@@ -221,25 +251,27 @@ __device__ inline uint32_t wave_first_false(uint32_t lo, uint32_t hi, Pred pred)
 // of EPT, 16-byte aligned), so every thread stores whole vectors; slots past 2k in the
 // row's padding become tombstones.  HIST: as in k_union, with blocks as large as LDS allows.
 // cuts[s][c] = number of A entries among the first c * tile slots of pair s (c = 0 .. ntiles;
-// the last one is clamped to 2k slots): what k_union_path's blocks need, one binary
-// search along a diagonal each, all side by side instead of one after the other in
-// front of every block's work.
+// the last one is clamped to 2k slots): what k_union_path's blocks need, one search
+// along a diagonal each, all side by side instead of one after the other in front of
+// every block's work.
+template <int L>
 __global__ __launch_bounds__(kBlock) void k_union_cuts(
         const uint32_t* __restrict__ a_idx, const uint32_t* __restrict__ b_idx, uint32_t k,
         int64_t in_stride, uint32_t tile, uint32_t ntiles, uint32_t* __restrict__ cuts) {
-    const uint32_t c = blockIdx.x * kBlock + threadIdx.x;
+    // L lanes per cut point: an L-ary search along the diagonal.  A binary search (L = 2)
+    // waits for 23 dependent pairs of loads for sets of millions of entries, a 16-ary one
+    // for 6 but issues four times as many; the host picks L by the number of cut points.
+    const uint32_t c = (blockIdx.x * kBlock + threadIdx.x) / L;
     const int s = blockIdx.y;
-    if (c > ntiles) return;
+    const bool work = c <= ntiles;
     const uint32_t* ai = a_idx + (int64_t)s * in_stride;
     const uint32_t* bi = b_idx + (int64_t)s * in_stride;
     const uint64_t pp = (uint64_t)c * tile;
     const uint32_t p = pp < 2ull * k ? (uint32_t)pp : 2 * k;
-    uint32_t lo = p > k ? p - k : 0u, hi = p < k ? p : k;
-    while (lo < hi) {                 // A[x] is among the first p slots iff A[x] <= B[p-1-x]
-        const uint32_t mid = (lo + hi) >> 1;
-        if (ai[mid] <= bi[p - 1 - mid]) lo = mid + 1; else hi = mid;
-    }
-    cuts[(size_t)s * (ntiles + 1) + c] = lo;
+    const uint32_t lo = work ? (p > k ? p - k : 0u) : 0u, hi = work ? (p < k ? p : k) : 0u;
+    // A[x] is among the first p slots iff A[x] <= B[p-1-x]
+    const uint32_t x = group_first_false<L>(lo, hi, [&](uint32_t x) { return ai[x] <= bi[p - 1 - x]; });
+    if (work && threadIdx.x % L == 0) cuts[(size_t)s * (ntiles + 1) + c] = x;
 }
 
 // FILTER (with HIST): of its tile the block keeps only the slots whose key reaches
@@ -466,21 +498,40 @@ __global__ __launch_bounds__(kSampleBlock) void k_merge_sample(
     const float* av = a_val + (int64_t)s * in_stride;
     const uint32_t* bi = b_idx + (int64_t)s * in_stride;
     const float* bv = b_val + (int64_t)s * in_stride;
+    static_assert(kSampleTile == kWave, "a tile is a wave's: the searches below are wave-cooperative");
     const uint32_t sub = threadIdx.x / kSampleTile, el = threadIdx.x % kSampleTile;
     const uint32_t tiles_per_round = (kSampleBlock / kSampleTile) * gridDim.x;
     for (uint64_t t = (uint64_t)blockIdx.x * (kSampleBlock / kSampleTile) + sub; t < n_tiles; t += tiles_per_round) {
-        const uint64_t q = t * tile_stride + el;
-        if (q >= k) continue;
+        const uint64_t q0 = t * tile_stride;                       // wave-uniform
+        if (q0 >= k) continue;
+        const uint32_t cnt = k - q0 < (uint64_t)kSampleTile ? (uint32_t)(k - q0) : (uint32_t)kSampleTile;
+        const bool act = el < cnt;
+        const uint64_t q = q0 + (act ? el : cnt - 1);              // idle lanes repeat the tile's last entry
         const uint32_t ia = ai[q], ib = bi[q];
         const float va = av[q], vb = bv[q];
-        uint32_t lo = 0, hi = k;                      // first B entry with index >= ia
-        while (lo < hi) { const uint32_t mid = (lo + hi) >> 1; if (bi[mid] < ia) lo = mid + 1; else hi = mid; }
+        // The tile's entries ascend, so the first B entry >= ia lies between those of the tile's
+        // first and last index, and likewise for ib in A: sixteen lanes each find one of these
+        // four bounds (6 rounds for millions of entries), then every lane finishes inside its
+        // short ranges, both searches in step - a dozen dependent rounds instead of 46.
+        const uint32_t ia_first = __shfl(ia, 0), ia_last = __shfl(ia, (int)cnt - 1);
+        const uint32_t ib_first = __shfl(ib, 0), ib_last = __shfl(ib, (int)cnt - 1);
+        const uint32_t j = el / 16;                                // which of the four bounds this lane helps with
+        const uint32_t* arr = j < 2 ? bi : ai;
+        const uint32_t want = j == 0 ? ia_first : j == 1 ? ia_last : j == 2 ? ib_first : ib_last;
+        const uint32_t bound = group_first_false<16>(0u, k, [&](uint32_t x) { return arr[x] < want; });
+        const uint32_t lo[4] = {__shfl(bound, 0), __shfl(bound, 16), __shfl(bound, 32), __shfl(bound, 48)};
+        uint32_t lb = lo[0], hb = lo[1] > lo[0] ? lo[1] : lo[0];   // first B entry with index >= ia: in [lb, hb]
+        uint32_t la = lo[2], ha = lo[3] > lo[2] ? lo[3] : lo[2];   // first A entry with index >= ib: in [la, ha]
+        while (lb < hb || la < ha) {
+            const uint32_t mb = (lb + hb) >> 1, ma = (la + ha) >> 1;
+            const uint32_t xb = bi[mb < k ? mb : k - 1], xa = ai[ma < k ? ma : k - 1];
+            if (lb < hb) { if (xb < ia) lb = mb + 1; else hb = mb; }
+            if (la < ha) { if (xa < ib) la = ma + 1; else ha = ma; }
+        }
         float v = va;
-        if (lo < k && bi[lo] == ia) v = v + bv[lo];
-        atomicAdd(&h[(__float_as_uint(v) & kAbs) >> kSampleShift], 1u);
-        lo = 0; hi = k;                               // first A entry with index >= ib
-        while (lo < hi) { const uint32_t mid = (lo + hi) >> 1; if (ai[mid] < ib) lo = mid + 1; else hi = mid; }
-        if (!(lo < k && ai[lo] == ib)) atomicAdd(&h[(__float_as_uint(vb) & kAbs) >> kSampleShift], 1u);
+        if (lb < k && bi[lb] == ia) v = v + bv[lb];
+        if (act) atomicAdd(&h[(__float_as_uint(v) & kAbs) >> kSampleShift], 1u);
+        if (act && !(la < k && ai[la] == ib)) atomicAdd(&h[(__float_as_uint(vb) & kAbs) >> kSampleShift], 1u);
     }
     __syncthreads();
     uint32_t* out = samp_hist + (size_t)s * kSampleBins;
