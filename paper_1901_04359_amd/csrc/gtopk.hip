@@ -405,7 +405,8 @@ SamplePlan plan_sample(int64_t m, uint32_t k, double sample_mean, double min_til
 // per block and non-empty bin, a global atomic in the pass.  Measured against the
 // histogram kernel it saves: at rho = 0.001 (45 candidates per 32768-element block) the
 // pass does not change and the select gains 6-8 us; at rho = 0.01 (460 per block) the pass
-// loses 55 us and the select gains 13 us; at rho = 0.25 (11,500 per block) the pass loses
+// loses 55 us and the select gains 13 us; at rho = 0.0725 (3,300 per block) the pass loses
+// 120 us and the select gains 85 us; at rho = 0.25 (11,500 per block) the pass loses
 // 80 us and the select gains 230 us.  So at both ends, not in between.
 bool pass_histograms(int64_t m, uint32_t k) {
     const double per_block = 1.4 * (double)k * (double)kChunk / (double)m;
