@@ -110,6 +110,21 @@ __device__ __forceinline__ void add_grouped(bool pred, uint32_t g, uint32_t* arr
     }
 }
 
+// The same for an array in LDS whose lanes mostly differ in g (entries listed group by
+// group, a few per group): one combined add if all lanes agree, else an LDS atomic per lane -
+// the loop above would take one round per distinct group.
+__device__ __forceinline__ void add_grouped_lds(bool pred, uint32_t g, uint32_t* arr) {
+    const uint64_t todo = __ballot(pred);
+    if (!todo) return;
+    const uint32_t leader = (uint32_t)__builtin_ctzll(todo);
+    const uint32_t gl = __shfl(g, leader);
+    if (__ballot(pred && g == gl) == todo) {
+        if (lane_id() == leader) atomicAdd(&arr[gl], (uint32_t)__popcll(todo));
+    } else if (pred) {
+        atomicAdd(&arr[g], 1u);
+    }
+}
+
 // ---- first digit of a key ----------------------------------------------------------
 // The 31-bit key space is cut into 4096 consecutive intervals ("bins").
 //   coarse (base = 0, shift = 19): bin = the key's top 12 bits (exponent + 4 mantissa bits).

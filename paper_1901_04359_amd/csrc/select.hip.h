@@ -1181,7 +1181,14 @@ __global__ __launch_bounds__(1024) void k_finish(Src src, SelState st) {
         nseg = tot;
         seg_cached = nseg <= kSegCache;
         if (seg_cached) {
-            for (uint32_t i = t; i < nseg; i += kT) s_ent[i] = seg_fetch(i);
+            // (all loads of a thread in flight together: each waits for a search in LDS and a load)
+            uint2 e[kSegCache / kT];
+#pragma unroll
+            for (uint32_t j = 0; j < kSegCache / kT; ++j)
+                if (j * kT + t < nseg) e[j] = seg_fetch(j * kT + t);
+#pragma unroll
+            for (uint32_t j = 0; j < kSegCache / kT; ++j)
+                if (j * kT + t < nseg) s_ent[j * kT + t] = e[j];
             __syncthreads();
         }
     }
@@ -1254,8 +1261,8 @@ __global__ __launch_bounds__(1024) void k_finish(Src src, SelState st) {
         __syncthreads();
         each_entry([&](uint32_t key, uint32_t g) {
             g &= (uint32_t)kMaxGroups - 1;
-            add_grouped(key != kNoKey && key > T, g, g_gt);
-            add_grouped(key != kNoKey && key == T, g, g_eq);
+            add_grouped_lds(key != kNoKey && key > T, g, g_gt);
+            add_grouped_lds(key != kNoKey && key == T, g, g_eq);
         });
         __syncthreads();
     }
