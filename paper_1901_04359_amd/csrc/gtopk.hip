@@ -112,7 +112,8 @@ constexpr uint32_t kMergeMinSlots = 512;        // merged sets: one round of a b
 
 // Groups per set when `sets` sets are selected from side by side.  Every block of k_bucket
 // and k_emit pays a fixed price (it reads the set's 4096-bin histogram, or the list of
-// in-bin keys), so a batch gets about kTargetBlocks blocks in total and no more (swept: 512 .. 4096).
+// in-bin keys), so a batch gets about kTargetBlocks blocks in total and no more (swept: 512 .. 4096;
+// a tree of 32 sets of 255,570 entries: 268 / 291 / 307 us at 1024 / 2048 / 4096).
 constexpr uint32_t kTargetBlocks = 1024;
 constexpr uint32_t kLocalTargetBlocks = 8192;   // the same for the local selection's P sets
 uint32_t groups_for(uint32_t sets) {
